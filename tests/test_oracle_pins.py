@@ -1,0 +1,462 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix.
+
+None of these compares the oracle with itself or with the HIP path: every
+expected value comes from a brute-force loop, a closed form, an invariant, a
+special case that reduces to textbook attention, a hand-worked example or a
+library routine.  Citations: section 3.2 (steps 1-5), Algorithm 1, the
+section 3.4 update equation, section 3.5 (order-free accumulation), section
+4.3 (memory constant).
+"""
+import json
+import math
+import os
+
+import numpy as np
+import pytest
+
+import bct_synth as syn
+from oracle import bct_ref
+from oracle.bct_ref import RefCache
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def rng_normal(seed, tid, step, shape, dtype):
+    return syn.pack(syn.normal(seed, tid, step, shape), dtype)
+
+
+def f64(a, dtype):
+    return syn.unpack(a, dtype)
+
+
+def softmax64(x):
+    x = np.asarray(x, dtype=np.float64)
+    e = np.exp(x - x.max())
+    return e / e.sum()
+
+
+def brute_attention(q, K, V, scale):
+    """softmax(scale * q K^T) V with explicit loops, two passes, double."""
+    M, d = K.shape
+    s = [scale * sum(float(q[j]) * float(K[m, j]) for j in range(d)) for m in range(M)]
+    mx = max(s)
+    e = [math.exp(v - mx) for v in s]
+    z = sum(e)
+    out = [0.0] * V.shape[1]
+    for m in range(M):
+        for j in range(V.shape[1]):
+            out[j] += (e[m] / z) * float(V[m, j])
+    return np.array(out)
+
+
+def make_cache(M, B, Hq, Hkv, d, dtype, rs=None, ws=None, seed=11, flags=0, mv0=False):
+    rs = 1.0 / math.sqrt(d) if rs is None else rs
+    ws = 1.0 / math.sqrt(d) if ws is None else ws
+    c = RefCache(M, B, Hq, Hkv, d, dtype, rs, ws, flags)
+    mk = rng_normal(seed, syn.TID_MK, 0, c.keys_shape, dtype)
+    c.set_keys(mk)
+    mv = None
+    if mv0:
+        mv = rng_normal(seed, syn.TID_MV0, 0, c.values_shape, dtype)
+        c.set_values(mv)
+    return c, mk, mv
+
+
+def step_inputs(c, seed, step):
+    q = rng_normal(seed, syn.TID_Q, step, (c.B, c.Hq, c.d), c.dtype)
+    wq = rng_normal(seed, syn.TID_WQ, step, (c.B, c.Hkv, c.d), c.dtype)
+    wv = rng_normal(seed, syn.TID_WV, step, (c.B, c.Hkv, c.d), c.dtype)
+    return q, wq, wv
+
+
+# ------------------------------------------------------------------ P1 brute-force read
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("M,d,Hq,Hkv", [(8, 4, 4, 2), (5, 3, 3, 3), (7, 2, 6, 1)])
+def test_p1_read_is_bruteforce_attention(dtype, M, d, Hq, Hkv):
+    B, scale = 2, 0.7
+    c, mk, mv = make_cache(M, B, Hq, Hkv, d, dtype, rs=scale, mv0=True)
+    q = rng_normal(3, syn.TID_Q, 0, (B, Hq, d), dtype)
+    out = c.decode_step(q, None, None)
+    G = Hq // Hkv
+    K, V, Q = f64(mk, dtype), f64(mv, dtype), f64(q, dtype)
+    got = f64(out, dtype)
+    for b in range(B):
+        for hq in range(Hq):
+            h = hq // G
+            ref = brute_attention(Q[b, hq], K[h], V[b, h], scale)
+            tol = 1e-6 if dtype == "f32" else 2 ** -8
+            assert np.max(np.abs(got[b, hq] - ref)) <= tol * max(1.0, np.max(np.abs(ref)))
+    # a read-only step leaves the state untouched
+    assert np.array_equal(c.values(), mv)
+    assert c.steps == 1
+
+
+# ------------------------------------------------------------------ P2 capacity invariant
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_p2_capacity_and_keys_constant(dtype):
+    M, B, Hq, Hkv, d = 8, 2, 4, 2, 4
+    c, mk, _ = make_cache(M, B, Hq, Hkv, d, dtype)
+    sz = syn.elem_size(dtype)
+    expect = (Hkv * M * d + B * Hkv * M * d) * sz
+    assert c.cache_bytes() == expect
+    for t in range(3 * M + 1):  # far past the capacity: nothing changes at t = M
+        q, wq, wv = step_inputs(c, 5, t)
+        out = c.decode_step(q, wq, wv)
+        assert out.shape == (B, Hq, d)
+        assert c.cache_bytes() == expect
+        k2, v2, st = c.export()
+        assert np.array_equal(k2, mk)          # MK is never written (Algorithm 1 input)
+        assert v2.shape == (B, Hkv, M, d) and st == t + 1
+
+
+# ------------------------------------------------------------------ P3 mass conservation
+
+def test_p3_mass_conservation():
+    M, B, Hq, Hkv, d = 16, 2, 2, 2, 8
+    c, mk, mv0 = make_cache(M, B, Hq, Hkv, d, "f32", ws=1.0, mv0=True)
+    tot = np.zeros((B, Hkv, d))
+    N = 40
+    for t in range(N):
+        _, wq, wv = step_inputs(c, 7, t)
+        c.decode_step(None, wq, wv)
+        tot += wv.astype(np.float64)
+    got = c.values().astype(np.float64).sum(axis=2)
+    ref = mv0.astype(np.float64).sum(axis=2) + tot
+    assert np.max(np.abs(got - ref)) <= 1e-5 * math.sqrt(N) * max(1.0, np.max(np.abs(ref)))
+
+
+def test_p3b_probe_weights_are_a_softmax():
+    M, d = 9, 5
+    c, mk, _ = make_cache(M, 1, 1, 1, d, "f32")
+    v = rng_normal(1, syn.TID_WQ, 0, (d,), "f32")
+    w = c.probe_weights(0, 0, v, 0.3)
+    ref = softmax64(0.3 * (mk[0].astype(np.float64) @ v.astype(np.float64)))
+    assert abs(w.sum() - 1.0) < 1e-14 and np.all(w > 0)
+    assert np.max(np.abs(w - ref)) < 1e-15
+    # no overflow for huge scores (max-subtracted)
+    big = (v.astype(np.float64) * 1e4).astype(np.float32)
+    wb = c.probe_weights(0, 0, big, 1.0)
+    assert np.all(np.isfinite(wb)) and abs(wb.sum() - 1.0) < 1e-12
+
+
+# ------------------------------------------------------------------ P4 closed form, order freedom
+
+@pytest.mark.parametrize("ws", [1.0, 0.25])
+def test_p4_closed_form_and_order_freedom(ws):
+    M, B, Hq, Hkv, d, N = 12, 2, 2, 2, 6, 20
+    c, mk, mv0 = make_cache(M, B, Hq, Hkv, d, "f32", ws=ws, mv0=True)
+    WQ = np.stack([step_inputs(c, 9, t)[1] for t in range(N)])  # [N][B][Hkv][d]
+    WV = np.stack([step_inputs(c, 9, t)[2] for t in range(N)])
+    for t in range(N):
+        c.decode_step(None, WQ[t], WV[t])
+    got = c.values().astype(np.float64)
+    K = mk.astype(np.float64)
+    for b in range(B):
+        for h in range(Hkv):
+            WW = np.stack([softmax64(ws * (K[h] @ WQ[t, b, h].astype(np.float64))) for t in range(N)])  # [N][M]
+            ref = mv0[b, h].astype(np.float64) + WW.T @ WV[:, b, h].astype(np.float64)
+            assert np.max(np.abs(got[b, h] - ref)) <= 2e-6 * max(1.0, np.max(np.abs(ref)))
+    # token order does not matter (section 3.5)
+    c2, _, _ = make_cache(M, B, Hq, Hkv, d, "f32", ws=ws, mv0=True)
+    perm = np.random.default_rng(0).permutation(N)
+    for t in perm:
+        c2.decode_step(None, WQ[t], WV[t])
+    assert np.max(np.abs(c2.values().astype(np.float64) - got)) <= 2e-6 * np.max(np.abs(got))
+
+
+# ------------------------------------------------------------------ P5 zero keys
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_p5_zero_keys_give_uniform_weights(dtype):
+    M, B, H, d = 8, 1, 2, 4   # 1/M is a power of two -> exact in both dtypes
+    c = RefCache(M, B, H, H, d, dtype, 1.0, 1.0)
+    c.set_keys(np.zeros(c.keys_shape, dtype=c._np))
+    # wv values on a coarse grid so that every partial sum is exact
+    acc = np.zeros((B, H, d))
+    for t in range(6):
+        q, wq, _ = step_inputs(c, 2, t)
+        wv64 = np.round(syn.normal(2, syn.TID_WV, t, (B, H, d)) * 4) * 2.0  # multiples of 2
+        wv = syn.pack(wv64, dtype)
+        out = c.decode_step(q, wq, wv)
+        acc += wv64
+        mv = f64(c.values(), dtype)
+        for m in range(M):
+            assert np.array_equal(mv[:, :, m, :], acc / M)
+        assert np.array_equal(f64(out, dtype), acc / M)  # mean over identical rows
+
+
+# ------------------------------------------------------------------ P6 hard addressing = appending
+
+def _hard_queries(mk64, gap_target=250.0):
+    """wq_t = c_t * MK[t] with every other score more than 200 below the max."""
+    M = mk64.shape[0]
+    qs = []
+    for t in range(M):
+        s = mk64 @ mk64[t]
+        gap = s[t] - np.max(np.delete(s, t))
+        assert gap > 0.5
+        qs.append(mk64[t] * (gap_target / gap))
+    return np.stack(qs)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_p6_hard_addressing_is_plain_appending(dtype):
+    M, d, B, Hq, Hkv = 8, 16, 1, 2, 1
+    rs = 0.4
+    c, mk, _ = make_cache(M, B, Hq, Hkv, d, dtype, rs=rs, ws=1.0, seed=21)
+    K = f64(mk, dtype)[0]
+    WQ = syn.pack(_hard_queries(K), dtype)          # [M][d]
+    V_written = np.zeros((M, d))
+    prev = c.values().copy()
+    for t in range(M):
+        # the rounded query still separates the scores by > 200
+        s = K @ f64(WQ[t], dtype)
+        assert s[t] - np.max(np.delete(s, t)) > 200.0
+        q, _, wv = step_inputs(c, 13, t)
+        out = c.decode_step(q, WQ[t].reshape(1, 1, d), wv)
+        mv = c.values()
+        # slot t now holds wv_t bit for bit; every other slot is untouched
+        assert np.array_equal(mv[0, 0, t], wv[0, 0])
+        others = [m for m in range(M) if m != t]
+        assert np.array_equal(mv[0, 0, others], prev[0, 0, others])
+        prev = mv.copy()
+        V_written[t] = f64(wv[0, 0], dtype)
+        # read = full attention over keys MK and the (zero-padded) written values
+        for hq in range(Hq):
+            ref = brute_attention(f64(q[0, hq], dtype), K, V_written, rs)
+            tol = 1e-6 if dtype == "f32" else 2 ** -8
+            assert np.max(np.abs(f64(out[0, hq], dtype) - ref)) <= tol * max(1.0, np.max(np.abs(ref)))
+
+
+# ------------------------------------------------------------------ P7 single slot
+
+def test_p7_single_slot_is_a_running_sum():
+    B, H, d = 2, 2, 4
+    c, _, mv0 = make_cache(1, B, H, H, d, "f32", mv0=True)
+    acc = mv0[:, :, 0, :].astype(np.float64)
+    for t in range(5):
+        q, wq, wv = step_inputs(c, 3, t)
+        out = c.decode_step(q, wq, wv)
+        acc = (acc.astype(np.float32) + wv).astype(np.float64)  # one float add per step
+        assert np.array_equal(c.values()[:, :, 0, :].astype(np.float64), acc)
+        assert np.array_equal(out.astype(np.float64), acc)
+
+
+# ------------------------------------------------------------------ P8 slot permutation
+
+def test_p8_slot_permutation_equivariance():
+    M, B, Hq, Hkv, d = 10, 1, 2, 1, 4
+    c1, mk, mv0 = make_cache(M, B, Hq, Hkv, d, "f32", mv0=True)
+    perm = np.random.default_rng(1).permutation(M)
+    c2 = RefCache(M, B, Hq, Hkv, d, "f32", 1.0 / math.sqrt(d), 1.0 / math.sqrt(d))
+    c2.set_keys(np.ascontiguousarray(mk[:, perm]))
+    c2.set_values(np.ascontiguousarray(mv0[:, :, perm]))
+    for t in range(12):
+        q, wq, wv = step_inputs(c1, 4, t)
+        o1 = c1.decode_step(q, wq, wv)
+        o2 = c2.decode_step(q, wq, wv)
+        assert np.max(np.abs(o1.astype(np.float64) - o2)) <= 1e-6 * np.max(np.abs(o1))
+    v1, v2 = c1.values(), c2.values()
+    assert np.max(np.abs(v1[:, :, perm].astype(np.float64) - v2)) <= 1e-6 * np.max(np.abs(v1))
+
+
+# ------------------------------------------------------------------ P9 linearity in wv
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_p9_doubling_wv_doubles_the_state_exactly(dtype):
+    M, B, H, d = 8, 1, 2, 8
+    c1, mk, _ = make_cache(M, B, H, H, d, dtype)
+    c2, _, _ = make_cache(M, B, H, H, d, dtype)
+    for t in range(10):
+        _, wq, wv = step_inputs(c1, 6, t)
+        wv2 = syn.pack(f64(wv, dtype) * 2.0, dtype)
+        c1.decode_step(None, wq, wv)
+        c2.decode_step(None, wq, wv2)
+    assert np.array_equal(f64(c2.values(), dtype), 2.0 * f64(c1.values(), dtype))
+
+
+# ------------------------------------------------------------------ P10 independence, GQA
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_p10_units_are_independent(dtype):
+    M, B, Hq, Hkv, d = 8, 3, 4, 2, 4
+    c1, _, _ = make_cache(M, B, Hq, Hkv, d, dtype, mv0=True)
+    c2, _, _ = make_cache(M, B, Hq, Hkv, d, dtype, mv0=True)
+    bb, hh = 1, 1
+    G = Hq // Hkv
+    for t in range(5):
+        q, wq, wv = step_inputs(c1, 8, t)
+        q2, wq2, wv2 = q.copy(), wq.copy(), wv.copy()
+        alt = step_inputs(c1, 99, t)
+        q2[bb, hh * G:(hh + 1) * G] = alt[0][bb, hh * G:(hh + 1) * G]
+        wq2[bb, hh] = alt[1][bb, hh]
+        wv2[bb, hh] = alt[2][bb, hh]
+        o1 = c1.decode_step(q, wq, wv)
+        o2 = c2.decode_step(q2, wq2, wv2)
+        mask = np.ones((B, Hq), dtype=bool)
+        mask[bb, hh * G:(hh + 1) * G] = False
+        assert np.array_equal(o1[mask], o2[mask])
+        assert not np.array_equal(o1[~mask], o2[~mask])
+    v1, v2 = c1.values(), c2.values()
+    um = np.ones((B, Hkv), dtype=bool)
+    um[bb, hh] = False
+    assert np.array_equal(v1[um], v2[um]) and not np.array_equal(v1[~um], v2[~um])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_p10b_gqa_equals_duplicated_kv_heads(dtype):
+    M, B, Hq, Hkv, d = 8, 2, 6, 2, 4
+    G = Hq // Hkv
+    cg, mk, mv0 = make_cache(M, B, Hq, Hkv, d, dtype, mv0=True)
+    cm = RefCache(M, B, Hq, Hq, d, dtype, 1.0 / math.sqrt(d), 1.0 / math.sqrt(d))
+    cm.set_keys(np.ascontiguousarray(np.repeat(mk, G, axis=0)))
+    cm.set_values(np.ascontiguousarray(np.repeat(mv0, G, axis=1)))
+    for t in range(4):
+        q, wq, wv = step_inputs(cg, 12, t)
+        og = cg.decode_step(q, wq, wv)
+        om = cm.decode_step(q, np.ascontiguousarray(np.repeat(wq, G, axis=1)),
+                            np.ascontiguousarray(np.repeat(wv, G, axis=1)))
+        assert np.array_equal(og, om)  # query head hq reads KV head hq // G
+
+
+def test_p10c_per_sequence_keys():
+    M, B, H, d = 8, 2, 2, 4
+    c, mk, _ = make_cache(M, B, H, H, d, "f32", flags=bct_ref.FLAG_MK_PER_SEQUENCE)
+    assert mk.shape == (B, H, M, d)
+    q, wq, wv = step_inputs(c, 15, 0)
+    out = c.decode_step(q, wq, wv)
+    for b in range(B):  # each batch element behaves as a batch-1 cache with its own keys
+        cb = RefCache(M, 1, H, H, d, "f32", 1.0 / math.sqrt(d), 1.0 / math.sqrt(d))
+        cb.set_keys(np.ascontiguousarray(mk[b]))
+        ob = cb.decode_step(q[b:b + 1], wq[b:b + 1], wv[b:b + 1])
+        assert np.array_equal(ob[0], out[b])
+
+
+# ------------------------------------------------------------------ P11 Algorithm 1's first-step branch
+
+def test_p11_first_step_without_write_keeps_mv0():
+    c, _, mv0 = make_cache(8, 1, 2, 2, 4, "bf16", mv0=True)
+    q, _, _ = step_inputs(c, 1, 0)
+    c.decode_step(q, None, None)
+    assert np.array_equal(c.values(), mv0) and c.steps == 1
+
+
+def test_argument_conventions():
+    c = RefCache(8, 1, 2, 2, 4, "f32", 1.0, 1.0)
+    q = np.zeros((1, 2, 4), np.float32)
+    o = np.zeros_like(q)
+    assert c.decode_step_rc(q, q, q, o) == 5          # keys not set yet
+    c.set_keys(np.zeros(c.keys_shape, np.float32))
+    assert c.decode_step_rc(q, q, None, o) == 1       # write half given
+    assert c.decode_step_rc(q, None, None, None) == 1  # read without out
+    assert c.decode_step_rc(None, None, None, None) == 1
+    assert c.decode_step_rc(q, q, q, o) == 0
+    with pytest.raises(ValueError):
+        RefCache(8, 1, 3, 2, 4, "f32", 1.0, 1.0)       # Hq not a multiple of Hkv
+
+
+# ------------------------------------------------------------------ P12 prefill
+
+def _chunk(c, seed, step0, T):
+    qs, wqs, wvs = zip(*[step_inputs(c, seed, step0 + t) for t in range(T)])
+    return (np.ascontiguousarray(np.stack(qs, 1)), np.ascontiguousarray(np.stack(wqs, 1)),
+            np.ascontiguousarray(np.stack(wvs, 1)))
+
+
+def test_p12_prefill_fp32_equals_sequential_bit_for_bit():
+    M, B, Hq, Hkv, d, T = 8, 2, 4, 2, 4, 7
+    cs, _, _ = make_cache(M, B, Hq, Hkv, d, "f32", mv0=True)
+    cp, _, _ = make_cache(M, B, Hq, Hkv, d, "f32", mv0=True)
+    q, wq, wv = _chunk(cs, 17, 0, T)
+    outs = [cs.decode_step(q[:, t].copy(), wq[:, t].copy(), wv[:, t].copy()) for t in range(T)]
+    outp = cp.prefill(q, wq, wv, T)
+    assert np.array_equal(np.stack(outs, 1), outp)     # float storage: the float copy IS the state
+    assert np.array_equal(cs.values(), cp.values())
+    assert cp.steps == T
+    # write-only prefill == Algorithm 1 run token by token
+    cw, _, _ = make_cache(M, B, Hq, Hkv, d, "f32", mv0=True)
+    assert cw.prefill(None, wq, wv, T) is None
+    assert np.array_equal(cw.values(), cs.values())
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_p12b_prefill_closed_form(dtype):
+    """out_t = rw_t . (MV_0 + sum_{s<=t} ww_s^T wv_s): write-then-read, causal inside the chunk."""
+    M, B, Hq, Hkv, d, T = 8, 2, 4, 2, 4, 6
+    rs, ws = 0.5, 0.8
+    G = Hq // Hkv
+    c, mk, mv0 = make_cache(M, B, Hq, Hkv, d, dtype, rs=rs, ws=ws, mv0=True)
+    q, wq, wv = _chunk(c, 19, 0, T)
+    out = f64(c.prefill(q, wq, wv, T), dtype)
+    K, V0, Q, WQ, WV = (f64(a, dtype) for a in (mk, mv0, q, wq, wv))
+    tol_o = 2e-6 if dtype == "f32" else 2 ** -8
+    for b in range(B):
+        for h in range(Hkv):
+            S = V0[b, h].copy()
+            for t in range(T):
+                S = S + np.outer(softmax64(ws * (K[h] @ WQ[b, t, h])), WV[b, t, h])
+                for g in range(G):
+                    ref = softmax64(rs * (K[h] @ Q[b, t, h * G + g])) @ S
+                    got = out[b, t, h * G + g]
+                    assert np.max(np.abs(got - ref)) <= tol_o * max(1.0, np.max(np.abs(ref)))
+            got_s = f64(c.values(), dtype)[b, h]
+            tol_s = 2e-6 if dtype == "f32" else 2 ** -8   # one final rounding to storage
+            assert np.max(np.abs(got_s - S)) <= tol_s * max(1.0, np.max(np.abs(S)))
+
+
+def test_p12c_prefill_bf16_close_to_sequential():
+    M, B, H, d, T = 8, 1, 2, 8, 16
+    cs, _, _ = make_cache(M, B, H, H, d, "bf16", mv0=True)
+    cp, _, _ = make_cache(M, B, H, H, d, "bf16", mv0=True)
+    q, wq, wv = _chunk(cs, 23, 0, T)
+    for t in range(T):
+        cs.decode_step(None, wq[:, t].copy(), wv[:, t].copy())
+    cp.prefill(None, wq, wv, T)
+    a, b = f64(cs.values(), "bf16"), f64(cp.values(), "bf16")
+    # T roundings of half an ulp each on one side, one on the other
+    assert np.max(np.abs(a - b)) <= (T + 1) * 2.0 ** -9 * np.max(np.abs(a))
+    assert not np.array_equal(a, b) or True
+
+
+# ------------------------------------------------------------------ hand-worked example
+
+def test_hand_worked_example():
+    with open(os.path.join(GOLDEN, "hand_worked_m2_d2.json")) as f:
+        g = json.load(f)
+    c = RefCache(2, 1, 1, 1, 2, "f32", g["read_scale"], g["write_scale"])
+    c.set_keys(np.array(g["MK"], dtype=np.float32).reshape(1, 2, 2))
+    for st in g["steps"]:
+        arr = lambda k: np.array(st[k], dtype=np.float32).reshape(1, 1, 2)
+        out = c.decode_step(arr("q"), arr("wq"), arr("wv"))
+        assert np.max(np.abs(out.reshape(2) - np.array(st["out"]))) <= 1e-6 * 5
+        assert np.max(np.abs(c.values().reshape(2, 2) - np.array(st["MV"]))) <= 1e-6 * 6
+
+
+# ------------------------------------------------------------------ rounding to bf16
+
+def test_bf16_rounding_against_grid_rounding_and_library_cast():
+    import torch
+    rng = np.random.default_rng(5)
+    bits = rng.integers(0, 2 ** 32, size=20000, dtype=np.uint64).astype(np.uint32)
+    edge = np.array([0x00000000, 0x80000000, 0x3F800000, 0x3F808000, 0x3F818000, 0x3F807FFF, 0x3F808001,
+                     0x7F7FFFFF, 0x7F800000, 0xFF800000, 0x00000001, 0x00008000, 0x00018000, 0x007FFFFF,
+                     0x00800000, 0x3EFFFFFF, 0x477FE000, 0x477FF000], dtype=np.uint32)
+    bits = np.concatenate([bits, edge])
+    x = bits.view(np.float32)
+    keep = ~np.isnan(x)
+    x = x[keep]
+    lib_cast = torch.from_numpy(x.copy()).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    for v, want in zip(x, lib_cast):
+        a = bct_ref.round_bf16_from_float(float(v))
+        b = bct_ref.round_bf16_from_double(float(v))
+        assert a == int(want), (v, a, want)
+        assert b == int(want), (v, b, want)
+    # the generator's packing agrees as well
+    assert np.array_equal(syn.f32_to_bf16_bits(x), lib_cast)
+    # a double that is NOT a float: exactly between two floats around a bf16 tie
+    tie = 1.0 + 2.0 ** -8                      # bf16 tie between 1.0 and 1.0078125
+    assert bct_ref.round_bf16_from_double(tie) == 0x3F80                 # ties to even
+    assert bct_ref.round_bf16_from_double(tie + 2.0 ** -40) == 0x3F81    # just above the tie
+    assert bct_ref.round_bf16_from_double(tie - 2.0 ** -40) == 0x3F80
