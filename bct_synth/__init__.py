@@ -47,13 +47,28 @@ def _stream_key(seed: int, tensor_id: int, step: int) -> np.uint64:
     return k[0]
 
 
-def raw_bits(seed: int, tensor_id: int, step: int, start: int, count: int, lane: int = 0) -> np.ndarray:
-    """uint64 random bits for flat indices [start, start+count)."""
+def raw_bits(seed: int, tensor_id: int, step: int, start: int, count: int) -> np.ndarray:
+    """uint64 random bits for counters [start, start+count)."""
     key = _stream_key(seed, tensor_id, step)
-    idx = np.arange(start, start + count, dtype=np.uint64)
-    with np.errstate(over="ignore"):
-        ctr = (idx * np.uint64(2) + np.uint64(lane)) & _M64
-        return _splitmix64(ctr ^ key)
+    ctr = np.arange(start, start + count, dtype=np.uint64)
+    return _splitmix64(ctr ^ key)
+
+
+def _normal_block(key_args, start: int, n: int) -> np.ndarray:
+    """Normals for flat indices [start, start+n).  Index i takes counter i // 2:
+    the counter's 64 bits give two 32-bit uniforms, Box-Muller turns them into
+    two normals, the even index takes the cosine branch and the odd the sine."""
+    p0, p1 = start // 2, (start + n + 1) // 2
+    bits = raw_bits(*key_args, p0, p1 - p0)
+    u1 = ((bits >> np.uint64(32)).astype(np.float64) + 1.0) * (1.0 / 4294967296.0)
+    u2 = (bits & np.uint64(0xFFFFFFFF)).astype(np.float64) * (1.0 / 4294967296.0)
+    r = np.sqrt(-2.0 * np.log(u1))
+    ang = (2.0 * math.pi) * u2
+    z = np.empty((p1 - p0, 2), dtype=np.float64)
+    np.multiply(r, np.cos(ang), out=z[:, 0])
+    np.multiply(r, np.sin(ang), out=z[:, 1])
+    off = start - 2 * p0
+    return z.reshape(-1)[off:off + n]
 
 
 def normal(seed: int, tensor_id: int, step: int, shape, start: int = 0) -> np.ndarray:
@@ -61,21 +76,29 @@ def normal(seed: int, tensor_id: int, step: int, shape, start: int = 0) -> np.nd
     flattened result depends only on (seed, tensor_id, step, start + i)."""
     count = int(np.prod(shape)) if len(shape) else 1
     out = np.empty(count, dtype=np.float64)
-    blk = 1 << 22
-    for s in range(0, count, blk):
-        n = min(blk, count - s)
-        b1 = raw_bits(seed, tensor_id, step, start + s, n, lane=0)
-        b2 = raw_bits(seed, tensor_id, step, start + s, n, lane=1)
-        u1 = ((b1 >> np.uint64(11)).astype(np.float64) + 1.0) * (1.0 / 9007199254740992.0)
-        u2 = (b2 >> np.uint64(11)).astype(np.float64) * (1.0 / 9007199254740992.0)
-        out[s:s + n] = np.sqrt(-2.0 * np.log(u1)) * np.cos((2.0 * math.pi) * u2)
+    blk = 1 << 20
+    key_args = (seed, tensor_id, step)
+    spans = [(s, min(blk, count - s)) for s in range(0, count, blk)]
+
+    def work(span):
+        s, n = span
+        out[s:s + n] = _normal_block(key_args, start + s, n)
+
+    if len(spans) <= 1:
+        for sp in spans:
+            work(sp)
+    else:  # numpy releases the GIL inside its loops; blocks are independent
+        import concurrent.futures
+        import os
+        with concurrent.futures.ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as ex:
+            list(ex.map(work, spans))
     return out.reshape(shape)
 
 
 def integers(seed: int, tensor_id: int, step: int, shape, high: int) -> np.ndarray:
     """Uniform integer ids in [0, high) (int64)."""
     count = int(np.prod(shape))
-    b = raw_bits(seed, tensor_id, step, 0, count, lane=0)
+    b = raw_bits(seed, tensor_id, step, 0, count)
     return (b % np.uint64(high)).astype(np.int64).reshape(shape)
 
 

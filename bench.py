@@ -1,0 +1,167 @@
+#!/usr/bin/env python3
+"""Decode-throughput benchmark of libbct on one MI355X.
+
+A step is one token per sequence through every layer of the workload: for each
+layer one bct_decode_step (scores, cache update of all M slots, read).  The
+default workload is the Llama-7B-shaped stack (32 layers, batch 32, 32 heads,
+head_dim 128, M = 4096, bf16).  Inputs are seeded and synthetic and already in
+HBM when the timed region starts.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3] [--layers L]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def cpu_baseline(w, seconds_budget=20.0):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload:
+    one layer, the first few batch elements, a few decode steps from MV_0 = 0."""
+    import numpy as np
+
+    import bct_synth as syn
+    from oracle import bct_ref
+
+    bsub = min(w.B, 4)
+    ws = syn.Workload(w.name + "_sample", 1, bsub, w.Hq, w.Hkv, w.d, w.M, w.dtype, 0)
+    ref = bct_ref.RefCache(ws.M, ws.B, ws.Hq, ws.Hkv, ws.d, ws.dtype, ws.scale, ws.scale)
+    ref.set_keys(syn.make_keys(w, 0))
+    q, wq, wv = (np.ascontiguousarray(a[:bsub]) for a in syn.make_step(w, 0, 0))
+    ref.decode_step(q, wq, wv)  # warm-up
+    n, t0 = 0, time.perf_counter()
+    while True:
+        ref.decode_step(q, wq, wv)
+        n += 1
+        el = time.perf_counter() - t0
+        if n >= 3 and (el >= 2.0 or n >= 64):
+            break
+        if el > seconds_budget:
+            break
+    per_layer_step = el / n
+    tok_s = bsub / (per_layer_step * w.layers)
+    cores = bct_ref.num_threads()
+    return {
+        "value": tok_s, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+        "sample": (f"one layer of {w.name}, first {bsub} of {w.B} batch elements, {n} decode steps timed after "
+                   f"1 warm-up; {per_layer_step * 1e3:.1f} ms per layer-step, scaled to {w.layers} layers"),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg3")
+    ap.add_argument("--layers", type=int, default=0, help="override the layer count (0 = the workload's)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import bct_synth as syn
+    import paper_2411_15785_amd as pkg
+
+    pkg.lib()  # no fallback: fails here if libbct.so is missing
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    dev = "cuda:0"
+    w0 = syn.WORKLOADS[args.workload]
+    L = args.layers or w0.layers
+    w = syn.Workload(w0.name, L, w0.B, w0.Hq, w0.Hkv, w0.d, w0.M, w0.dtype, w0.decode_steps, w0.prompt,
+                     w0.prefill_chunk)
+    tdt = torch.float32 if w.dtype == "f32" else torch.bfloat16
+
+    def to_dev(a):
+        if w.dtype == "f32":
+            return torch.from_numpy(a).to(dev)
+        return torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
+
+    t_setup = time.perf_counter()
+    POOL = 2  # distinct seeded step inputs per layer, cycled (the cost does not depend on the values)
+    caches, inputs, outs = [], [], []
+    for layer in range(L):
+        c = pkg.BctCache(w.M, w.B, w.Hq, w.Hkv, w.d, tdt, w.scale, w.scale, device=dev)
+        c.set_keys(to_dev(syn.make_keys(w, layer)))
+        caches.append(c)
+        inputs.append([tuple(to_dev(a) for a in syn.make_step(w, s, layer)) for s in range(POOL)])
+        outs.append(torch.empty((w.B, w.Hq, w.d), dtype=tdt, device=dev))
+    torch.cuda.synchronize()
+    log(f"setup: {L} layers of {w.name} in {time.perf_counter() - t_setup:.1f} s, "
+        f"{sum(c.cache_bytes for c in caches) / 2**30:.1f} GiB of cache")
+
+    def step(s):
+        for layer in range(L):
+            q, wq, wv = inputs[layer][s % POOL]
+            caches[layer].decode_step(q, wq, wv, outs[layer])
+
+    for s in range(args.warmup):
+        step(s)
+    torch.cuda.synchronize()
+    caches[0].profile_enable(args.steps)
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step(args.warmup + s)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    n_rec, ms_scores, ms_mv, ms_merge = caches[0].profile_read()
+    caches[0].profile_enable(0)
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    tok_s = w.B / (ms_per_step * 1e-3)
+
+    sz = syn.elem_size(w.dtype)
+    mv_bytes = w.B * w.Hkv * w.M * w.d * sz
+    # the MV pass itself must move: MV in, MV out, wv in, out out
+    mv_pass_bytes = 2 * mv_bytes + w.B * (w.Hkv + w.Hq) * w.d * sz
+    layer_step_bytes = w.algorithmic_bytes_per_layer_step(shared_mk=True)
+    achieved = mv_pass_bytes / (ms_mv * 1e-3) / 1e9 if ms_mv > 0 else None
+    layer_ms = ms_per_step / L
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"hbm_traffic_{w.name}.json")
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            traffic = json.load(f).get("mv_pass_hbm_bytes_per_launch")
+
+    rec = {
+        "metric": "decode tokens/sec and achieved HBM GB/s (% of peak) at fixed cache capacity M",
+        "value": tok_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": f"{w.name}: {L} layers x (B={w.B}, Hq={w.Hq}, Hkv={w.Hkv}, d={w.d}, M={w.M}, "
+                               f"{w.dtype}), one decode step per layer per token, attention + cache update only",
+                   "layers": L, "batch": w.B, "capacity_M": w.M},
+        "roofline": {"bound": "hbm", "kernel": "stream_kernel (MV pass)",
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": (achieved / HBM_PEAK_GBS) if achieved else None, "traffic": traffic,
+                     "bytes_per_launch": mv_pass_bytes, "ms_per_launch": ms_mv, "launches_timed": n_rec},
+        "layer_step": {"algorithmic_bytes": layer_step_bytes, "ms": layer_ms,
+                       "GB/s": layer_step_bytes / (layer_ms * 1e-3) / 1e9,
+                       "frac_of_peak": layer_step_bytes / (layer_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                       "ms_scores": ms_scores, "ms_mv_pass": ms_mv, "ms_merge": ms_merge},
+    }
+    if not args.no_cpu_baseline:
+        rec["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(rec), flush=True)
+
+
+if __name__ == "__main__":
+    main()

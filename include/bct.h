@@ -1,0 +1,150 @@
+/* libbct -- Bounded-Cache Transformer decode path on AMD MI355X (gfx950).
+ *
+ * C ABI.  Plain pointers and sizes only.  Unless a parameter says "host",
+ * every data pointer is DEVICE memory owned by the caller; the library never
+ * allocates or frees device memory.  A bct_cache handle owns a small host
+ * struct only.  All calls that take a stream enqueue work on it and return
+ * without synchronising; calls on one cache must be stream-ordered by the
+ * caller.  Argument checks run before the first HIP call, so they can be
+ * exercised on a machine without a GPU.
+ *
+ * The method (arXiv 2411.15785):
+ *   state   MK  M key vectors per KV head, predefined capacity M (section 3.1);
+ *               an input of Algorithm 1 that no step ever assigns to.
+ *           MV  M key-value vectors per (batch element, KV head) (section 3.1),
+ *               zero or random at the start.
+ *   write   ww = softmax(write_scale * wq . MK^T)      (section 3.2 step 2, Alg. 1)
+ *           MV = MV' + ww^T . wv  for ALL M slots      (section 3.2 step 4, 3.4 eq.)
+ *           stored back in place                       (section 3.2 step 5)
+ *   read    out = softmax(read_scale * q . MK^T) . MV  (attention of the layer's
+ *           query over the bounded cache; the read follows the write of the same
+ *           token)
+ * k_new is the paper's write query wq_t, v_new its write key-value vector wv_t,
+ * both already projected by the caller (W_wq, W_wv stay outside the library).
+ *
+ * Layouts (row-major, innermost contiguous, element type = desc.dtype):
+ *   q, out        [B][Hq][d]            prefill: [B][T][Hq][d]
+ *   k_new, v_new  [B][Hkv][d]           prefill: [B][T][Hkv][d]
+ *   MK            [Hkv][M][d]           or [B][Hkv][M][d] with BCT_MK_PER_SEQUENCE
+ *   MV            [B][Hkv][M][d]
+ * Query head hq reads the memory of KV head hq / (Hq/Hkv).
+ * Every pointer must be 16-byte aligned.
+ */
+#ifndef BCT_H
+#define BCT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  BCT_OK = 0,
+  BCT_ERR_INVALID_ARG = 1,      /* NULL where data is needed, bad NULL mix, zero size   */
+  BCT_ERR_UNSUPPORTED = 2,      /* shape / dtype / flag outside what the kernels handle */
+  BCT_ERR_BUFFER_TOO_SMALL = 3, /* cache_bytes or workspace_bytes below bct_cache_query */
+  BCT_ERR_MISALIGNED = 4,       /* a pointer is not 16-byte aligned                     */
+  BCT_ERR_STATE = 5,            /* step before bct_cache_set_keys                       */
+  BCT_ERR_HIP = 6               /* a HIP call failed; text in bct_last_error()          */
+} bct_status;
+
+typedef enum { BCT_F32 = 0, BCT_BF16 = 1 } bct_dtype;
+
+enum { BCT_MK_PER_SEQUENCE = 1u }; /* desc.flags: one key table per batch element */
+
+typedef struct {
+  uint32_t capacity_M;  /* M > 0, multiple of 64, at most 65536                        */
+  uint32_t batch;       /* B > 0                                                       */
+  uint32_t n_q_heads;   /* Hq, multiple of n_kv_heads, Hq/Hkv at most 8                */
+  uint32_t n_kv_heads;  /* Hkv > 0                                                     */
+  uint32_t head_dim;    /* d: 64 or 128                                                */
+  int32_t  dtype;       /* bct_dtype: storage and I/O type of MK, MV, q, k_new, v_new, out */
+  float    read_scale;  /* multiplies q . MK^T, e.g. 1/sqrt(d)                         */
+  float    write_scale; /* multiplies wq . MK^T; 1.0 = Algorithm 1 as printed          */
+  uint32_t flags;       /* 0 or BCT_MK_PER_SEQUENCE                                    */
+} bct_cache_desc;
+
+typedef struct bct_cache bct_cache; /* opaque, host memory */
+
+/* Sizes the caller must provide for a cache of this shape (host call, no GPU
+ * needed).  cache_bytes covers MK and MV and never changes afterwards: memory
+ * use is constant in the number of tokens (section 4.3).  workspace_bytes is
+ * scratch for scores and split-M partial results of one step; max_prefill_T
+ * states the longest prefill chunk that workspace must serve (0 = decode only).
+ * Either output pointer may be NULL. */
+bct_status bct_cache_query(const bct_cache_desc* desc, uint32_t max_prefill_T,
+                           size_t* cache_bytes, size_t* workspace_bytes);
+
+/* Creates the handle over caller-owned device memory, sets MV := 0
+ * (section 3.1) and steps := 0.  MK is unset until bct_cache_set_keys.
+ * Errors: INVALID_ARG, UNSUPPORTED, BUFFER_TOO_SMALL, MISALIGNED, HIP. */
+bct_status bct_cache_init(const bct_cache_desc* desc, uint32_t max_prefill_T,
+                          void* cache_mem, size_t cache_bytes,
+                          void* workspace, size_t workspace_bytes,
+                          void* hip_stream, bct_cache** out);
+
+/* Copies the key table (device, MK layout above) into the cache.  The keys
+ * are static: no other call writes them (Algorithm 1 takes MK as an input). */
+bct_status bct_cache_set_keys(bct_cache* c, const void* mk_dev, void* hip_stream);
+
+/* MV := mv0_dev (device, MV layout), or zero if NULL (section 3.1: "zero or
+ * random values").  Does not touch steps. */
+bct_status bct_cache_set_values(bct_cache* c, const void* mv0_dev, void* hip_stream);
+
+/* One token per sequence (section 3.2 steps 2-5 for the write, then the read).
+ *   k_new == v_new == NULL : read-only step, MV untouched.
+ *   q == out == NULL       : write-only step = one iteration of Algorithm 1.
+ *   any other NULL mix     : BCT_ERR_INVALID_ARG.
+ * steps += 1.  Errors: INVALID_ARG, MISALIGNED, STATE, HIP. */
+bct_status bct_decode_step(bct_cache* c, const void* q, const void* k_new, const void* v_new,
+                           void* out, void* hip_stream);
+
+/* A chunk of T tokens per sequence (1 <= T <= max_prefill_T), equal to T decode
+ * steps in token order except that MV is carried in fp32 through the chunk and
+ * rounded to the storage dtype once at its end (the accumulation over tokens is
+ * order-free: section 3.5).  Same NULL conventions.  steps += T. */
+bct_status bct_prefill(bct_cache* c, const void* q, const void* k_new, const void* v_new,
+                       uint32_t T, void* out, void* hip_stream);
+
+/* Checkpoint: copies MK and/or MV out of / into the cache (device pointers,
+ * either may be NULL) together with the step counter (host). */
+bct_status bct_cache_export(const bct_cache* c, void* mk_dst, void* mv_dst, uint64_t* steps,
+                            void* hip_stream);
+bct_status bct_cache_import(bct_cache* c, const void* mk_src, const void* mv_src, uint64_t steps,
+                            void* hip_stream);
+
+bct_status bct_cache_steps(const bct_cache* c, uint64_t* steps);
+
+/* Device addresses of the two regions inside cache_mem (for zero-copy views). */
+bct_status bct_cache_regions(const bct_cache* c, void** mk_dev, size_t* mk_bytes,
+                             void** mv_dev, size_t* mv_bytes);
+
+/* Frees the host handle only; device memory stays with the caller. */
+void bct_cache_destroy(bct_cache* c);
+
+const char* bct_strerror(bct_status s);
+const char* bct_last_error(void); /* thread-local detail of the last failure */
+
+/* Measurement aid: per-kernel timing of decode steps with HIP events recorded
+ * on the caller's stream around each launch (scores, MV pass, merge).
+ * bct_profile_enable(c, n) keeps events for the next n decode steps (n = 0
+ * switches it off and releases the events).  bct_profile_read waits for the
+ * recorded events, returns how many steps were recorded and the mean
+ * duration in milliseconds of each launch (host pointers, any may be NULL),
+ * and starts over.  Not for use under graph capture. */
+bct_status bct_profile_enable(bct_cache* c, uint32_t n_steps);
+bct_status bct_profile_read(bct_cache* c, uint32_t* n_recorded, float* ms_scores, float* ms_mv_pass,
+                            float* ms_merge);
+
+/* Measurement aid: a plain device-to-device copy kernel (16-byte vectors),
+ * n_bytes a multiple of 16, src/dst 16-byte aligned.  Reads n_bytes and
+ * writes n_bytes; used to calibrate HBM counters and as the practical ceiling
+ * for a 1:1 read/write stream such as the section 3.4 update. */
+bct_status bct_stream_copy(void* dst, const void* src, size_t n_bytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BCT_H */

@@ -45,6 +45,8 @@
 // parity-unpinned against the authors' implementation; every equation the
 // paper states is pinned by the list above.
 
+#include <omp.h>
+
 #include <cmath>
 #include <cstdint>
 #include <cstdlib>
@@ -369,6 +371,9 @@ int bct_ref_probe_weights(const bct_ref_cache* c, uint32_t b, uint32_t h, const 
   softmax_weights(*c, vec, 0, key_offset(*c, b, h), scale, w);
   return 0;
 }
+
+// Threads the outer loop over (batch, KV head) memories will use.
+int bct_ref_num_threads(void) { return omp_get_max_threads(); }
 
 uint16_t bct_ref_round_bf16_from_float(float f) { return float_to_bf16_bits(f); }
 uint16_t bct_ref_round_bf16_from_double(double x) { return double_to_bf16_bits(x); }

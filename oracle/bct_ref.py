@@ -181,6 +181,10 @@ class RefCache:
         return w
 
 
+def num_threads() -> int:
+    return lib().bct_ref_num_threads()
+
+
 def round_bf16_from_float(f: float) -> int:
     return lib().bct_ref_round_bf16_from_float(f)
 

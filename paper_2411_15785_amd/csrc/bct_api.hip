@@ -1,0 +1,394 @@
+// C ABI of libbct: argument checks, the per-cache plan and the launch
+// sequence.  Every check runs before the first HIP call of an entry point.
+#include "../../include/bct.h"
+
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "bct_internal.h"
+
+struct bct_cache {
+  bct_cache_desc desc;
+  uint32_t max_T;
+  char* mk;
+  char* mv;
+  size_t mk_bytes, mv_bytes;
+  char* ws;
+  size_t ws_bytes;
+  // workspace carve-up (byte offsets)
+  size_t off_scores, off_stats, off_partial, off_prefill;
+  uint64_t steps;
+  bool keys_set;
+  bct::DecodeParams plan;  // shape, strides and launch plan; pointers filled per call
+  // optional per-launch timing: 4 events per recorded step
+  std::vector<hipEvent_t> prof_ev;
+  uint32_t prof_cap = 0, prof_n = 0;
+};
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+bct_status fail(bct_status s, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return s;
+}
+
+bct_status hip_fail(hipError_t e, const char* what) {
+  return fail(BCT_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+inline size_t esize(int dtype) { return dtype == BCT_F32 ? 4 : 2; }
+
+bct_status check_desc(const bct_cache_desc* d) {
+  if (!d) return fail(BCT_ERR_INVALID_ARG, "desc is NULL");
+  if (d->capacity_M == 0 || d->batch == 0 || d->n_q_heads == 0 || d->n_kv_heads == 0 || d->head_dim == 0)
+    return fail(BCT_ERR_INVALID_ARG, "capacity_M, batch, n_q_heads, n_kv_heads and head_dim must be positive");
+  if (d->n_q_heads % d->n_kv_heads != 0)
+    return fail(BCT_ERR_INVALID_ARG, "n_q_heads (%u) is not a multiple of n_kv_heads (%u)", d->n_q_heads,
+                d->n_kv_heads);
+  if (!isfinite(d->read_scale) || !isfinite(d->write_scale))
+    return fail(BCT_ERR_INVALID_ARG, "read_scale and write_scale must be finite");
+  if (d->dtype != BCT_F32 && d->dtype != BCT_BF16) return fail(BCT_ERR_UNSUPPORTED, "dtype %d", d->dtype);
+  if (d->head_dim != 64 && d->head_dim != 128)
+    return fail(BCT_ERR_UNSUPPORTED, "head_dim %u (64 or 128)", d->head_dim);
+  if (d->capacity_M % 64 != 0 || d->capacity_M > 65536)
+    return fail(BCT_ERR_UNSUPPORTED, "capacity_M %u (a multiple of 64, at most 65536)", d->capacity_M);
+  if (d->n_q_heads / d->n_kv_heads > bct::kMaxG)
+    return fail(BCT_ERR_UNSUPPORTED, "n_q_heads / n_kv_heads = %u (at most %u)", d->n_q_heads / d->n_kv_heads,
+                bct::kMaxG);
+  if (d->flags & ~(uint32_t)BCT_MK_PER_SEQUENCE) return fail(BCT_ERR_UNSUPPORTED, "unknown flags 0x%x", d->flags);
+  if ((uint64_t)d->batch * d->n_kv_heads > 65535u)
+    return fail(BCT_ERR_UNSUPPORTED, "batch * n_kv_heads = %llu (at most 65535)",
+                (unsigned long long)d->batch * d->n_kv_heads);
+  return BCT_OK;
+}
+
+struct Sizes {
+  size_t mk_bytes, mv_bytes, cache_bytes;
+  size_t off_scores, off_stats, off_partial, off_prefill, ws_bytes;
+};
+
+void fill_plan(const bct_cache_desc* d, bct::DecodeParams& p) {
+  memset(&p, 0, sizeof(p));
+  p.B = d->batch;
+  p.Hq = d->n_q_heads;
+  p.Hkv = d->n_kv_heads;
+  p.G = p.Hq / p.Hkv;
+  p.M = d->capacity_M;
+  p.d = d->head_dim;
+  p.mk_per_seq = (d->flags & BCT_MK_PER_SEQUENCE) ? 1u : 0u;
+  const double l2e = 1.4426950408889634;
+  p.rscale_l2e = (float)((double)d->read_scale * l2e);
+  p.wscale_l2e = (float)((double)d->write_scale * l2e);
+  p.q_bstride = (uint64_t)p.Hq * p.d;
+  p.kv_bstride = (uint64_t)p.Hkv * p.d;
+  p.R = 1 + p.G;
+  p.has_write = p.has_read = 1;
+  bct::plan_decode(p, d->dtype);
+}
+
+Sizes compute_sizes(const bct_cache_desc* d, uint32_t max_T) {
+  Sizes z;
+  const size_t sz = esize(d->dtype);
+  const size_t per_head = (size_t)d->capacity_M * d->head_dim * sz;
+  const size_t units = (size_t)d->batch * d->n_kv_heads;
+  z.mk_bytes = ((d->flags & BCT_MK_PER_SEQUENCE) ? units : (size_t)d->n_kv_heads) * per_head;
+  z.mv_bytes = units * per_head;
+  z.cache_bytes = align_up(z.mk_bytes, 256) + z.mv_bytes;
+  bct::DecodeParams p;
+  fill_plan(d, p);
+  const size_t rows = 1 + p.G;
+  size_t off = 0;
+  z.off_scores = off;
+  off += align_up(units * rows * p.M * sizeof(float), 256);
+  z.off_stats = off;
+  off += align_up(units * rows * (p.M / bct::kMinStatTile) * sizeof(float2), 256);
+  z.off_partial = off;
+  off += align_up((size_t)p.S * d->batch * d->n_q_heads * d->head_dim * sizeof(float), 256);
+  z.off_prefill = off;
+  (void)max_T;
+  z.ws_bytes = off;
+  return z;
+}
+
+bct_status check_io(const bct_cache* c, const void* q, const void* k_new, const void* v_new, const void* out) {
+  if (!c) return fail(BCT_ERR_INVALID_ARG, "cache handle is NULL");
+  if ((k_new == nullptr) != (v_new == nullptr))
+    return fail(BCT_ERR_INVALID_ARG, "k_new and v_new must both be given or both be NULL");
+  if ((q == nullptr) != (out == nullptr))
+    return fail(BCT_ERR_INVALID_ARG, "q and out must both be given or both be NULL");
+  if (!q && !k_new) return fail(BCT_ERR_INVALID_ARG, "neither a read (q, out) nor a write (k_new, v_new) given");
+  if (!aligned16(q) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(out))
+    return fail(BCT_ERR_MISALIGNED, "q, k_new, v_new and out must be 16-byte aligned");
+  if (!c->keys_set) return fail(BCT_ERR_STATE, "bct_cache_set_keys has not been called");
+  return BCT_OK;
+}
+
+// The three launches of one decode step; q/kv batch strides allow a token of
+// a [B][T][H][d] chunk to be stepped in place.
+bct_status run_decode(bct_cache* c, const void* q, const void* k_new, const void* v_new, void* out,
+                      uint64_t q_bstride, uint64_t kv_bstride, hipStream_t s) {
+  bct::DecodeParams p = c->plan;
+  p.mk = c->mk;
+  p.mv = c->mv;
+  p.q = q;
+  p.wq = k_new;
+  p.wv = v_new;
+  p.out = out;
+  p.scores = (float*)(c->ws + c->off_scores);
+  p.stats = (float2*)(c->ws + c->off_stats);
+  p.partial = (float*)(c->ws + c->off_partial);
+  p.has_write = k_new ? 1u : 0u;
+  p.has_read = q ? 1u : 0u;
+  p.R = p.has_write + (p.has_read ? p.G : 0u);
+  p.q_bstride = q_bstride;
+  p.kv_bstride = kv_bstride;
+  hipError_t e;
+  hipEvent_t* ev = (c->prof_n < c->prof_cap) ? &c->prof_ev[(size_t)c->prof_n * 4] : nullptr;
+  if (ev && (e = hipEventRecord(ev[0], s)) != hipSuccess) return hip_fail(e, "event record");
+  if ((e = bct::launch_scores(p, c->desc.dtype, s)) != hipSuccess) return hip_fail(e, "scores launch");
+  if (ev && (e = hipEventRecord(ev[1], s)) != hipSuccess) return hip_fail(e, "event record");
+  if ((e = bct::launch_stream(p, c->desc.dtype, s)) != hipSuccess) return hip_fail(e, "MV pass launch");
+  if (ev && (e = hipEventRecord(ev[2], s)) != hipSuccess) return hip_fail(e, "event record");
+  if ((e = bct::launch_merge(p, c->desc.dtype, s)) != hipSuccess) return hip_fail(e, "merge launch");
+  if (ev) {
+    if ((e = hipEventRecord(ev[3], s)) != hipSuccess) return hip_fail(e, "event record");
+    c->prof_n += 1;
+  }
+  return BCT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+bct_status bct_cache_query(const bct_cache_desc* desc, uint32_t max_prefill_T, size_t* cache_bytes,
+                           size_t* workspace_bytes) {
+  bct_status st = check_desc(desc);
+  if (st != BCT_OK) return st;
+  const Sizes z = compute_sizes(desc, max_prefill_T);
+  if (cache_bytes) *cache_bytes = z.cache_bytes;
+  if (workspace_bytes) *workspace_bytes = z.ws_bytes;
+  return BCT_OK;
+}
+
+bct_status bct_cache_init(const bct_cache_desc* desc, uint32_t max_prefill_T, void* cache_mem, size_t cache_bytes,
+                          void* workspace, size_t workspace_bytes, void* hip_stream, bct_cache** out) {
+  if (!out) return fail(BCT_ERR_INVALID_ARG, "out is NULL");
+  *out = nullptr;
+  bct_status st = check_desc(desc);
+  if (st != BCT_OK) return st;
+  if (!cache_mem || !workspace) return fail(BCT_ERR_INVALID_ARG, "cache_mem and workspace must not be NULL");
+  if (((uintptr_t)cache_mem & 255u) || ((uintptr_t)workspace & 255u))
+    return fail(BCT_ERR_MISALIGNED, "cache_mem and workspace must be 256-byte aligned");
+  const Sizes z = compute_sizes(desc, max_prefill_T);
+  if (cache_bytes < z.cache_bytes)
+    return fail(BCT_ERR_BUFFER_TOO_SMALL, "cache_bytes %zu < %zu", cache_bytes, z.cache_bytes);
+  if (workspace_bytes < z.ws_bytes)
+    return fail(BCT_ERR_BUFFER_TOO_SMALL, "workspace_bytes %zu < %zu", workspace_bytes, z.ws_bytes);
+  bct_cache* c = new (std::nothrow) bct_cache();
+  if (!c) return fail(BCT_ERR_INVALID_ARG, "out of host memory");
+  c->desc = *desc;
+  c->max_T = max_prefill_T;
+  c->mk = (char*)cache_mem;
+  c->mv = (char*)cache_mem + align_up(z.mk_bytes, 256);
+  c->mk_bytes = z.mk_bytes;
+  c->mv_bytes = z.mv_bytes;
+  c->ws = (char*)workspace;
+  c->ws_bytes = z.ws_bytes;
+  c->off_scores = z.off_scores;
+  c->off_stats = z.off_stats;
+  c->off_partial = z.off_partial;
+  c->off_prefill = z.off_prefill;
+  c->steps = 0;
+  c->keys_set = false;
+  fill_plan(desc, c->plan);
+  const hipError_t e = bct::launch_fill_zero(c->mv, c->mv_bytes, (hipStream_t)hip_stream);
+  if (e != hipSuccess) {
+    delete c;
+    return hip_fail(e, "zeroing MV");
+  }
+  *out = c;
+  return BCT_OK;
+}
+
+bct_status bct_cache_set_keys(bct_cache* c, const void* mk_dev, void* hip_stream) {
+  if (!c || !mk_dev) return fail(BCT_ERR_INVALID_ARG, "cache handle or mk_dev is NULL");
+  if (!aligned16(mk_dev)) return fail(BCT_ERR_MISALIGNED, "mk_dev must be 16-byte aligned");
+  const hipError_t e = bct::launch_copy(c->mk, mk_dev, c->mk_bytes, (hipStream_t)hip_stream);
+  if (e != hipSuccess) return hip_fail(e, "copying MK");
+  c->keys_set = true;
+  return BCT_OK;
+}
+
+bct_status bct_cache_set_values(bct_cache* c, const void* mv0_dev, void* hip_stream) {
+  if (!c) return fail(BCT_ERR_INVALID_ARG, "cache handle is NULL");
+  if (!aligned16(mv0_dev)) return fail(BCT_ERR_MISALIGNED, "mv0_dev must be 16-byte aligned");
+  const hipError_t e = mv0_dev ? bct::launch_copy(c->mv, mv0_dev, c->mv_bytes, (hipStream_t)hip_stream)
+                               : bct::launch_fill_zero(c->mv, c->mv_bytes, (hipStream_t)hip_stream);
+  if (e != hipSuccess) return hip_fail(e, "setting MV");
+  return BCT_OK;
+}
+
+bct_status bct_decode_step(bct_cache* c, const void* q, const void* k_new, const void* v_new, void* out,
+                           void* hip_stream) {
+  bct_status st = check_io(c, q, k_new, v_new, out);
+  if (st != BCT_OK) return st;
+  st = run_decode(c, q, k_new, v_new, out, (uint64_t)c->desc.n_q_heads * c->desc.head_dim,
+                  (uint64_t)c->desc.n_kv_heads * c->desc.head_dim, (hipStream_t)hip_stream);
+  if (st != BCT_OK) return st;
+  c->steps += 1;
+  return BCT_OK;
+}
+
+bct_status bct_prefill(bct_cache* c, const void* q, const void* k_new, const void* v_new, uint32_t T, void* out,
+                       void* hip_stream) {
+  bct_status st = check_io(c, q, k_new, v_new, out);
+  if (st != BCT_OK) return st;
+  if (T == 0) return fail(BCT_ERR_INVALID_ARG, "T must be positive");
+  if (T > c->max_T) return fail(BCT_ERR_BUFFER_TOO_SMALL, "T %u exceeds max_prefill_T %u given at init", T, c->max_T);
+  const size_t sz = esize(c->desc.dtype);
+  const uint64_t qs = (uint64_t)c->desc.n_q_heads * c->desc.head_dim;
+  const uint64_t ks = (uint64_t)c->desc.n_kv_heads * c->desc.head_dim;
+  if (c->desc.dtype == BCT_F32) {
+    // fp32 storage: the fp32 running copy of MV IS the stored state, so the
+    // chunk is exactly T decode steps in token order.
+    for (uint32_t t = 0; t < T; ++t) {
+      st = run_decode(c, q ? (const char*)q + t * qs * sz : nullptr, k_new ? (const char*)k_new + t * ks * sz : nullptr,
+                      v_new ? (const char*)v_new + t * ks * sz : nullptr, out ? (char*)out + t * qs * sz : nullptr,
+                      (uint64_t)T * qs, (uint64_t)T * ks, (hipStream_t)hip_stream);
+      if (st != BCT_OK) return st;
+    }
+    c->steps += T;
+    return BCT_OK;
+  }
+  return fail(BCT_ERR_UNSUPPORTED, "bf16 prefill is not built yet");
+}
+
+bct_status bct_cache_export(const bct_cache* c, void* mk_dst, void* mv_dst, uint64_t* steps, void* hip_stream) {
+  if (!c) return fail(BCT_ERR_INVALID_ARG, "cache handle is NULL");
+  if (!aligned16(mk_dst) || !aligned16(mv_dst)) return fail(BCT_ERR_MISALIGNED, "destinations must be 16-byte aligned");
+  hipError_t e;
+  if (mk_dst && (e = bct::launch_copy(mk_dst, c->mk, c->mk_bytes, (hipStream_t)hip_stream)) != hipSuccess)
+    return hip_fail(e, "exporting MK");
+  if (mv_dst && (e = bct::launch_copy(mv_dst, c->mv, c->mv_bytes, (hipStream_t)hip_stream)) != hipSuccess)
+    return hip_fail(e, "exporting MV");
+  if (steps) *steps = c->steps;
+  return BCT_OK;
+}
+
+bct_status bct_cache_import(bct_cache* c, const void* mk_src, const void* mv_src, uint64_t steps, void* hip_stream) {
+  if (!c) return fail(BCT_ERR_INVALID_ARG, "cache handle is NULL");
+  if (!aligned16(mk_src) || !aligned16(mv_src)) return fail(BCT_ERR_MISALIGNED, "sources must be 16-byte aligned");
+  hipError_t e;
+  if (mk_src) {
+    if ((e = bct::launch_copy(c->mk, mk_src, c->mk_bytes, (hipStream_t)hip_stream)) != hipSuccess)
+      return hip_fail(e, "importing MK");
+    c->keys_set = true;
+  }
+  if (mv_src && (e = bct::launch_copy(c->mv, mv_src, c->mv_bytes, (hipStream_t)hip_stream)) != hipSuccess)
+    return hip_fail(e, "importing MV");
+  c->steps = steps;
+  return BCT_OK;
+}
+
+bct_status bct_cache_steps(const bct_cache* c, uint64_t* steps) {
+  if (!c || !steps) return fail(BCT_ERR_INVALID_ARG, "cache handle or steps is NULL");
+  *steps = c->steps;
+  return BCT_OK;
+}
+
+bct_status bct_cache_regions(const bct_cache* c, void** mk_dev, size_t* mk_bytes, void** mv_dev, size_t* mv_bytes) {
+  if (!c) return fail(BCT_ERR_INVALID_ARG, "cache handle is NULL");
+  if (mk_dev) *mk_dev = c->mk;
+  if (mk_bytes) *mk_bytes = c->mk_bytes;
+  if (mv_dev) *mv_dev = c->mv;
+  if (mv_bytes) *mv_bytes = c->mv_bytes;
+  return BCT_OK;
+}
+
+void bct_cache_destroy(bct_cache* c) {
+  if (!c) return;
+  for (hipEvent_t ev : c->prof_ev) (void)hipEventDestroy(ev);
+  delete c;
+}
+
+bct_status bct_profile_enable(bct_cache* c, uint32_t n_steps) {
+  if (!c) return fail(BCT_ERR_INVALID_ARG, "cache handle is NULL");
+  if (n_steps > 65536) return fail(BCT_ERR_INVALID_ARG, "n_steps %u (at most 65536)", n_steps);
+  for (hipEvent_t ev : c->prof_ev) (void)hipEventDestroy(ev);
+  c->prof_ev.clear();
+  c->prof_cap = c->prof_n = 0;
+  for (uint32_t i = 0; i < n_steps * 4; ++i) {
+    hipEvent_t ev;
+    const hipError_t e = hipEventCreate(&ev);
+    if (e != hipSuccess) {
+      for (hipEvent_t x : c->prof_ev) (void)hipEventDestroy(x);
+      c->prof_ev.clear();
+      return hip_fail(e, "hipEventCreate");
+    }
+    c->prof_ev.push_back(ev);
+  }
+  c->prof_cap = n_steps;
+  return BCT_OK;
+}
+
+bct_status bct_profile_read(bct_cache* c, uint32_t* n_recorded, float* ms_scores, float* ms_mv_pass,
+                            float* ms_merge) {
+  if (!c) return fail(BCT_ERR_INVALID_ARG, "cache handle is NULL");
+  double acc[3] = {0, 0, 0};
+  for (uint32_t i = 0; i < c->prof_n; ++i) {
+    hipEvent_t* ev = &c->prof_ev[(size_t)i * 4];
+    hipError_t e = hipEventSynchronize(ev[3]);
+    if (e != hipSuccess) return hip_fail(e, "hipEventSynchronize");
+    for (int k = 0; k < 3; ++k) {
+      float ms = 0.f;
+      if ((e = hipEventElapsedTime(&ms, ev[k], ev[k + 1])) != hipSuccess) return hip_fail(e, "hipEventElapsedTime");
+      acc[k] += ms;
+    }
+  }
+  const double n = c->prof_n ? (double)c->prof_n : 1.0;
+  if (n_recorded) *n_recorded = c->prof_n;
+  if (ms_scores) *ms_scores = (float)(acc[0] / n);
+  if (ms_mv_pass) *ms_mv_pass = (float)(acc[1] / n);
+  if (ms_merge) *ms_merge = (float)(acc[2] / n);
+  c->prof_n = 0;
+  return BCT_OK;
+}
+
+const char* bct_strerror(bct_status s) {
+  switch (s) {
+    case BCT_OK: return "ok";
+    case BCT_ERR_INVALID_ARG: return "invalid argument";
+    case BCT_ERR_UNSUPPORTED: return "unsupported shape, dtype or flag";
+    case BCT_ERR_BUFFER_TOO_SMALL: return "buffer too small";
+    case BCT_ERR_MISALIGNED: return "misaligned pointer";
+    case BCT_ERR_STATE: return "call out of order";
+    case BCT_ERR_HIP: return "HIP error";
+  }
+  return "unknown status";
+}
+
+const char* bct_last_error(void) { return g_err; }
+
+bct_status bct_stream_copy(void* dst, const void* src, size_t n_bytes, void* hip_stream) {
+  if (!dst || !src) return fail(BCT_ERR_INVALID_ARG, "dst or src is NULL");
+  if (n_bytes % 16 != 0) return fail(BCT_ERR_INVALID_ARG, "n_bytes must be a multiple of 16");
+  if (!aligned16(dst) || !aligned16(src)) return fail(BCT_ERR_MISALIGNED, "dst and src must be 16-byte aligned");
+  const hipError_t e = bct::launch_copy(dst, src, n_bytes, (hipStream_t)hip_stream);
+  if (e != hipSuccess) return hip_fail(e, "copy launch");
+  return BCT_OK;
+}
+
+}  // extern "C"

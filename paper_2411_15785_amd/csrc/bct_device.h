@@ -1,0 +1,114 @@
+// Device-side helpers of libbct: 16-byte vector access, storage-dtype
+// conversion and wavefront (64-lane) reductions for gfx950.
+#ifndef BCT_DEVICE_H
+#define BCT_DEVICE_H
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace bct {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+struct F32 {
+  typedef float elem;
+  static constexpr int kElemsPerVec = 4;  // elements in one 16-byte vector
+};
+struct BF16 {
+  typedef uint16_t elem;
+  static constexpr int kElemsPerVec = 8;
+};
+
+// 16 bytes of storage -> E floats (exact widening).
+template <typename DT>
+__device__ __forceinline__ void unpack16(const u32x4 v, float* f);
+
+template <>
+__device__ __forceinline__ void unpack16<F32>(const u32x4 v, float* f) {
+  f[0] = __uint_as_float(v.x);
+  f[1] = __uint_as_float(v.y);
+  f[2] = __uint_as_float(v.z);
+  f[3] = __uint_as_float(v.w);
+}
+template <>
+__device__ __forceinline__ void unpack16<BF16>(const u32x4 v, float* f) {
+  f[0] = __uint_as_float(v.x << 16);
+  f[1] = __uint_as_float(v.x & 0xFFFF0000u);
+  f[2] = __uint_as_float(v.y << 16);
+  f[3] = __uint_as_float(v.y & 0xFFFF0000u);
+  f[4] = __uint_as_float(v.z << 16);
+  f[5] = __uint_as_float(v.z & 0xFFFF0000u);
+  f[6] = __uint_as_float(v.w << 16);
+  f[7] = __uint_as_float(v.w & 0xFFFF0000u);
+}
+
+// Two floats -> two bf16 in one word, round-to-nearest-even (the hardware
+// conversion of gfx950: v_cvt_pk_bf16_f32).
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  bf16x2 r;
+  r.x = (__bf16)lo;
+  r.y = (__bf16)hi;
+  return __builtin_bit_cast(uint32_t, r);
+}
+
+// E floats -> 16 bytes of storage, rounding to the storage dtype; the floats
+// are overwritten with the stored (rounded) values so that a later read uses
+// exactly what the cache now holds.
+template <typename DT>
+__device__ __forceinline__ u32x4 pack16_round(float* f);
+
+template <>
+__device__ __forceinline__ u32x4 pack16_round<F32>(float* f) {
+  u32x4 v;
+  v.x = __float_as_uint(f[0]);
+  v.y = __float_as_uint(f[1]);
+  v.z = __float_as_uint(f[2]);
+  v.w = __float_as_uint(f[3]);
+  return v;
+}
+template <>
+__device__ __forceinline__ u32x4 pack16_round<BF16>(float* f) {
+  u32x4 v;
+  v.x = pack_bf16x2(f[0], f[1]);
+  v.y = pack_bf16x2(f[2], f[3]);
+  v.z = pack_bf16x2(f[4], f[5]);
+  v.w = pack_bf16x2(f[6], f[7]);
+  unpack16<BF16>(v, f);
+  return v;
+}
+
+// One float -> storage element (used by the small epilogues).
+__device__ __forceinline__ void store_elem(float* p, size_t i, float v) { p[i] = v; }
+__device__ __forceinline__ void store_elem(uint16_t* p, size_t i, float v) {
+  p[i] = __builtin_bit_cast(uint16_t, (__bf16)v);
+}
+__device__ __forceinline__ float load_elem(const float* p, size_t i) { return p[i]; }
+__device__ __forceinline__ float load_elem(const uint16_t* p, size_t i) {
+  return __uint_as_float((uint32_t)p[i] << 16);
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// Butterfly reductions over the lanes whose ids differ in the bits of `mask`
+// (a contiguous range of bits given as lowest and highest xor distance).
+// The butterfly visits partners in a fixed order, so results are reproducible.
+template <int LO, int HI>
+__device__ __forceinline__ float xor_sum(float v) {
+#pragma unroll
+  for (int o = LO; o <= HI; o <<= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+template <int LO, int HI>
+__device__ __forceinline__ float xor_max(float v) {
+#pragma unroll
+  for (int o = LO; o <= HI; o <<= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+}  // namespace bct
+
+#endif

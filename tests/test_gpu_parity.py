@@ -1,0 +1,230 @@
+"""GPU parity: libbct (through its C ABI) against the CPU oracle, element by
+element on the same seeded inputs.  Tolerances: fp32 out <= 1e-5 (max over
+vectors of max|diff| / max|ref|); bf16 out <= 2e-2 absolute; stored bf16 state
+within 1 ulp of the oracle's after one step from a common state; MK, step
+counters, sizes and hard-addressed slots bit-exact.
+"""
+import math
+
+import numpy as np
+import pytest
+
+import bct_synth as syn
+from _util import bf16_ulp, f64, make_pair, rel_normwise, sub, to_dev, to_np, torch_dtype
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def P():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    import paper_2411_15785_amd as pkg
+    pkg.lib()  # fails loudly if libbct.so is missing
+    return pkg
+
+
+@pytest.fixture(scope="module")
+def R():
+    from oracle import bct_ref
+    return bct_ref
+
+
+def check_out(got, ref, dtype, what=""):
+    g, r = f64(got, dtype), f64(ref, dtype)
+    assert np.all(np.isfinite(g)), what
+    if dtype == "f32":
+        e = rel_normwise(g, r)
+        assert e <= 1e-5, f"{what}: fp32 out rel err {e:.3e}"
+    else:
+        e = float(np.max(np.abs(g - r)))
+        assert e <= 2e-2, f"{what}: bf16 out abs err {e:.3e}"
+        # far tighter in practice: within two bf16 ulps of the vector's largest entry
+        tight = np.max(np.abs(g - r), axis=-1) / bf16_ulp(np.max(np.abs(r), axis=-1))
+        assert np.max(tight) <= 2.0, f"{what}: bf16 out {np.max(tight):.2f} ulp of the vector max"
+    return e
+
+
+def check_state_one_step(got, ref, dtype, what=""):
+    """State after ONE step from a common state: the two sides differ only where the
+    fp32 write weight differs in its last bits, i.e. rare flips of one rounding."""
+    g, r = f64(got, dtype), f64(ref, dtype)
+    if dtype == "f32":
+        e = float(np.max(np.abs(g - r)) / max(np.max(np.abs(r)), 1e-30))
+        assert e <= 1e-5, f"{what}: fp32 state rel err {e:.3e}"
+        return
+    d = np.abs(g - r)
+    ulp = bf16_ulp(r)
+    assert np.all(d <= ulp * 1.0001), f"{what}: bf16 state off by {np.max(d / ulp):.2f} ulp"
+    frac = float(np.mean(d > 0))
+    assert frac <= 5e-3, f"{what}: {frac:.2e} of the state elements differ"
+
+
+def step_np(w, t, layer=0):
+    return syn.make_step(w, t, layer)
+
+
+def run_lockstep(w, ref, gpu, bs, steps, t0=0, every_state=0, what=""):
+    worst = 0.0
+    for t in range(t0, t0 + steps):
+        q, wq, wv = step_np(w, t)
+        o_ref = ref.decode_step(sub(q, bs), sub(wq, bs), sub(wv, bs))
+        o_gpu = gpu.decode_step(to_dev(q, w.dtype), to_dev(wq, w.dtype), to_dev(wv, w.dtype))
+        worst = max(worst, check_out(to_np(o_gpu, w.dtype)[bs], o_ref, w.dtype, f"{what} step {t}"))
+    return worst
+
+
+# ------------------------------------------------------------------ config 1 (fp32, whole run)
+
+def test_cfg1_fp32_all_256_steps(P, R):
+    w = syn.WORKLOADS["cfg1"]
+    ref, gpu, mk, _, bs = make_pair(w, R.RefCache, P.BctCache)
+    assert gpu.cache_bytes >= ref.cache_bytes()
+    run_lockstep(w, ref, gpu, bs, w.decode_steps, what="cfg1")
+    mk_g, mv_g, st = gpu.export()
+    assert st == w.decode_steps == ref.steps
+    assert np.array_equal(to_np(mk_g, w.dtype), mk)          # MK bit-exact, never written
+    mv_r = ref.values()
+    e = np.max(np.abs(to_np(mv_g, w.dtype).astype(np.float64) - mv_r)) / np.max(np.abs(mv_r))
+    assert e <= 1e-5, f"cfg1 state rel err {e:.3e}"
+
+
+# ------------------------------------------------------------------ single step from a common state, all variants
+
+SMALL = [
+    # name, B, Hq, Hkv, d, M, dtype
+    ("f32_d64", 2, 4, 4, 64, 128, "f32"),
+    ("f32_d128_gqa2", 2, 4, 2, 128, 192, "f32"),
+    ("bf16_d128", 3, 4, 4, 128, 256, "bf16"),
+    ("bf16_d128_gqa4", 2, 8, 2, 128, 320, "bf16"),
+    ("bf16_d64_gqa8", 1, 8, 1, 64, 128, "bf16"),
+    ("bf16_d128_gqa3", 2, 6, 2, 128, 64, "bf16"),
+    ("f32_d64_gqa5", 1, 5, 1, 64, 64, "f32"),
+    ("bf16_d128_m2112", 2, 2, 2, 128, 2112, "bf16"),   # 33 chunks of 64: ragged split of the MV pass
+]
+
+
+@pytest.mark.parametrize("name,B,Hq,Hkv,d,M,dtype", SMALL)
+@pytest.mark.parametrize("mode", ["rw", "write_only", "read_only"])
+@pytest.mark.parametrize("flags", [0, 1])
+def test_one_step_from_common_state(P, R, name, B, Hq, Hkv, d, M, dtype, mode, flags):
+    w = syn.Workload(name, 1, B, Hq, Hkv, d, M, dtype, 4)
+    ref, gpu, mk, mv0, bs = make_pair(w, R.RefCache, P.BctCache, flags=flags, mv0=True)
+    for t in range(3):
+        q, wq, wv = step_np(w, t)
+        if mode == "write_only":
+            q = None
+        if mode == "read_only":
+            wq = wv = None
+        # resynchronise: both sides start the step from the oracle's state
+        gpu.set_values(to_dev(ref.values(), dtype))
+        o_ref = ref.decode_step(q, wq, wv)
+        o_gpu = gpu.decode_step(to_dev(q, dtype), to_dev(wq, dtype), to_dev(wv, dtype))
+        if mode != "write_only":
+            check_out(to_np(o_gpu, dtype), o_ref, dtype, f"{name}/{mode} step {t}")
+        else:
+            assert o_gpu is None and o_ref is None
+        mk_g, mv_g, st = gpu.export()
+        assert np.array_equal(to_np(mk_g, dtype), mk)
+        if mode == "read_only":
+            assert np.array_equal(to_np(mv_g, dtype), ref.values())   # untouched, bit for bit
+        else:
+            check_state_one_step(to_np(mv_g, dtype), ref.values(), dtype, f"{name}/{mode} step {t}")
+        assert st == t + 1
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_write_scale_one_is_algorithm_1_as_printed(P, R, dtype):
+    w = syn.Workload("ws1", 1, 2, 2, 2, 64, 128, dtype, 4)
+    ref, gpu, _, _, bs = make_pair(w, R.RefCache, P.BctCache, write_scale=1.0, read_scale=0.2)
+    for t in range(3):
+        q, wq, wv = step_np(w, t)
+        gpu.set_values(to_dev(ref.values(), dtype))
+        o_ref = ref.decode_step(q, wq, wv)
+        o_gpu = gpu.decode_step(to_dev(q, dtype), to_dev(wq, dtype), to_dev(wv, dtype))
+        check_out(to_np(o_gpu, dtype), o_ref, dtype, f"ws1 step {t}")
+        check_state_one_step(to_np(gpu.export()[1], dtype), ref.values(), dtype, f"ws1 step {t}")
+
+
+# ------------------------------------------------------------------ hard addressing: slots and indexing bit-exact
+
+@pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 128)])
+def test_hard_addressing_writes_exactly_one_slot(P, R, dtype, d):
+    M, B, Hq, Hkv = 64, 2, 4, 2
+    w = syn.Workload("hard", 1, B, Hq, Hkv, d, M, dtype, M)
+    ref, gpu, mk, _, bs = make_pair(w, R.RefCache, P.BctCache, write_scale=1.0)
+    K = f64(mk, dtype)
+    order = np.random.default_rng(3).permutation(M)
+    for t in range(M):
+        wq64 = np.empty((B, Hkv, d))
+        for h in range(Hkv):
+            s = K[h] @ K[h, order[t]]
+            gap = s[order[t]] - np.max(np.delete(s, order[t]))
+            assert gap > 1.0
+            wq64[:, h] = K[h, order[t]] * (300.0 / gap)
+        wq = syn.pack(wq64, dtype)
+        for h in range(Hkv):   # still separated by > 200 after rounding the query
+            s = K[h] @ f64(wq[0, h], dtype)
+            assert s[order[t]] - np.max(np.delete(s, order[t])) > 200.0
+        q, _, wv = step_np(w, t)
+        before = to_np(gpu.export()[1], dtype)
+        o_gpu = gpu.decode_step(to_dev(q, dtype), to_dev(wq, dtype), to_dev(wv, dtype))
+        o_ref = ref.decode_step(q, wq, wv)
+        after = to_np(gpu.export()[1], dtype)
+        others = np.delete(np.arange(M), order[t])
+        assert np.array_equal(after[:, :, order[t], :], wv)                   # the slot holds wv_t bit for bit
+        assert np.array_equal(after[:, :, others, :], before[:, :, others, :])  # nothing else moved
+        assert np.array_equal(after, ref.values())                            # whole state bit-exact
+        check_out(to_np(o_gpu, dtype), o_ref, dtype, f"hard step {t}")
+
+
+# ------------------------------------------------------------------ determinism, checkpoint, capacity
+
+def test_determinism_and_checkpoint_roundtrip(P, R):
+    import torch
+    w = syn.Workload("det", 1, 4, 8, 4, 128, 1024, "bf16", 8)
+    outs, states = [], []
+    for rep in range(2):
+        _, gpu, _, _, _ = make_pair(w, R.RefCache, P.BctCache, mv0=True)
+        o = []
+        for t in range(6):
+            q, wq, wv = step_np(w, t)
+            o.append(to_np(gpu.decode_step(to_dev(q, w.dtype), to_dev(wq, w.dtype), to_dev(wv, w.dtype)), w.dtype))
+            if rep == 1 and t == 2:   # checkpoint after step 3, restore into a fresh cache, continue there
+                mk_c, mv_c, st_c = gpu.export()
+                gpu2 = P.BctCache(w.M, w.B, w.Hq, w.Hkv, w.d, torch_dtype(w.dtype), w.scale, w.scale)
+                gpu2.import_(mk_c, mv_c, st_c)
+                gpu = gpu2
+        outs.append(np.stack(o))
+        states.append(to_np(gpu.export()[1], w.dtype))
+        assert gpu.steps == 6
+    assert np.array_equal(outs[0], outs[1])
+    assert np.array_equal(states[0], states[1])
+
+
+def test_capacity_is_constant_and_errors_are_reported(P, R):
+    import ctypes
+    import torch
+    w = syn.Workload("cap", 1, 2, 2, 2, 64, 64, "f32", 8)
+    gpu = P.BctCache(w.M, w.B, w.Hq, w.Hkv, w.d, torch.float32)
+    L = P.lib()
+    q, wq, wv = (to_dev(a, "f32") for a in step_np(w, 0))
+    out = torch.empty_like(q)
+    s = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    p = lambda t: ctypes.c_void_p(t.data_ptr())
+    assert L.bct_decode_step(gpu._h, p(q), p(wq), p(wv), p(out), s) == P.BCT_ERR_STATE   # keys not set
+    gpu.set_keys(to_dev(syn.make_keys(w), "f32"))
+    assert L.bct_decode_step(gpu._h, p(q), p(wq), None, p(out), s) == P.BCT_ERR_INVALID_ARG
+    assert L.bct_decode_step(gpu._h, p(q), None, None, None, s) == P.BCT_ERR_INVALID_ARG
+    assert L.bct_decode_step(gpu._h, None, None, None, None, s) == P.BCT_ERR_INVALID_ARG
+    assert L.bct_decode_step(None, p(q), p(wq), p(wv), p(out), s) == P.BCT_ERR_INVALID_ARG
+    mis = ctypes.c_void_p(q.data_ptr() + 4)
+    assert L.bct_decode_step(gpu._h, mis, p(wq), p(wv), p(out), s) == P.BCT_ERR_MISALIGNED
+    assert gpu.steps == 0                                   # failed calls do not count
+    free0 = torch.cuda.memory_allocated()
+    for t in range(3 * w.M):                                # far past the capacity
+        gpu.decode_step(q, wq, wv, out)
+    torch.cuda.synchronize()
+    assert torch.cuda.memory_allocated() == free0           # no growth, no allocation in the step
+    assert gpu.steps == 3 * w.M
+    assert torch.isfinite(out).all()
