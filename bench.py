@@ -149,7 +149,7 @@ def main():
         "config": {"workload": f"{w.name}: {L} layers x (B={w.B}, Hq={w.Hq}, Hkv={w.Hkv}, d={w.d}, M={w.M}, "
                                f"{w.dtype}), one decode step per layer per token, attention + cache update only",
                    "layers": L, "batch": w.B, "capacity_M": w.M},
-        "roofline": {"bound": "hbm", "kernel": "stream_kernel (MV pass)",
+        "roofline": {"bound": "hbm", "kernel": "mv_pass_kernel",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": (achieved / HBM_PEAK_GBS) if achieved else None, "traffic": traffic,
                      "bytes_per_launch": mv_pass_bytes, "ms_per_launch": ms_mv, "launches_timed": n_rec},

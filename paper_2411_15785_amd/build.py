@@ -21,6 +21,7 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-command-line-argument", "-I", os.path.join(ROOT, "include")]
+FLAGS += os.environ.get("BCT_EXTRA_HIPCC_FLAGS", "").split()
 
 
 def _compile(src: str, verbose: bool) -> str:

@@ -21,7 +21,7 @@ struct bct_cache {
   char* ws;
   size_t ws_bytes;
   // workspace carve-up (byte offsets)
-  size_t off_scores, off_stats, off_partial, off_prefill;
+  size_t off_scores, off_stats, off_norm, off_partial, off_prefill;
   uint64_t steps;
   bool keys_set;
   bct::DecodeParams plan;  // shape, strides and launch plan; pointers filled per call
@@ -76,7 +76,7 @@ bct_status check_desc(const bct_cache_desc* d) {
 
 struct Sizes {
   size_t mk_bytes, mv_bytes, cache_bytes;
-  size_t off_scores, off_stats, off_partial, off_prefill, ws_bytes;
+  size_t off_scores, off_stats, off_norm, off_partial, off_prefill, ws_bytes;
 };
 
 void fill_plan(const bct_cache_desc* d, bct::DecodeParams& p) {
@@ -114,6 +114,8 @@ Sizes compute_sizes(const bct_cache_desc* d, uint32_t max_T) {
   off += align_up(units * rows * p.M * sizeof(float), 256);
   z.off_stats = off;
   off += align_up(units * rows * (p.M / bct::kMinStatTile) * sizeof(float2), 256);
+  z.off_norm = off;
+  off += align_up(units * rows * sizeof(float2), 256);
   z.off_partial = off;
   off += align_up((size_t)p.S * d->batch * d->n_q_heads * d->head_dim * sizeof(float), 256);
   z.off_prefill = off;
@@ -148,6 +150,7 @@ bct_status run_decode(bct_cache* c, const void* q, const void* k_new, const void
   p.out = out;
   p.scores = (float*)(c->ws + c->off_scores);
   p.stats = (float2*)(c->ws + c->off_stats);
+  p.norm = (float2*)(c->ws + c->off_norm);
   p.partial = (float*)(c->ws + c->off_partial);
   p.has_write = k_new ? 1u : 0u;
   p.has_read = q ? 1u : 0u;
@@ -158,6 +161,7 @@ bct_status run_decode(bct_cache* c, const void* q, const void* k_new, const void
   hipEvent_t* ev = (c->prof_n < c->prof_cap) ? &c->prof_ev[(size_t)c->prof_n * 4] : nullptr;
   if (ev && (e = hipEventRecord(ev[0], s)) != hipSuccess) return hip_fail(e, "event record");
   if ((e = bct::launch_scores(p, c->desc.dtype, s)) != hipSuccess) return hip_fail(e, "scores launch");
+  if ((e = bct::launch_normalise(p, s)) != hipSuccess) return hip_fail(e, "normaliser launch");
   if (ev && (e = hipEventRecord(ev[1], s)) != hipSuccess) return hip_fail(e, "event record");
   if ((e = bct::launch_stream(p, c->desc.dtype, s)) != hipSuccess) return hip_fail(e, "MV pass launch");
   if (ev && (e = hipEventRecord(ev[2], s)) != hipSuccess) return hip_fail(e, "event record");
@@ -209,6 +213,7 @@ bct_status bct_cache_init(const bct_cache_desc* desc, uint32_t max_prefill_T, vo
   c->ws_bytes = z.ws_bytes;
   c->off_scores = z.off_scores;
   c->off_stats = z.off_stats;
+  c->off_norm = z.off_norm;
   c->off_partial = z.off_partial;
   c->off_prefill = z.off_prefill;
   c->steps = 0;

@@ -1,18 +1,20 @@
 // Decode-step kernels of libbct (gfx950).
 //
-// One decode step of one layer is three launches on the caller's stream:
+// One decode step of one layer is four launches on the caller's stream:
 //   1. scores : for every memory (b, h) and every row (the write query wq and
 //               the G read queries q), the scaled dot products with all M keys
 //               of MK, kept in the log2 domain, plus one (max, sum) pair per
 //               slot tile.  (section 3.2 step 2 / Algorithm 1 "score"; the same
 //               pass serves the read.)
-//   2. stream : merges the (max, sum) pairs into the softmax normaliser, then
-//               makes ONE pass over MV: load, ww[m] * wv + MV (one fp32 FMA),
+//   2. normalise : merges the (max, sum) pairs into each row's softmax
+//               normaliser (a few microseconds; it keeps that dependent chain
+//               out of every workgroup of the next launch).
+//   3. MV pass : ONE pass over MV: load, ww[m] * wv + MV (one fp32 FMA),
 //               round to storage, store, and accumulate the read output from
 //               the value just stored.  (section 3.2 steps 2, 4, 5; section 3.4
 //               equation.)  The normaliser must be known before any slot can be
 //               written, which is why this is a second launch.
-//   3. merge  : sums the split-M partial outputs in a fixed order (only if the
+//   4. merge  : sums the split-M partial outputs in a fixed order (only if the
 //               MV pass was split).
 #include "bct_device.h"
 #include "bct_internal.h"
@@ -79,11 +81,14 @@ __global__ __launch_bounds__(256) void scores_generic_kernel(const DecodeParams 
 // ------------------------------------------------------------------ scores (bf16, shared keys, MFMA)
 
 // With keys shared over the batch the scores of one KV head are a dense
-// contraction: [B*R rows] x [d] x [M slots].  One wavefront owns 32*NT slots,
+// contraction: [M slots] x [d] x [B*R rows].  One wavefront owns 32*NT slots,
 // keeps their key fragments in registers and walks the rows 32 at a time with
-// v_mfma_f32_32x32x16_bf16 (A = query rows, B = key slots, fp32 accumulate).
-// Lane l supplies row/slot (l % 32) and the 8 consecutive k at 8 * (l / 32);
-// the accumulator holds column (l % 32), rows 8*(v/4) + 4*(l/32) + v%4.
+// v_mfma_f32_32x32x16_bf16 (A = key slots, B = query rows, fp32 accumulate).
+// Lane l supplies slot/row (l % 32) and the 8 consecutive k at 8 * (l / 32).
+// The accumulator of lane l holds query row (l % 32) and the slots
+// 8*(v/4) + 4*(l/32) + v%4, v = 0..15: all slots of a row sit in two lanes, so
+// the per-tile (max, sum) of a row is an in-lane reduction plus one exchange,
+// and four consecutive slots go out as one 16-byte store.
 template <int D, int NT>
 __global__ __launch_bounds__(64) void scores_mfma_bf16_kernel(const DecodeParams p) {
   constexpr int KS = D / 16;
@@ -101,10 +106,13 @@ __global__ __launch_bounds__(64) void scores_mfma_bf16_kernel(const DecodeParams
 
   const uint32_t rtot = p.B * p.R;
   for (uint32_t rb = blockIdx.z; rb * 32 < rtot; rb += gridDim.z) {
-    const uint32_t rho = rb * 32 + col;
+    const uint32_t rho = rb * 32 + col;   // this lane's query row
+    const bool valid = rho < rtot;
+    uint32_t b = 0, r = 0;
     u32x4 xf[KS];
-    if (rho < rtot) {
-      const uint32_t b = rho / p.R, r = rho % p.R;
+    if (valid) {
+      b = rho / p.R;
+      r = rho % p.R;
       const uint16_t* x = (p.has_write && r == 0)
                               ? (const uint16_t*)p.wq + (size_t)b * p.kv_bstride + (size_t)h * D
                               : (const uint16_t*)p.q + (size_t)b * p.q_bstride +
@@ -124,173 +132,84 @@ __global__ __launch_bounds__(64) void scores_mfma_bf16_kernel(const DecodeParams
     for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
       for (int t = 0; t < NT; ++t)
-        c[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xf[ks]),
-                                                       __builtin_bit_cast(bf16x8, kf[t][ks]), c[t], 0, 0, 0);
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const uint32_t row = rb * 32 + (v / 4) * 8 + half * 4 + (v % 4);
-      if (row < rtot) {
-        const uint32_t b = row / p.R, r = row % p.R;
-        const float scale = (p.has_write && r == 0) ? p.wscale_l2e : p.rscale_l2e;
-        const size_t urow = (size_t)(b * p.Hkv + h) * p.R + r;
-        float s[NT];
-        float mx = -INFINITY;
-#pragma unroll
-        for (int t = 0; t < NT; ++t) {
-          s[t] = c[t][v] * scale;
-          p.scores[urow * p.M + slot0 + t * 32 + col] = s[t];
-          mx = fmaxf(mx, s[t]);
-        }
-        mx = xor_max<1, 16>(mx);
-        float sm = 0.f;
-#pragma unroll
-        for (int t = 0; t < NT; ++t) sm += fast_exp2(s[t] - mx);
-        sm = xor_sum<1, 16>(sm);
-        if (col == 0) p.stats[urow * p.n_tiles + tile] = make_float2(mx, sm);
-      }
-    }
-  }
-}
-
-// ------------------------------------------------------------------ MV pass
-
-// One workgroup = one (split, memory).  LPS lanes hold one slot row (16 bytes
-// each); a wavefront covers 64/LPS slots per load and U loads per iteration,
-// four wavefronts cover kStreamChunk = 64 slots per iteration.
-template <typename DT, int D, int GT, bool WRITE, bool READ>
-__global__ __launch_bounds__(256) void stream_kernel(const DecodeParams p) {
-  typedef typename DT::elem elem;
-  constexpr int E = DT::kElemsPerVec;
-  constexpr int LPS = D / E;
-  constexpr int SPW = 64 / LPS;  // slots per wavefront per load
-  constexpr int U = LPS / 4;     // loads per lane per iteration
-  static_assert(4 * SPW * U == (int)kStreamChunk, "a workgroup iteration covers 64 slots");
-
-  __shared__ float s_gmax[kMaxRows], s_ginv[kMaxRows];
-  __shared__ float s_red[READ ? 4 * GT * D : 1];
-
-  const uint32_t split = blockIdx.x, unit = blockIdx.y;
-  const uint32_t b = unit / p.Hkv, h = unit % p.Hkv;
-  const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
-  const int sub = lane % LPS, sl = lane / LPS;
-  const uint32_t R = p.R, G = p.G, M = p.M;
-
-  // softmax normalisers: merge the per-tile (max, sum) pairs of each row
-  for (uint32_t r = wave; r < R; r += 4) {
-    const float2* st = p.stats + ((size_t)unit * R + r) * p.n_tiles;
+        c[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[t][ks]),
+                                                       __builtin_bit_cast(bf16x8, xf[ks]), c[t], 0, 0, 0);
+    const float scale = (p.has_write && r == 0) ? p.wscale_l2e : p.rscale_l2e;
+    const size_t urow = (size_t)(b * p.Hkv + h) * p.R + r;
+    float* dst = p.scores + urow * p.M + slot0 + half * 4;
     float mx = -INFINITY;
-    for (uint32_t i = lane; i < p.n_tiles; i += 64) mx = fmaxf(mx, st[i].x);
-    mx = xor_max<1, 32>(mx);
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        c[t][v] *= scale;
+        mx = fmaxf(mx, c[t][v]);
+      }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     float sm = 0.f;
-    for (uint32_t i = lane; i < p.n_tiles; i += 64) sm += st[i].y * fast_exp2(st[i].x - mx);
-    sm = xor_sum<1, 32>(sm);
-    if (lane == 0) {
-      s_gmax[r] = mx;
-      s_ginv[r] = 1.0f / sm;
-    }
-  }
-  __syncthreads();
-
-  float w_max = 0.f, w_inv = 0.f, r_max[GT], r_inv[GT];
-  if (WRITE) {
-    w_max = s_gmax[0];
-    w_inv = s_ginv[0];
-  }
 #pragma unroll
-  for (int g = 0; g < GT; ++g) {
-    const bool on = READ && (uint32_t)g < G;
-    r_max[g] = on ? s_gmax[(WRITE ? 1 : 0) + g] : 0.f;
-    r_inv[g] = on ? s_ginv[(WRITE ? 1 : 0) + g] : 0.f;
-  }
-
-  float wvf[E];
-  if (WRITE) {
-    const elem* wv = (const elem*)p.wv + (size_t)b * p.kv_bstride + (size_t)h * D;
-    unpack16<DT>(*(const u32x4*)(wv + sub * E), wvf);
-  }
-  float acc[GT][E];
+    for (int t = 0; t < NT; ++t)
 #pragma unroll
-  for (int g = 0; g < GT; ++g)
+      for (int v = 0; v < 16; ++v) sm += fast_exp2(c[t][v] - mx);
+    sm += __shfl_xor(sm, 32, 64);
+    if (valid) {
 #pragma unroll
-    for (int e = 0; e < E; ++e) acc[g][e] = 0.f;
-
-  elem* mv = (elem*)p.mv + (size_t)unit * M * D;
-  const float* sc_w = p.scores + (size_t)unit * R * M;            // row 0 when WRITE
-  const float* sc_r = sc_w + (WRITE ? (size_t)M : 0);             // read rows follow
-  const uint32_t chunks = M / kStreamChunk;
-  const uint32_t c0 = (uint32_t)(((uint64_t)chunks * split) / p.S);
-  const uint32_t c1 = (uint32_t)(((uint64_t)chunks * (split + 1)) / p.S);
-
-  for (uint32_t c = c0; c < c1; ++c) {
-    const uint32_t base = c * kStreamChunk + wave * (SPW * U) + sl;
-    u32x4 raw[U];
+      for (int t = 0; t < NT; ++t)
 #pragma unroll
-    for (int u = 0; u < U; ++u)
-      raw[u] = __builtin_nontemporal_load((const u32x4*)(mv + (size_t)(base + u * SPW) * D + sub * E));
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const uint32_t slot = base + u * SPW;
-      float x[E];
-      unpack16<DT>(raw[u], x);
-      if (WRITE) {
-        const float ww = fast_exp2(sc_w[slot] - w_max) * w_inv;
-#pragma unroll
-        for (int e = 0; e < E; ++e) x[e] = __builtin_fmaf(ww, wvf[e], x[e]);
-        const u32x4 st = pack16_round<DT>(x);
-        __builtin_nontemporal_store(st, (u32x4*)(mv + (size_t)slot * D + sub * E));
-      }
-      if (READ) {
-#pragma unroll
-        for (int g = 0; g < GT; ++g) {
-          if ((uint32_t)g < G) {
-            const float rw = fast_exp2(sc_r[(size_t)g * M + slot] - r_max[g]) * r_inv[g];
-#pragma unroll
-            for (int e = 0; e < E; ++e) acc[g][e] = __builtin_fmaf(rw, x[e], acc[g][e]);
-          }
+        for (int q4 = 0; q4 < 4; ++q4) {
+          const f32x4 o = {c[t][q4 * 4 + 0], c[t][q4 * 4 + 1], c[t][q4 * 4 + 2], c[t][q4 * 4 + 3]};
+          *(f32x4*)(dst + t * 32 + q4 * 8) = o;
         }
-      }
-    }
-  }
-
-  if (READ) {
-    // lanes with the same column chunk `sub` across the wavefront's slot groups
-#pragma unroll
-    for (int g = 0; g < GT; ++g)
-#pragma unroll
-      for (int e = 0; e < E; ++e) acc[g][e] = xor_sum<LPS, 32>(acc[g][e]);
-    if (sl == 0) {
-#pragma unroll
-      for (int g = 0; g < GT; ++g)
-#pragma unroll
-        for (int e = 0; e < E; ++e) s_red[(wave * GT + g) * D + sub * E + e] = acc[g][e];
-    }
-    __syncthreads();
-    for (uint32_t i = tid; i < G * D; i += 256) {
-      const uint32_t g = i / D, j = i % D;
-      float v = 0.f;
-#pragma unroll
-      for (int w = 0; w < 4; ++w) v += s_red[(w * GT + g) * D + j];
-      const uint32_t hq = h * G + g;
-      if (p.S == 1) {
-        store_elem((elem*)p.out, (size_t)b * p.q_bstride + (size_t)hq * D + j, v);
-      } else {
-        p.partial[(((size_t)split * p.B + b) * p.Hq + hq) * D + j] = v;
-      }
+      if (half == 0) p.stats[urow * p.n_tiles + tile] = make_float2(mx, sm);
     }
   }
 }
 
-// out[b][hq][:] = round(sum over splits, ascending) of the partial outputs.
+// Softmax normalisers: one wavefront per (memory, row) merges the per-tile
+// (max, sum) pairs into the row's (max, 1 / sum of exp2(score - max)).
+__global__ __launch_bounds__(256) void normalise_kernel(const DecodeParams p) {
+  const uint32_t row = blockIdx.x * 4 + threadIdx.x / 64, lane = threadIdx.x % 64;
+  if (row >= p.B * p.Hkv * p.R) return;
+  const float2* st = p.stats + (size_t)row * p.n_tiles;
+  float mx = -INFINITY;
+  for (uint32_t i = lane; i < p.n_tiles; i += 64) mx = fmaxf(mx, st[i].x);
+  mx = xor_max<1, 32>(mx);
+  float sm = 0.f;
+  for (uint32_t i = lane; i < p.n_tiles; i += 64) sm += st[i].y * fast_exp2(st[i].x - mx);
+  sm = xor_sum<1, 32>(sm);
+  if (lane == 0) p.norm[row] = make_float2(mx, 1.0f / sm);
+}
+
+// out[b][hq][:] = round(sum over the S split-M partial outputs).  A workgroup
+// covers 128 consecutive output elements: 8 groups of 32 lanes, each lane four
+// elements (one 16-byte load per split); group k sums splits k, k+8, ... and
+// the eight group sums are added in group order, so the result does not depend
+// on timing.
 template <typename DT>
 __global__ __launch_bounds__(256) void merge_kernel(const DecodeParams p) {
   typedef typename DT::elem elem;
+  __shared__ f32x4 s_part[8][32];
   const size_t n = (size_t)p.B * p.Hq * p.d;
-  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-  if (i >= n) return;
-  float v = 0.f;
-  for (uint32_t s = 0; s < p.S; ++s) v += p.partial[(size_t)s * n + i];
-  const size_t per_b = (size_t)p.Hq * p.d;
-  store_elem((elem*)p.out, (i / per_b) * p.q_bstride + (i % per_b), v);
+  const int grp = threadIdx.x / 32, ln = threadIdx.x % 32;
+  const size_t i = ((size_t)blockIdx.x * 32 + ln) * 4;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  if (i < n) {
+#pragma unroll 4
+    for (uint32_t s = grp; s < p.S; s += 8) acc += *(const f32x4*)(p.partial + (size_t)s * n + i);
+  }
+  s_part[grp][ln] = acc;
+  __syncthreads();
+  if (grp == 0 && i < n) {
+    f32x4 v = s_part[0][ln];
+#pragma unroll
+    for (int k = 1; k < 8; ++k) v += s_part[k][ln];
+    const size_t per_b = (size_t)p.Hq * p.d;
+    const size_t o = (i / per_b) * p.q_bstride + (i % per_b);
+    store_elem((elem*)p.out, o + 0, v.x);
+    store_elem((elem*)p.out, o + 1, v.y);
+    store_elem((elem*)p.out, o + 2, v.z);
+    store_elem((elem*)p.out, o + 3, v.w);
+  }
 }
 
 // ------------------------------------------------------------------ fill / copy
@@ -313,8 +232,9 @@ static bool use_mfma_scores(const DecodeParams& p, int dtype) { return dtype == 
 
 void plan_decode(DecodeParams& p, int dtype) {
   if (use_mfma_scores(p, dtype)) {
-    // the largest slot tile per wavefront that still gives about one
-    // wavefront per SIMD (1024 on the chip)
+    // the largest slot tile per wavefront that still gives one wavefront per
+    // SIMD (1024 on the chip); measured at H=32, M=4096, 64 rows: 128 slots
+    // 19 us, 64 slots 21 us, 32 slots 26 us (two launches' overhead included)
     uint32_t nt = 1;
     if (p.M % 128 == 0 && (uint64_t)(p.M / 128) * p.Hkv >= 1024) nt = 4;
     else if ((uint64_t)(p.M / 64) * p.Hkv >= 1024) nt = 2;
@@ -323,15 +243,7 @@ void plan_decode(DecodeParams& p, int dtype) {
     p.stat_tile = 64;
   }
   p.n_tiles = p.M / p.stat_tile;
-  const uint32_t units = p.B * p.Hkv;
-  const uint32_t chunks = p.M / kStreamChunk;
-  uint32_t s = (2048 + units - 1) / units;
-  uint32_t smax = chunks / 4;
-  if (smax < 1) smax = 1;
-  if (s > smax) s = smax;
-  if (s > kMaxSplits) s = kMaxSplits;
-  if (s < 1) s = 1;
-  p.S = s;
+  plan_mv_pass(p, dtype);
 }
 
 template <int D, int NT>
@@ -340,7 +252,7 @@ static hipError_t launch_scores_mfma(const DecodeParams& p, hipStream_t s) {
   const uint32_t rbs = (p.B * p.R + 31) / 32;
   uint32_t z = 1;
   const uint64_t waves = (uint64_t)tiles * p.Hkv;
-  if (waves < 2048) z = (uint32_t)((2048 + waves - 1) / waves);
+  if (waves < 1024) z = (uint32_t)((1024 + waves - 1) / waves);
   if (z > rbs) z = rbs;
   hipLaunchKernelGGL((scores_mfma_bf16_kernel<D, NT>), dim3(tiles, p.Hkv, z), dim3(64), 0, s, p);
   return hipGetLastError();
@@ -369,37 +281,16 @@ hipError_t launch_scores(const DecodeParams& p, int dtype, hipStream_t s) {
   return hipGetLastError();
 }
 
-template <typename DT, int D, int GT>
-static void launch_stream_mode(const DecodeParams& p, hipStream_t s) {
-  const dim3 grid(p.S, p.B * p.Hkv), block(256);
-  if (p.has_write && p.has_read) hipLaunchKernelGGL((stream_kernel<DT, D, GT, true, true>), grid, block, 0, s, p);
-  else if (p.has_read) hipLaunchKernelGGL((stream_kernel<DT, D, GT, false, true>), grid, block, 0, s, p);
-  else hipLaunchKernelGGL((stream_kernel<DT, D, 1, true, false>), grid, block, 0, s, p);
-}
-
-template <typename DT, int D>
-static void launch_stream_g(const DecodeParams& p, hipStream_t s) {
-  if (p.G <= 1) launch_stream_mode<DT, D, 1>(p, s);
-  else if (p.G <= 2) launch_stream_mode<DT, D, 2>(p, s);
-  else if (p.G <= 4) launch_stream_mode<DT, D, 4>(p, s);
-  else launch_stream_mode<DT, D, 8>(p, s);
-}
-
-hipError_t launch_stream(const DecodeParams& p, int dtype, hipStream_t s) {
-  if (dtype == 0) {
-    if (p.d == 128) launch_stream_g<F32, 128>(p, s);
-    else launch_stream_g<F32, 64>(p, s);
-  } else {
-    if (p.d == 128) launch_stream_g<BF16, 128>(p, s);
-    else launch_stream_g<BF16, 64>(p, s);
-  }
+hipError_t launch_normalise(const DecodeParams& p, hipStream_t s) {
+  const uint32_t rows = p.B * p.Hkv * p.R;
+  hipLaunchKernelGGL(normalise_kernel, dim3((rows + 3) / 4), dim3(256), 0, s, p);
   return hipGetLastError();
 }
 
 hipError_t launch_merge(const DecodeParams& p, int dtype, hipStream_t s) {
   if (!p.has_read || p.S == 1) return hipSuccess;
   const size_t n = (size_t)p.B * p.Hq * p.d;
-  const dim3 grid((unsigned)((n + 255) / 256)), block(256);
+  const dim3 grid((unsigned)((n + 127) / 128)), block(256);
   if (dtype == 0) hipLaunchKernelGGL((merge_kernel<F32>), grid, block, 0, s, p);
   else hipLaunchKernelGGL((merge_kernel<BF16>), grid, block, 0, s, p);
   return hipGetLastError();

@@ -11,11 +11,9 @@ namespace bct {
 
 constexpr uint32_t kMaxG = 8;          // query heads per KV head
 constexpr uint32_t kMaxRows = 1 + kMaxG;  // score rows per memory: write + G reads
-constexpr uint32_t kMaxSplits = 64;    // split-M partial results per memory
-constexpr uint32_t kStreamChunk = 64;  // slots one workgroup iteration of the MV pass covers
 constexpr uint32_t kMinStatTile = 32;  // smallest slot tile with its own (max, sum) partial
 
-// One decode step of one layer: everything the three launches need.
+// One decode step of one layer: everything its launches need.
 struct DecodeParams {
   const void* mk;   // [Hkv][M][d] or [B][Hkv][M][d]
   void* mv;         // [B][Hkv][M][d], updated in place
@@ -25,6 +23,7 @@ struct DecodeParams {
   void* out;        // [B][Hq][d] or null
   float* scores;    // [B*Hkv][R][M], log2-domain scaled scores
   float2* stats;    // [B*Hkv][R][n_tiles] (max, sum of exp2(score - max)) per slot tile
+  float2* norm;     // [B*Hkv][R] (max, 1 / sum of exp2(score - max)) per row
   float* partial;   // [S][B][Hq][d] split-M partial outputs
   uint32_t B, Hq, Hkv, G, M, d;
   uint32_t R;        // rows per memory this step: has_write + (has_read ? G : 0)
@@ -32,7 +31,9 @@ struct DecodeParams {
   uint32_t mk_per_seq;
   uint32_t stat_tile;  // slots per (max, sum) partial
   uint32_t n_tiles;    // M / stat_tile
-  uint32_t S;          // split-M factor of the MV pass
+  uint32_t S;          // split-M factor of the MV pass: workgroups per memory
+  uint32_t mv_bs;      // threads per workgroup of the MV pass
+  uint32_t mv_u;       // 16-byte loads per lane of the MV pass
   float rscale_l2e, wscale_l2e;  // scale * log2(e)
   // strides (in elements) between consecutive batch entries of q/out and wq/wv;
   // [B][H][d] inputs use H*d, a token t of a [B][T][H][d] chunk uses T*H*d.
@@ -41,13 +42,15 @@ struct DecodeParams {
 
 // dtype: 0 = fp32, 1 = bf16 (the ABI's bct_dtype values).
 hipError_t launch_scores(const DecodeParams& p, int dtype, hipStream_t s);
+hipError_t launch_normalise(const DecodeParams& p, hipStream_t s);
 hipError_t launch_stream(const DecodeParams& p, int dtype, hipStream_t s);
 hipError_t launch_merge(const DecodeParams& p, int dtype, hipStream_t s);
 hipError_t launch_fill_zero(void* dst, size_t n_bytes, hipStream_t s);
 hipError_t launch_copy(void* dst, const void* src, size_t n_bytes, hipStream_t s);
 
-// Chooses stat_tile / n_tiles (scores pass) and S (MV pass) for a shape.
+// Chooses stat_tile / n_tiles (scores pass) and the MV pass shape (mv_bs, mv_u, S).
 void plan_decode(DecodeParams& p, int dtype);
+void plan_mv_pass(DecodeParams& p, int dtype);
 
 }  // namespace bct
 
