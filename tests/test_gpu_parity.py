@@ -45,9 +45,12 @@ def check_out(got, ref, dtype, what=""):
     return e
 
 
-def check_state_one_step(got, ref, dtype, what=""):
+def check_state_one_step(got, ref, dtype, what="", before=None):
     """State after ONE step from a common state: the two sides differ only where the
-    fp32 write weight differs in its last bits, i.e. rare flips of one rounding."""
+    fp32 write weight differs in its last bits (~1e-6 relative), i.e. rare flips of one
+    rounding.  Where the increment nearly cancels the old value the result is tiny and
+    the weight error, which scales with the increment (at most |new| + |old|), is no
+    longer small against ITS ulp: `before` (the common old state) adds that allowance."""
     g, r = f64(got, dtype), f64(ref, dtype)
     if dtype == "f32":
         e = float(np.max(np.abs(g - r)) / max(np.max(np.abs(r)), 1e-30))
@@ -55,7 +58,10 @@ def check_state_one_step(got, ref, dtype, what=""):
         return
     d = np.abs(g - r)
     ulp = bf16_ulp(r)
-    assert np.all(d <= ulp * 1.0001), f"{what}: bf16 state off by {np.max(d / ulp):.2f} ulp"
+    allow = ulp * 1.0001
+    if before is not None:
+        allow = allow + 4e-6 * (np.abs(r) + np.abs(f64(before, dtype)))
+    assert np.all(d <= allow), f"{what}: bf16 state off by {np.max(d / allow):.2f} x the allowance"
     frac = float(np.mean(d > 0))
     assert frac <= 5e-3, f"{what}: {frac:.2e} of the state elements differ"
 
