@@ -173,8 +173,8 @@ class BctCache:
         self._h = h
 
     def __del__(self):
-        if getattr(self, "_h", None):
-            lib().bct_cache_destroy(self._h)
+        if getattr(self, "_h", None) and _lib is not None:
+            _lib.bct_cache_destroy(self._h)
             self._h = None
 
     # -- shapes

@@ -21,7 +21,7 @@ struct bct_cache {
   char* ws;
   size_t ws_bytes;
   // workspace carve-up (byte offsets)
-  size_t off_scores, off_stats, off_norm, off_partial, off_prefill;
+  size_t off_scores, off_stats, off_norm, off_partial, off_pf_norm_w, off_pf_norm_r, off_pf_snap;
   uint64_t steps;
   bool keys_set;
   bct::DecodeParams plan;  // shape, strides and launch plan; pointers filled per call
@@ -76,7 +76,7 @@ bct_status check_desc(const bct_cache_desc* d) {
 
 struct Sizes {
   size_t mk_bytes, mv_bytes, cache_bytes;
-  size_t off_scores, off_stats, off_norm, off_partial, off_prefill, ws_bytes;
+  size_t off_scores, off_stats, off_norm, off_partial, off_pf_norm_w, off_pf_norm_r, off_pf_snap, ws_bytes;
 };
 
 void fill_plan(const bct_cache_desc* d, bct::DecodeParams& p) {
@@ -118,8 +118,17 @@ Sizes compute_sizes(const bct_cache_desc* d, uint32_t max_T) {
   off += align_up(units * rows * sizeof(float2), 256);
   z.off_partial = off;
   off += align_up((size_t)p.S * d->batch * d->n_q_heads * d->head_dim * sizeof(float), 256);
-  z.off_prefill = off;
-  (void)max_T;
+  // prefill of a bf16 cache: row normalisers and the MV snapshots at sub-chunk starts
+  z.off_pf_norm_w = z.off_pf_norm_r = z.off_pf_snap = off;
+  if (max_T > 0 && d->dtype == BCT_BF16) {
+    z.off_pf_norm_w = off;
+    off += align_up(units * max_T * sizeof(float2), 256);
+    z.off_pf_norm_r = off;
+    off += align_up(units * max_T * p.G * sizeof(float2), 256);
+    z.off_pf_snap = off;
+    const size_t nb = (max_T + bct::kPrefillSubChunk - 1) / bct::kPrefillSubChunk;
+    off += align_up((nb - 1) * z.mv_bytes, 256);
+  }
   z.ws_bytes = off;
   return z;
 }
@@ -215,7 +224,9 @@ bct_status bct_cache_init(const bct_cache_desc* desc, uint32_t max_prefill_T, vo
   c->off_stats = z.off_stats;
   c->off_norm = z.off_norm;
   c->off_partial = z.off_partial;
-  c->off_prefill = z.off_prefill;
+  c->off_pf_norm_w = z.off_pf_norm_w;
+  c->off_pf_norm_r = z.off_pf_norm_r;
+  c->off_pf_snap = z.off_pf_snap;
   c->steps = 0;
   c->keys_set = false;
   fill_plan(desc, c->plan);
@@ -278,7 +289,33 @@ bct_status bct_prefill(bct_cache* c, const void* q, const void* k_new, const voi
     c->steps += T;
     return BCT_OK;
   }
-  return fail(BCT_ERR_UNSUPPORTED, "bf16 prefill is not built yet");
+  bct::PrefillParams pp;
+  memset(&pp, 0, sizeof(pp));
+  pp.mk = (const uint16_t*)c->mk;
+  pp.mv = (uint16_t*)c->mv;
+  pp.q = (const uint16_t*)q;
+  pp.wq = (const uint16_t*)k_new;
+  pp.wv = (const uint16_t*)v_new;
+  pp.out = (uint16_t*)out;
+  pp.norm_w = (float2*)(c->ws + c->off_pf_norm_w);
+  pp.norm_r = (float2*)(c->ws + c->off_pf_norm_r);
+  pp.snap = (uint16_t*)(c->ws + c->off_pf_snap);
+  pp.B = c->plan.B;
+  pp.Hq = c->plan.Hq;
+  pp.Hkv = c->plan.Hkv;
+  pp.G = c->plan.G;
+  pp.M = c->plan.M;
+  pp.d = c->plan.d;
+  pp.T = T;
+  pp.has_write = k_new ? 1u : 0u;
+  pp.has_read = q ? 1u : 0u;
+  pp.mk_per_seq = c->plan.mk_per_seq;
+  pp.rscale_l2e = c->plan.rscale_l2e;
+  pp.wscale_l2e = c->plan.wscale_l2e;
+  const hipError_t e = bct::launch_prefill_bf16(pp, (hipStream_t)hip_stream);
+  if (e != hipSuccess) return hip_fail(e, "prefill launch");
+  c->steps += T;
+  return BCT_OK;
 }
 
 bct_status bct_cache_export(const bct_cache* c, void* mk_dst, void* mv_dst, uint64_t* steps, void* hip_stream) {

@@ -40,6 +40,25 @@ struct DecodeParams {
   uint64_t q_bstride, kv_bstride;
 };
 
+// One prefill chunk of a bf16 cache: everything its launches need.
+struct PrefillParams {
+  const uint16_t* mk;  // [Hkv][M][d] or [B][Hkv][M][d]
+  uint16_t* mv;        // [B][Hkv][M][d], updated in place
+  const uint16_t* q;   // [B][T][Hq][d] or null
+  const uint16_t* wq;  // [B][T][Hkv][d] or null
+  const uint16_t* wv;  // [B][T][Hkv][d] or null
+  uint16_t* out;       // [B][T][Hq][d] or null
+  float2* norm_w;      // [B*Hkv][T]   (max, 1/sum) of each write row
+  float2* norm_r;      // [B*Hkv][T*G] (max, 1/sum) of each read row
+  uint16_t* snap;      // [ceil(T/128)-1][B*Hkv][M][d]: MV at the start of sub-chunks 1, 2, ...
+  uint32_t B, Hq, Hkv, G, M, d, T;
+  uint32_t has_write, has_read, mk_per_seq;
+  float rscale_l2e, wscale_l2e;
+  uint32_t c_begin;    // first sub-chunk of a read launch
+};
+constexpr uint32_t kPrefillSubChunk = 128;
+hipError_t launch_prefill_bf16(const PrefillParams& p, hipStream_t s);
+
 // dtype: 0 = fp32, 1 = bf16 (the ABI's bct_dtype values).
 hipError_t launch_scores(const DecodeParams& p, int dtype, hipStream_t s);
 hipError_t launch_normalise(const DecodeParams& p, hipStream_t s);

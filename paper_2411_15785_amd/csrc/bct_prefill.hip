@@ -1,0 +1,527 @@
+// Chunked prefill of libbct for bf16 caches (gfx950, MFMA).
+//
+// A chunk of T tokens is T decode steps in token order with MV carried in fp32
+// through the chunk.  Because MK is static, the write weights ww_t do not
+// depend on MV, so the recurrence unrolls into dense contractions (section 3.5,
+// "Optimized for Parallelism": the per-token updates are independent and can be
+// accumulated concurrently):
+//     WW = softmax_rows(write_scale * WQ . MK^T)   [T x M]
+//     RW = softmax_rows(read_scale  * Q  . MK^T)   [T*G x M]
+//     MV_end   = round(MV_start + WW^T . WV)                       (section 3.4 eq., summed over t)
+//     out_t    = RW_t . (MV_start + sum_{s<=t} ww_s^T wv_s)         (read after the token's own write)
+// Tokens are grouped in sub-chunks of 128.  For sub-chunk c,
+//     out_c = RW_c . MV_c + tril(RW_c . WW_c^T) . WV_c,   MV_c = MV at the start of the sub-chunk,
+// where the state kernel, which walks the sub-chunks in order with its MV tile
+// in fp32 registers, leaves MV_c (rounded to bf16, as an MFMA operand has to be)
+// in the workspace.  Launches: stats -> read(c = 0) -> state -> read(c >= 1).
+//
+// All matrix products use v_mfma_f32_32x32x16_bf16 with both operands read from
+// LDS tiles whose rows run along the contraction index (C[i][j] += sum_k
+// A[i][k] B[j][k]); tiles whose memory layout runs the other way (MV, WV) are
+// transposed on their way into LDS.  Rows are padded by 16 bytes so that the 32
+// lanes of an operand read fall into different banks.  The accumulator of lane
+// l holds column j = l % 32 and rows i = 8*(v/4) + 4*(l/32) + v%4; each product
+// is oriented so that a lane's four consecutive v run along the NEXT product's
+// contraction index and can be written to LDS as one 8-byte store.
+//
+// Precision: scores in fp32 from exact bf16 products; softmax weights are
+// rounded to bf16 as MFMA operands for the reads; for the state they are split
+// into hi + lo bf16 parts (two MFMAs) so that the stored MV carries fp32-grade
+// weights like the decode step does.
+#include "bct_device.h"
+#include "bct_internal.h"
+
+namespace bct {
+
+namespace {
+
+constexpr int kTC = 128;          // tokens per sub-chunk = rows per tile
+constexpr float kNegBig = -1e30f;  // stands in for -inf in running maxima
+
+__device__ __forceinline__ f32x16 mfma_bf16(const bf16x8 a, const bf16x8 b, const f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ bf16x8 frag(const uint16_t* tile, int ld, int row, int k) {
+  return *(const bf16x8*)(tile + row * ld + k);
+}
+__device__ __forceinline__ f32x16 zero16() {
+  f32x16 z;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) z[v] = 0.f;
+  return z;
+}
+__device__ __forceinline__ uint16_t bf16_bits(float x) { return __builtin_bit_cast(uint16_t, (__bf16)x); }
+__device__ __forceinline__ float bf16_val(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+
+// NROWS rows of D bf16 from global memory into an LDS tile, row r at
+// dst + r*ld.  rowptr(r) gives the row's address or nullptr for a zero row.
+template <int D, int NROWS, typename F>
+__device__ __forceinline__ void rows_to_lds(uint16_t* dst, int ld, F rowptr) {
+  constexpr int CPR = D / 8, RPP = 256 / CPR;
+  const int ch = threadIdx.x % CPR;
+  for (int r = threadIdx.x / CPR; r < NROWS; r += RPP) {
+    const uint16_t* src = rowptr(r);
+    u32x4 v = {0u, 0u, 0u, 0u};
+    if (src) v = *(const u32x4*)(src + ch * 8);
+    *(u32x4*)(dst + r * ld + ch * 8) = v;
+  }
+}
+// The same rows, transposed: element (r, j) lands at dst + j*ld + r.
+template <int D, int NROWS, typename F>
+__device__ __forceinline__ void rows_to_lds_t(uint16_t* dst, int ld, F rowptr) {
+  constexpr int CPR = D / 8, RPP = 256 / CPR;
+  const int ch = threadIdx.x % CPR;
+  for (int r = threadIdx.x / CPR; r < NROWS; r += RPP) {
+    const uint16_t* src = rowptr(r);
+    u32x4 v = {0u, 0u, 0u, 0u};
+    if (src) v = *(const u32x4*)(src + ch * 8);
+    uint16_t* d = dst + (ch * 8) * ld + r;
+    d[0 * ld] = (uint16_t)(v.x & 0xFFFFu);
+    d[1 * ld] = (uint16_t)(v.x >> 16);
+    d[2 * ld] = (uint16_t)(v.y & 0xFFFFu);
+    d[3 * ld] = (uint16_t)(v.y >> 16);
+    d[4 * ld] = (uint16_t)(v.z & 0xFFFFu);
+    d[5 * ld] = (uint16_t)(v.z >> 16);
+    d[6 * ld] = (uint16_t)(v.w & 0xFFFFu);
+    d[7 * ld] = (uint16_t)(v.w >> 16);
+  }
+}
+__device__ __forceinline__ void store4_bf16(uint16_t* dst, float a, float b, float c, float d) {
+  uint2 w;
+  w.x = pack_bf16x2(a, b);
+  w.y = pack_bf16x2(c, d);
+  *(uint2*)dst = w;
+}
+
+__device__ __forceinline__ void merge_stat(float& m, float& s, float mo, float so) {
+  const float mn = fmaxf(m, mo);
+  s = s * fast_exp2(m - mn) + so * fast_exp2(mo - mn);
+  m = mn;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------ stats
+
+// Row statistics of the score matrix: for each write row (token t) and read
+// row (token t, query head g) of a memory, max and 1 / sum of exp2(score - max)
+// over all M slots.  One workgroup = 128 rows; it walks the keys 128 slots at
+// a time; wavefront w scores slots 32w..32w+31 of the tile against all rows.
+template <int D>
+__global__ __launch_bounds__(256) void prefill_stats_kernel(const PrefillParams p) {
+  constexpr int LD = D + 8, KS = D / 16;
+  __shared__ __attribute__((aligned(16))) uint16_t sX[kTC * LD];
+  __shared__ __attribute__((aligned(16))) uint16_t sK[128 * LD];
+  __shared__ float2 sRed[4][kTC];
+
+  const uint32_t unit = blockIdx.y, b = unit / p.Hkv, h = unit % p.Hkv;
+  const uint32_t nw = p.has_write ? p.T : 0u, nr = p.has_read ? p.T * p.G : 0u;
+  const uint32_t row0 = blockIdx.x * kTC;
+  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64, col = lane % 32, half = lane / 32;
+
+  rows_to_lds<D, kTC>(sX, LD, [&](int r) -> const uint16_t* {
+    uint32_t row = row0 + r;
+    if (row < nw) return p.wq + (((size_t)b * p.T + row) * p.Hkv + h) * D;
+    row -= nw;
+    if (row < nr) return p.q + (((size_t)b * p.T + row / p.G) * p.Hq + h * p.G + row % p.G) * D;
+    return nullptr;
+  });
+  const uint16_t* mk = p.mk + (size_t)(p.mk_per_seq ? unit : h) * p.M * D;
+
+  float scale[4], m[4], s[4];
+#pragma unroll
+  for (int jt = 0; jt < 4; ++jt) {
+    scale[jt] = (row0 + 32 * jt + col < nw) ? p.wscale_l2e : p.rscale_l2e;
+    m[jt] = kNegBig;
+    s[jt] = 0.f;
+  }
+  for (uint32_t m0 = 0; m0 < p.M; m0 += 128) {
+    __syncthreads();
+    rows_to_lds<D, 128>(sK, LD, [&](int r) -> const uint16_t* {
+      return (m0 + r < p.M) ? mk + (size_t)(m0 + r) * D : nullptr;
+    });
+    __syncthreads();
+    if (m0 + 32 * wave < p.M) {  // M is a multiple of 64: a wavefront's 32 slots are all in or all out
+      f32x16 acc[4];
+#pragma unroll
+      for (int jt = 0; jt < 4; ++jt) acc[jt] = zero16();
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const bf16x8 a = frag(sK, LD, 32 * wave + col, ks * 16 + half * 8);
+#pragma unroll
+        for (int jt = 0; jt < 4; ++jt) acc[jt] = mfma_bf16(a, frag(sX, LD, 32 * jt + col, ks * 16 + half * 8), acc[jt]);
+      }
+#pragma unroll
+      for (int jt = 0; jt < 4; ++jt) {
+        float tmax = kNegBig;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          acc[jt][v] *= scale[jt];
+          tmax = fmaxf(tmax, acc[jt][v]);
+        }
+        const float mn = fmaxf(m[jt], tmax);
+        float add = 0.f;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) add += fast_exp2(acc[jt][v] - mn);
+        s[jt] = s[jt] * fast_exp2(m[jt] - mn) + add;
+        m[jt] = mn;
+      }
+    }
+  }
+#pragma unroll
+  for (int jt = 0; jt < 4; ++jt) {
+    merge_stat(m[jt], s[jt], __shfl_xor(m[jt], 32, 64), __shfl_xor(s[jt], 32, 64));
+    if (half == 0) sRed[wave][32 * jt + col] = make_float2(m[jt], s[jt]);
+  }
+  __syncthreads();
+  if (threadIdx.x < kTC) {
+    float mm = sRed[0][threadIdx.x].x, ss = sRed[0][threadIdx.x].y;
+#pragma unroll
+    for (int w = 1; w < 4; ++w) merge_stat(mm, ss, sRed[w][threadIdx.x].x, sRed[w][threadIdx.x].y);
+    uint32_t row = row0 + threadIdx.x;
+    if (row < nw) {
+      p.norm_w[(size_t)unit * p.T + row] = make_float2(mm, 1.0f / ss);
+    } else if (row - nw < nr) {
+      p.norm_r[(size_t)unit * p.T * p.G + (row - nw)] = make_float2(mm, 1.0f / ss);
+    }
+  }
+}
+
+// ------------------------------------------------------------------ read
+
+// Output rows of one tile of 128 read rows of sub-chunk c (row rho of the
+// sub-chunk = token rho / G, query head rho % G):
+//     out = RW . MV_c  +  mask(RW . WW_c^T) . WV_c ,  mask: write token s <= the row's token.
+// The workgroup walks the M slots 64 at a time, recomputing the score tiles.
+template <int D, bool INTRA>
+__global__ __launch_bounds__(256) void prefill_read_kernel(const PrefillParams p) {
+  constexpr int LD = D + 8, KS = D / 16;
+  constexpr int LP = 64 + 8;    // row length of tiles contracted over 64 slots
+  constexpr int LA = kTC + 8;   // row length of tiles contracted over 128 tokens
+  constexpr int kLoop = 64 * LD + D * LP + 2 * kTC * LP;  // sK, sVt, sPr, sPw
+  constexpr int kTail = kTC * LA + D * LA;                // sA, sWVt
+  constexpr int kRegion = kLoop > kTail ? kLoop : kTail;
+  __shared__ __attribute__((aligned(16))) uint16_t sXr[kTC * LD];
+  __shared__ __attribute__((aligned(16))) uint16_t sXw[kTC * LD];
+  __shared__ __attribute__((aligned(16))) uint16_t sBuf[kRegion];
+  uint16_t* const sK = sBuf;
+  uint16_t* const sVt = sK + 64 * LD;
+  uint16_t* const sPr = sVt + D * LP;
+  uint16_t* const sPw = sPr + kTC * LP;
+  uint16_t* const sA = sBuf;
+  uint16_t* const sWVt = sA + kTC * LA;
+
+  const uint32_t unit = blockIdx.y, b = unit / p.Hkv, h = unit % p.Hkv;
+  const uint32_t G = p.G, T = p.T;
+  const uint32_t c = p.c_begin + blockIdx.x / G, gp = blockIdx.x % G;
+  const uint32_t t0 = c * kTC, rho0 = gp * kTC;
+  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64, col = lane % 32, half = lane / 32;
+  constexpr bool intra = INTRA;  // the chunk also writes: add the within-sub-chunk term
+  const size_t units = (size_t)p.B * p.Hkv;
+
+  rows_to_lds<D, kTC>(sXr, LD, [&](int r) -> const uint16_t* {
+    const uint32_t rho = rho0 + r, t = t0 + rho / G;
+    return t < T ? p.q + (((size_t)b * T + t) * p.Hq + h * G + rho % G) * D : nullptr;
+  });
+  if (intra) {
+    rows_to_lds<D, kTC>(sXw, LD, [&](int r) -> const uint16_t* {
+      return t0 + r < T ? p.wq + (((size_t)b * T + t0 + r) * p.Hkv + h) * D : nullptr;
+    });
+  }
+  const uint16_t* mk = p.mk + (size_t)(p.mk_per_seq ? unit : h) * p.M * D;
+  const uint16_t* mvsrc = ((c == 0 || !intra) ? p.mv : p.snap + (size_t)(c - 1) * units * p.M * D) +
+                          (size_t)unit * p.M * D;
+
+  // score step: wavefront = (slot half si, row half rj); lane column = row
+  const int si = wave & 1, rj = wave >> 1;
+  float2 nrm_r[2], nrm_w[2];
+#pragma unroll
+  for (int jt = 0; jt < 2; ++jt) {
+    const uint32_t r = 64 * rj + 32 * jt + col;
+    const uint32_t rho = rho0 + r, t = t0 + rho / G;
+    nrm_r[jt] = t < T ? p.norm_r[(size_t)unit * T * G + (size_t)t * G + rho % G] : make_float2(0.f, 0.f);
+    nrm_w[jt] = (intra && t0 + r < T) ? p.norm_w[(size_t)unit * T + t0 + r] : make_float2(0.f, 0.f);
+  }
+  // product step: wavefront = (row block, value-column block)
+  constexpr int OMI = D / 64;                      // 32-row tiles per wavefront in the output product
+  const int orow = (D == 128) ? 64 * (wave & 1) : 32 * wave;
+  const int ocol = (D == 128) ? 64 * (wave >> 1) : 0;
+  f32x16 oacc[OMI][2], aacc[2][2];
+#pragma unroll
+  for (int it = 0; it < OMI; ++it)
+#pragma unroll
+    for (int jt = 0; jt < 2; ++jt) oacc[it][jt] = zero16();
+#pragma unroll
+  for (int it = 0; it < 2; ++it)
+#pragma unroll
+    for (int jt = 0; jt < 2; ++jt) aacc[it][jt] = zero16();
+
+  for (uint32_t m0 = 0; m0 < p.M; m0 += 64) {
+    __syncthreads();
+    rows_to_lds<D, 64>(sK, LD, [&](int r) -> const uint16_t* { return mk + (size_t)(m0 + r) * D; });
+    rows_to_lds_t<D, 64>(sVt, LP, [&](int r) -> const uint16_t* { return mvsrc + (size_t)(m0 + r) * D; });
+    __syncthreads();
+    {
+      f32x16 sr[2], sw[2];
+#pragma unroll
+      for (int jt = 0; jt < 2; ++jt) {
+        sr[jt] = zero16();
+        sw[jt] = zero16();
+      }
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const int k = ks * 16 + half * 8;
+        const bf16x8 a = frag(sK, LD, 32 * si + col, k);
+#pragma unroll
+        for (int jt = 0; jt < 2; ++jt) {
+          sr[jt] = mfma_bf16(a, frag(sXr, LD, 64 * rj + 32 * jt + col, k), sr[jt]);
+          if (intra) sw[jt] = mfma_bf16(a, frag(sXw, LD, 64 * rj + 32 * jt + col, k), sw[jt]);
+        }
+      }
+#pragma unroll
+      for (int jt = 0; jt < 2; ++jt) {
+        const int r = 64 * rj + 32 * jt + col;
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          float e[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            e[i] = fast_exp2(sr[jt][4 * q4 + i] * p.rscale_l2e - nrm_r[jt].x) * nrm_r[jt].y;
+          store4_bf16(sPr + r * LP + 32 * si + 8 * q4 + 4 * half, e[0], e[1], e[2], e[3]);
+          if (intra) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+              e[i] = fast_exp2(sw[jt][4 * q4 + i] * p.wscale_l2e - nrm_w[jt].x) * nrm_w[jt].y;
+            store4_bf16(sPw + r * LP + 32 * si + 8 * q4 + 4 * half, e[0], e[1], e[2], e[3]);
+          }
+        }
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const int k = ks * 16 + half * 8;
+      bf16x8 bv[2];
+#pragma unroll
+      for (int jt = 0; jt < 2; ++jt) bv[jt] = frag(sVt, LP, ocol + 32 * jt + col, k);
+#pragma unroll
+      for (int it = 0; it < OMI; ++it) {
+        const bf16x8 a = frag(sPr, LP, orow + 32 * it + col, k);
+#pragma unroll
+        for (int jt = 0; jt < 2; ++jt) oacc[it][jt] = mfma_bf16(a, bv[jt], oacc[it][jt]);
+      }
+      if (intra) {
+        // rows of this product = write tokens s, columns = read rows
+        bf16x8 br[2];
+#pragma unroll
+        for (int jt = 0; jt < 2; ++jt) br[jt] = frag(sPr, LP, 64 * (wave >> 1) + 32 * jt + col, k);
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+          const bf16x8 a = frag(sPw, LP, 64 * (wave & 1) + 32 * it + col, k);
+#pragma unroll
+          for (int jt = 0; jt < 2; ++jt) aacc[it][jt] = mfma_bf16(a, br[jt], aacc[it][jt]);
+        }
+      }
+    }
+  }
+
+  if (intra) {
+    __syncthreads();
+    // A[row][s] = (s <= token of the row) ? sum_m rw[row][m] ww[s][m] : 0
+#pragma unroll
+    for (int jt = 0; jt < 2; ++jt) {
+      const int r = 64 * (wave >> 1) + 32 * jt + col;
+      const int tl = (int)((rho0 + r) / G);  // the row's token within the sub-chunk
+#pragma unroll
+      for (int it = 0; it < 2; ++it)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          const int s0 = 64 * (wave & 1) + 32 * it + 8 * q4 + 4 * half;
+          float e[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) e[i] = (s0 + i <= tl) ? aacc[it][jt][4 * q4 + i] : 0.f;
+          store4_bf16(sA + r * LA + s0, e[0], e[1], e[2], e[3]);
+        }
+    }
+    rows_to_lds_t<D, kTC>(sWVt, LA, [&](int r) -> const uint16_t* {
+      return t0 + r < T ? p.wv + (((size_t)b * T + t0 + r) * p.Hkv + h) * D : nullptr;
+    });
+    __syncthreads();
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      const int k = ks * 16 + half * 8;
+      bf16x8 bv[2];
+#pragma unroll
+      for (int jt = 0; jt < 2; ++jt) bv[jt] = frag(sWVt, LA, ocol + 32 * jt + col, k);
+#pragma unroll
+      for (int it = 0; it < OMI; ++it) {
+        const bf16x8 a = frag(sA, LA, orow + 32 * it + col, k);
+#pragma unroll
+        for (int jt = 0; jt < 2; ++jt) oacc[it][jt] = mfma_bf16(a, bv[jt], oacc[it][jt]);
+      }
+    }
+  }
+
+#pragma unroll
+  for (int it = 0; it < OMI; ++it)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const uint32_t r = orow + 32 * it + 8 * (v / 4) + 4 * half + (v % 4);
+      const uint32_t rho = rho0 + r, t = t0 + rho / G;
+      if (t < T) {
+        uint16_t* o = p.out + (((size_t)b * T + t) * p.Hq + h * G + rho % G) * D;
+#pragma unroll
+        for (int jt = 0; jt < 2; ++jt) o[ocol + 32 * jt + col] = bf16_bits(oacc[it][jt][v]);
+      }
+    }
+}
+
+// ------------------------------------------------------------------ state
+
+// MV tile of 64 slots: acc = MV_start; for each sub-chunk c: (if reads follow)
+// leave round(acc) as MV_c for c >= 1, then acc += WW_c^T . WV_c; finally
+// MV = round(acc).  The write weights are recomputed per sub-chunk.
+template <int D>
+__global__ __launch_bounds__(256) void prefill_state_kernel(const PrefillParams p) {
+  constexpr int LD = D + 8, KS = D / 16, LT = kTC + 8;
+  constexpr int SNJ = D / 64;  // 32-column tiles per wavefront in the state product
+  __shared__ __attribute__((aligned(16))) uint16_t sK[64 * LD];
+  __shared__ __attribute__((aligned(16))) uint16_t sXw[kTC * LD];
+  __shared__ __attribute__((aligned(16))) uint16_t sWVt[D * LT];
+  __shared__ __attribute__((aligned(16))) uint16_t sPh[64 * LT];
+  __shared__ __attribute__((aligned(16))) uint16_t sPl[64 * LT];
+  __shared__ float2 sNorm[kTC];
+
+  const uint32_t unit = blockIdx.y, b = unit / p.Hkv, h = unit % p.Hkv;
+  const uint32_t m0 = blockIdx.x * 64, T = p.T;
+  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64, col = lane % 32, half = lane / 32;
+  const size_t units = (size_t)p.B * p.Hkv;
+  const uint16_t* mk = p.mk + (size_t)(p.mk_per_seq ? unit : h) * p.M * D;
+  uint16_t* mv = p.mv + ((size_t)unit * p.M + m0) * D;
+
+  rows_to_lds<D, 64>(sK, LD, [&](int r) -> const uint16_t* { return mk + (size_t)(m0 + r) * D; });
+
+  // state product: wavefront = (slot half, column block); lane column = value column
+  const int mslot = 32 * (wave & 1), mcol = (D / 2) * (wave >> 1);
+  f32x16 macc[SNJ];
+#pragma unroll
+  for (int jt = 0; jt < SNJ; ++jt)
+#pragma unroll
+    for (int v = 0; v < 16; ++v)
+      macc[jt][v] = bf16_val(mv[(size_t)(mslot + 8 * (v / 4) + 4 * half + (v % 4)) * D + mcol + 32 * jt + col]);
+
+  const uint32_t nb = (T + kTC - 1) / kTC;
+  for (uint32_t c = 0; c < nb; ++c) {
+    const uint32_t t0 = c * kTC;
+    if (p.has_read && c > 0) {
+      uint16_t* sn = p.snap + ((size_t)(c - 1) * units + unit) * p.M * D + (size_t)m0 * D;
+#pragma unroll
+      for (int jt = 0; jt < SNJ; ++jt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          sn[(size_t)(mslot + 8 * (v / 4) + 4 * half + (v % 4)) * D + mcol + 32 * jt + col] = bf16_bits(macc[jt][v]);
+    }
+    __syncthreads();
+    rows_to_lds<D, kTC>(sXw, LD, [&](int r) -> const uint16_t* {
+      return t0 + r < T ? p.wq + (((size_t)b * T + t0 + r) * p.Hkv + h) * D : nullptr;
+    });
+    rows_to_lds_t<D, kTC>(sWVt, LT, [&](int r) -> const uint16_t* {
+      return t0 + r < T ? p.wv + (((size_t)b * T + t0 + r) * p.Hkv + h) * D : nullptr;
+    });
+    if (threadIdx.x < kTC)
+      sNorm[threadIdx.x] = (t0 + threadIdx.x < T) ? p.norm_w[(size_t)unit * T + t0 + threadIdx.x] : make_float2(0.f, 0.f);
+    __syncthreads();
+    {
+      // scores: rows = tokens (64 per wavefront), columns = slots (32 per wavefront)
+      const int tok0 = 64 * (wave & 1), sl0 = 32 * (wave >> 1);
+      f32x16 sc[2];
+      sc[0] = zero16();
+      sc[1] = zero16();
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const int k = ks * 16 + half * 8;
+        const bf16x8 bk = frag(sK, LD, sl0 + col, k);
+#pragma unroll
+        for (int it = 0; it < 2; ++it) sc[it] = mfma_bf16(frag(sXw, LD, tok0 + 32 * it + col, k), bk, sc[it]);
+      }
+#pragma unroll
+      for (int it = 0; it < 2; ++it)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          const int tl = tok0 + 32 * it + 8 * q4 + 4 * half;
+          float hi[4], lo[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float2 n = sNorm[tl + i];
+            const float w = fast_exp2(sc[it][4 * q4 + i] * p.wscale_l2e - n.x) * n.y;
+            hi[i] = bf16_val(bf16_bits(w));
+            lo[i] = w - hi[i];
+          }
+          store4_bf16(sPh + (sl0 + col) * LT + tl, hi[0], hi[1], hi[2], hi[3]);
+          store4_bf16(sPl + (sl0 + col) * LT + tl, lo[0], lo[1], lo[2], lo[3]);
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      const int k = ks * 16 + half * 8;
+      const bf16x8 ah = frag(sPh, LT, mslot + col, k), al = frag(sPl, LT, mslot + col, k);
+#pragma unroll
+      for (int jt = 0; jt < SNJ; ++jt) {
+        const bf16x8 bv = frag(sWVt, LT, mcol + 32 * jt + col, k);
+        macc[jt] = mfma_bf16(ah, bv, macc[jt]);
+        macc[jt] = mfma_bf16(al, bv, macc[jt]);
+      }
+    }
+  }
+#pragma unroll
+  for (int jt = 0; jt < SNJ; ++jt)
+#pragma unroll
+    for (int v = 0; v < 16; ++v)
+      mv[(size_t)(mslot + 8 * (v / 4) + 4 * half + (v % 4)) * D + mcol + 32 * jt + col] = bf16_bits(macc[jt][v]);
+}
+
+// ------------------------------------------------------------------ host side
+
+hipError_t launch_prefill_bf16(const PrefillParams& p0, hipStream_t s) {
+  PrefillParams p = p0;
+  const uint32_t units = p.B * p.Hkv;
+  const uint32_t rows = (p.has_write ? p.T : 0u) + (p.has_read ? p.T * p.G : 0u);
+  const uint32_t nb = (p.T + kTC - 1) / kTC;
+  const bool d128 = p.d == 128;
+  const dim3 block(256);
+  hipError_t e;
+
+  const dim3 gs((rows + kTC - 1) / kTC, units);
+  if (d128) hipLaunchKernelGGL(prefill_stats_kernel<128>, gs, block, 0, s, p);
+  else hipLaunchKernelGGL(prefill_stats_kernel<64>, gs, block, 0, s, p);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+
+  auto read = [&](uint32_t c_begin, uint32_t c_count) -> hipError_t {
+    p.c_begin = c_begin;
+    const dim3 g(c_count * p.G, units);
+    if (p.has_write) {
+      if (d128) hipLaunchKernelGGL((prefill_read_kernel<128, true>), g, block, 0, s, p);
+      else hipLaunchKernelGGL((prefill_read_kernel<64, true>), g, block, 0, s, p);
+    } else {
+      if (d128) hipLaunchKernelGGL((prefill_read_kernel<128, false>), g, block, 0, s, p);
+      else hipLaunchKernelGGL((prefill_read_kernel<64, false>), g, block, 0, s, p);
+    }
+    return hipGetLastError();
+  };
+  if (p.has_read) {
+    // without a write every sub-chunk reads MV as it is; with one, sub-chunk 0
+    // must read MV before the state kernel overwrites it
+    if ((e = read(0, p.has_write ? 1u : nb)) != hipSuccess) return e;
+  }
+  if (p.has_write) {
+    const dim3 g(p.M / 64, units);
+    if (d128) hipLaunchKernelGGL(prefill_state_kernel<128>, g, block, 0, s, p);
+    else hipLaunchKernelGGL(prefill_state_kernel<64>, g, block, 0, s, p);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (p.has_read && nb > 1 && (e = read(1, nb - 1)) != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+}  // namespace bct

@@ -1,0 +1,147 @@
+"""GPU parity of bct_prefill against the oracle's chunk routine (fp32 copy of MV carried
+through the chunk, one rounding at its end).
+
+fp32 caches: the chunk is stepped token by token through the decode kernels, so the
+decode tolerances apply.  bf16 caches take the MFMA path: softmax weights and the
+sub-chunk snapshots of MV enter the read products rounded to bf16 (relative 2^-9 each,
+independent over the M slots), which puts the output within a few bf16 ulps of the
+output vector's largest entry (asserted at 4) and far inside the 2e-2 absolute bound;
+the state uses hi+lo bf16 weights (relative 2^-17) and is held to the one-step decode
+criterion: within 1 ulp plus the cancellation allowance, few elements different.
+"""
+import numpy as np
+import pytest
+
+import bct_synth as syn
+from _util import bf16_ulp, f64, make_pair, rel_normwise, to_dev, to_np
+from test_gpu_parity import check_state_one_step
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def P():
+    import torch
+    assert torch.cuda.is_available()
+    import paper_2411_15785_amd as pkg
+    pkg.lib()
+    return pkg
+
+
+@pytest.fixture(scope="module")
+def R():
+    from oracle import bct_ref
+    return bct_ref
+
+
+# Allowance on the state beyond one rounding flip, relative to |new| + |old|.  The error of
+# the summed increment scales with sum_t |ww_t wv_t|, which exceeds the increment itself by
+# about sqrt(T) (random signs, T <= 512 here): weights good to 2^-18 (hi + lo bf16) x 22,
+# times 3 for the tail over ~10^6 elements.  It stays below 0.2 bf16 ulp of typical entries.
+PF_REL = 3e-4
+
+
+def check_prefill_out(got, ref, dtype, what):
+    g, r = f64(got, dtype), f64(ref, dtype)
+    assert np.all(np.isfinite(g)), what
+    if dtype == "f32":
+        e = rel_normwise(g, r)
+        assert e <= 1e-5, f"{what}: fp32 out rel err {e:.3e}"
+        return e
+    e = float(np.max(np.abs(g - r)))
+    assert e <= 2e-2, f"{what}: bf16 out abs err {e:.3e}"
+    tight = float(np.max(np.max(np.abs(g - r), axis=-1) / bf16_ulp(np.max(np.abs(r), axis=-1))))
+    assert tight <= 4.0, f"{what}: bf16 out {tight:.2f} ulp of the vector max"
+    return tight
+
+
+CASES = [
+    # name, B, Hq, Hkv, d, M, dtype, T
+    ("f32_small", 2, 4, 2, 64, 128, "f32", 5),
+    ("bf16_T128", 2, 2, 2, 128, 256, "bf16", 128),
+    ("bf16_ragged200", 2, 4, 2, 128, 256, "bf16", 200),
+    ("bf16_T1", 1, 2, 2, 128, 64, "bf16", 1),
+    ("bf16_d64_T130", 1, 2, 1, 64, 128, "bf16", 130),
+    ("bf16_gqa4_T300", 1, 8, 2, 128, 192, "bf16", 300),
+    ("bf16_gqa3_T70", 1, 3, 1, 128, 64, "bf16", 70),
+    ("bf16_T512", 1, 2, 2, 128, 1024, "bf16", 512),
+]
+
+
+@pytest.mark.parametrize("name,B,Hq,Hkv,d,M,dtype,T", CASES)
+@pytest.mark.parametrize("mode", ["rw", "write_only", "read_only"])
+def test_prefill_chunk_matches_oracle(P, R, name, B, Hq, Hkv, d, M, dtype, T, mode):
+    w = syn.Workload(name, 1, B, Hq, Hkv, d, M, dtype, 0)
+    ref, gpu, mk, mv0, _ = make_pair(w, R.RefCache, P.BctCache, mv0=True, max_prefill_T=T)
+    for chunk in range(2):   # the second chunk starts from the first one's state
+        q, wq, wv = syn.make_step(w, chunk * T, T=T)
+        if mode == "write_only":
+            q = None
+        if mode == "read_only":
+            wq = wv = None
+        before = ref.values()
+        gpu.set_values(to_dev(before, dtype))     # common starting state
+        o_ref = ref.prefill(q, wq, wv, T)
+        o_gpu = gpu.prefill(to_dev(q, dtype), to_dev(wq, dtype), to_dev(wv, dtype), T)
+        what = f"{name}/{mode} chunk {chunk}"
+        if mode != "write_only":
+            e = check_prefill_out(to_np(o_gpu, dtype), o_ref, dtype, what)
+            print(f"{what}: out err {e:.3g}")
+        mk_g, mv_g, st = gpu.export()
+        assert np.array_equal(to_np(mk_g, dtype), mk)
+        if mode == "read_only":
+            assert np.array_equal(to_np(mv_g, dtype), before)
+        else:
+            g64, r64, b64 = f64(to_np(mv_g, dtype), dtype), f64(ref.values(), dtype), f64(before, dtype)
+            excess = np.maximum(np.abs(g64 - r64) - bf16_ulp(r64), 0) / (np.abs(r64) + np.abs(b64) + 1e-30)
+            print(f"{what}: state excess over 1 ulp, relative to |new|+|old|: {excess.max():.3e}")
+            check_state_one_step(to_np(mv_g, dtype), ref.values(), dtype, what, before=before, rel=PF_REL)
+            print(f"{what}: {np.mean(to_np(mv_g, dtype) != ref.values()):.3%} of state elements differ")
+        assert st == (chunk + 1) * T == ref.steps
+
+
+def test_prefill_per_sequence_keys_and_scales(P, R):
+    w = syn.Workload("pf_perseq", 1, 2, 4, 2, 128, 128, "bf16", 0)
+    T = 96
+    ref, gpu, mk, _, _ = make_pair(w, R.RefCache, P.BctCache, flags=1, mv0=True, max_prefill_T=T,
+                                   read_scale=0.05, write_scale=0.2)
+    q, wq, wv = syn.make_step(w, 0, T=T)
+    before = ref.values()
+    o_ref = ref.prefill(q, wq, wv, T)
+    o_gpu = gpu.prefill(to_dev(q, "bf16"), to_dev(wq, "bf16"), to_dev(wv, "bf16"), T)
+    check_prefill_out(to_np(o_gpu, "bf16"), o_ref, "bf16", "per-seq")
+    check_state_one_step(to_np(gpu.export()[1], "bf16"), ref.values(), "bf16", "per-seq", before=before, rel=PF_REL)
+
+
+def test_prefill_then_decode_continues(P, R):
+    """A prompt through bct_prefill, then decode steps: the two entry points share one state."""
+    w = syn.Workload("pf_dec", 1, 2, 4, 4, 128, 256, "bf16", 0)
+    T = 160
+    ref, gpu, _, _, _ = make_pair(w, R.RefCache, P.BctCache, max_prefill_T=T)
+    q, wq, wv = syn.make_step(w, 0, T=T)
+    ref.prefill(q, wq, wv, T)
+    gpu.prefill(to_dev(q, "bf16"), to_dev(wq, "bf16"), to_dev(wv, "bf16"), T)
+    for t in range(T, T + 4):
+        q, wq, wv = syn.make_step(w, t)
+        gpu.set_values(to_dev(ref.values(), "bf16"))
+        o_ref = ref.decode_step(q, wq, wv)
+        o_gpu = gpu.decode_step(to_dev(q, "bf16"), to_dev(wq, "bf16"), to_dev(wv, "bf16"))
+        assert np.max(np.abs(f64(to_np(o_gpu, "bf16"), "bf16") - f64(o_ref, "bf16"))) <= 2e-2
+    assert gpu.steps == T + 4
+
+
+def test_prefill_argument_errors(P):
+    import ctypes
+    import torch
+    w = syn.Workload("pf_err", 1, 1, 2, 2, 128, 64, "bf16", 0)
+    gpu = P.BctCache(w.M, w.B, w.Hq, w.Hkv, w.d, torch.bfloat16, max_prefill_T=8)
+    gpu.set_keys(to_dev(syn.make_keys(w), "bf16"))
+    L = P.lib()
+    q, wq, wv = (to_dev(a, "bf16") for a in syn.make_step(w, 0, T=16))
+    out = torch.empty_like(q)
+    s = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    p = lambda t: ctypes.c_void_p(t.data_ptr())
+    assert L.bct_prefill(gpu._h, p(q), p(wq), p(wv), 16, p(out), s) == P.BCT_ERR_BUFFER_TOO_SMALL  # T > max_prefill_T
+    assert L.bct_prefill(gpu._h, p(q), p(wq), p(wv), 0, p(out), s) == P.BCT_ERR_INVALID_ARG
+    assert L.bct_prefill(gpu._h, p(q), p(wq), None, 8, p(out), s) == P.BCT_ERR_INVALID_ARG
+    assert gpu.steps == 0
