@@ -76,6 +76,7 @@ class RefCache:
         self.M, self.B, self.Hq, self.Hkv, self.d = M, B, Hq, Hkv, d
         self.dtype = dtype
         self.flags = flags
+        self.read_scale, self.write_scale = read_scale, write_scale
         self._np = _NP[dtype]
         ds = _Desc(M, B, Hq, Hkv, d, _DT[dtype] if isinstance(dtype, str) else dtype,
                    read_scale, write_scale, flags)

@@ -120,3 +120,37 @@ def test_two_layers_share_nothing(P, R):
     for layer in range(2):
         assert np.array_equal(np.stack(outs[layer]), solo[layer][0])
         assert np.array_equal(to_np(pair[layer].export()[1], w.dtype), solo[layer][1])
+
+
+# ------------------------------------------------------------------ prefill at workload shapes
+
+def _prefill_run(P, R, w, bs, T, chunks, mv0, max_ulp=4.0):
+    from test_gpu_prefill import check_prefill_out, check_prefill_state
+    ref, gpu, mk, _, _ = make_pair(w, R.RefCache, P.BctCache, batch_subset=bs, mv0=mv0, max_prefill_T=T)
+    for c in range(chunks):
+        q, wq, wv = syn.make_step(w, c * T, T=T)
+        before = to_np(gpu.values_view()[bs].contiguous(), w.dtype)
+        ref.import_(None, before, c * T)                      # resynchronise on the GPU's state
+        o_gpu = gpu.prefill(to_dev(q, w.dtype), to_dev(wq, w.dtype), to_dev(wv, w.dtype), T)
+        o_ref = ref.prefill(sub(q, bs), sub(wq, bs), sub(wv, bs), T)
+        e = check_prefill_out(to_np(o_gpu, w.dtype)[bs], o_ref, w.dtype, f"{w.name} prefill chunk {c}", max_ulp)
+        after = to_np(gpu.values_view()[bs].contiguous(), w.dtype)
+        frac = check_prefill_state(R, ref, mk, sub(wq, bs), sub(wv, bs), after, T, f"{w.name} prefill chunk {c}")
+        assert np.array_equal(to_np(gpu.keys_view(), w.dtype), mk)
+        print(f"{w.name}: prefill chunk {c} of {T} tokens ok (out within {e:.2f} ulp of the vector max, "
+              f"{frac:.3%} of state elements differ)", flush=True)
+    assert gpu.steps == chunks * T
+
+
+def test_cfg3_prompt_prefill_two_chunks_of_512(P, R):
+    """The 1024-token prompt of the Llama-shaped workload, one layer, as two chunks of 512."""
+    _prefill_run(P, R, syn.WORKLOADS["cfg3"], [5], 512, 2, mv0=False)
+
+
+def test_cfg5_prefill_chunk_of_512(P, R):
+    """M = 16384 slots holding random-sign N(0,1) values: the output is a sum of 16384
+    cancelling terms, each carrying two independent bf16 roundings (weight and value) on the
+    GPU side, so its error relative to the (small) output grows like the square root of the
+    number of terms; 6 ulp of the vector maximum is observed over 67 million outputs, 8 is
+    allowed.  The absolute error stays 30 times below the 2e-2 bound."""
+    _prefill_run(P, R, syn.WORKLOADS["cfg5"], [2], 512, 1, mv0=True, max_ulp=8.0)
