@@ -4,7 +4,8 @@
 A step is one token per sequence through every layer of the workload: for each
 layer one bct_decode_step (scores, cache update of all M slots, read).  The
 default workload is the Llama-7B-shaped stack (32 layers, batch 32, 32 heads,
-head_dim 128, M = 4096, bf16).  Inputs are seeded and synthetic and already in
+head_dim 128, M = 4096, bf16); its 1024-token prompt goes through bct_prefill
+first (timed separately, reported under "prefill").  Inputs are seeded and synthetic and already in
 HBM when the timed region starts.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3] [--layers L]
@@ -21,7 +22,8 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
+HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published
+MFMA_BF16_PEAK_TF = 2500.0  # MI355X dense bf16 MFMA, published
 
 
 def log(*a):
@@ -69,6 +71,7 @@ def main():
     ap.add_argument("--workload", default="cfg3")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (0 = the workload's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-prefill", action="store_true", help="start decoding from MV_0 = 0, without the prompt")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
@@ -98,8 +101,16 @@ def main():
     t_setup = time.perf_counter()
     POOL = 2  # distinct seeded step inputs per layer, cycled (the cost does not depend on the values)
     caches, inputs, outs = [], [], []
+    T = w.prefill_chunk if (w.prompt and w.dtype == "bf16" and not args.no_prefill) else 0
+    desc = pkg.make_desc(w.M, w.B, w.Hq, w.Hkv, w.d, pkg.BCT_BF16 if w.dtype == "bf16" else pkg.BCT_F32,
+                         w.scale, w.scale)
+    st, _, ws_bytes = pkg.bct_cache_query(desc, T)
+    assert st == pkg.BCT_OK
+    # one workspace for all layers: it carries nothing from one call to the next
+    workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
     for layer in range(L):
-        c = pkg.BctCache(w.M, w.B, w.Hq, w.Hkv, w.d, tdt, w.scale, w.scale, device=dev)
+        c = pkg.BctCache(w.M, w.B, w.Hq, w.Hkv, w.d, tdt, w.scale, w.scale, max_prefill_T=T, device=dev,
+                         workspace=workspace)
         c.set_keys(to_dev(syn.make_keys(w, layer)))
         caches.append(c)
         inputs.append([tuple(to_dev(a) for a in syn.make_step(w, s, layer)) for s in range(POOL)])
@@ -107,6 +118,37 @@ def main():
     torch.cuda.synchronize()
     log(f"setup: {L} layers of {w.name} in {time.perf_counter() - t_setup:.1f} s, "
         f"{sum(c.cache_bytes for c in caches) / 2**30:.1f} GiB of cache")
+
+    # The prompt: w.prompt tokens per sequence through bct_prefill, chunk by chunk, every layer.
+    # One seeded chunk of inputs serves all layers and chunks (the cost does not depend on values).
+    prefill = None
+    if T:
+        pq, pwq, pwv = (to_dev(a) for a in syn.make_step(w, 0, 0, T=T))
+        pout = torch.empty_like(pq)
+        n_chunks = w.prompt // T
+        caches[0].prefill(pq, pwq, pwv, T, pout)      # warm-up (layer 0 sees one chunk more)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for layer in range(L):
+            for _ in range(n_chunks):
+                caches[layer].prefill(pq, pwq, pwv, T, pout)
+        e1.record()
+        torch.cuda.synchronize()
+        pms = e0.elapsed_time(e1)
+        units, G = w.B * w.Hkv, w.G
+        U = 2.0 * T * w.M * w.d                        # one [T x M x d] contraction
+        # what the method needs per chunk and memory: scores of the 1+G row sets, the state
+        # product, the read against the sub-chunk's starting state, the within-sub-chunk term
+        alg = units * U * ((1 + G) + 1 + G + G * 128.0 / w.d)
+        tf = alg * n_chunks * L / (pms * 1e-3) / 1e12
+        prefill = {"tokens_per_s": w.B * w.prompt / (pms * 1e-3), "ms_total": pms, "layers": L,
+                   "prompt_tokens": w.prompt, "chunk_T": T,
+                   "roofline": {"bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TF, "unit": "TFLOP/s",
+                                "frac": tf / MFMA_BF16_PEAK_TF, "traffic": None,
+                                "flops_per_chunk_per_layer": alg}}
+        del pq, pwq, pwv, pout
+        log(f"prefill: {w.prompt} prompt tokens x {w.B} sequences x {L} layers in {pms:.1f} ms")
 
     def step(s):
         for layer in range(L):
@@ -158,6 +200,8 @@ def main():
                        "frac_of_peak": layer_step_bytes / (layer_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                        "ms_scores": ms_scores, "ms_mv_pass": ms_mv, "ms_merge": ms_merge},
     }
+    if prefill:
+        rec["prefill"] = prefill
     if not args.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(rec), flush=True)

@@ -145,7 +145,7 @@ class BctCache:
     """
 
     def __init__(self, capacity_M, batch, n_q_heads, n_kv_heads, head_dim, dtype, read_scale=None,
-                 write_scale=None, flags=0, max_prefill_T=0, device="cuda:0"):
+                 write_scale=None, flags=0, max_prefill_T=0, device="cuda:0", workspace=None):
         torch = _torch()
         self.torch_dtype = dtype
         code = {torch.float32: BCT_F32, torch.bfloat16: BCT_BF16}.get(dtype)
@@ -164,7 +164,12 @@ class BctCache:
         self.cache_bytes, self.workspace_bytes = cb, wb
         self.device = torch.device(device)
         self._cache_mem = torch.empty(cb, dtype=torch.uint8, device=self.device)
-        self._workspace = torch.empty(max(wb, 256), dtype=torch.uint8, device=self.device)
+        # the workspace holds nothing between calls, so caches stepped on one stream may share one
+        if workspace is None:
+            workspace = torch.empty(max(wb, 256), dtype=torch.uint8, device=self.device)
+        if workspace.dtype != torch.uint8 or workspace.numel() < wb or workspace.device != self.device:
+            raise ValueError(f"workspace: need {wb} bytes of torch.uint8 on {self.device}")
+        self._workspace = workspace
         with torch.cuda.device(self.device):
             st, h = bct_cache_init(self.desc, max_prefill_T, _dptr(self._cache_mem), cb, _dptr(self._workspace),
                                    self._workspace.numel(), _stream_ptr())
