@@ -21,7 +21,7 @@ struct bct_cache {
   char* ws;
   size_t ws_bytes;
   // workspace carve-up (byte offsets)
-  size_t off_scores, off_stats, off_norm, off_partial, off_pf_norm_w, off_pf_norm_r, off_pf_snap;
+  size_t off_scores, off_stats, off_norm, off_partial, off_pf_norm_w, off_pf_norm_r, off_pf_wvt, off_pf_snap;
   uint64_t steps;
   bool keys_set;
   bct::DecodeParams plan;  // shape, strides and launch plan; pointers filled per call
@@ -76,7 +76,7 @@ bct_status check_desc(const bct_cache_desc* d) {
 
 struct Sizes {
   size_t mk_bytes, mv_bytes, cache_bytes;
-  size_t off_scores, off_stats, off_norm, off_partial, off_pf_norm_w, off_pf_norm_r, off_pf_snap, ws_bytes;
+  size_t off_scores, off_stats, off_norm, off_partial, off_pf_norm_w, off_pf_norm_r, off_pf_wvt, off_pf_snap, ws_bytes;
 };
 
 void fill_plan(const bct_cache_desc* d, bct::DecodeParams& p) {
@@ -119,15 +119,17 @@ Sizes compute_sizes(const bct_cache_desc* d, uint32_t max_T) {
   z.off_partial = off;
   off += align_up((size_t)p.S * d->batch * d->n_q_heads * d->head_dim * sizeof(float), 256);
   // prefill of a bf16 cache: row normalisers and the MV snapshots at sub-chunk starts
-  z.off_pf_norm_w = z.off_pf_norm_r = z.off_pf_snap = off;
+  z.off_pf_norm_w = z.off_pf_norm_r = z.off_pf_wvt = z.off_pf_snap = off;
   if (max_T > 0 && d->dtype == BCT_BF16) {
     z.off_pf_norm_w = off;
     off += align_up(units * max_T * sizeof(float2), 256);
     z.off_pf_norm_r = off;
     off += align_up(units * max_T * p.G * sizeof(float2), 256);
-    z.off_pf_snap = off;
     const size_t nb = (max_T + bct::kPrefillSubChunk - 1) / bct::kPrefillSubChunk;
-    off += align_up((nb - 1) * z.mv_bytes, 256);
+    z.off_pf_wvt = off;
+    off += align_up(units * d->head_dim * nb * bct::kPrefillSubChunk * sz, 256);
+    z.off_pf_snap = off;
+    off += align_up(nb * z.mv_bytes, 256);
   }
   z.ws_bytes = off;
   return z;
@@ -226,6 +228,7 @@ bct_status bct_cache_init(const bct_cache_desc* desc, uint32_t max_prefill_T, vo
   c->off_partial = z.off_partial;
   c->off_pf_norm_w = z.off_pf_norm_w;
   c->off_pf_norm_r = z.off_pf_norm_r;
+  c->off_pf_wvt = z.off_pf_wvt;
   c->off_pf_snap = z.off_pf_snap;
   c->steps = 0;
   c->keys_set = false;
@@ -300,6 +303,7 @@ bct_status bct_prefill(bct_cache* c, const void* q, const void* k_new, const voi
   pp.norm_w = (float2*)(c->ws + c->off_pf_norm_w);
   pp.norm_r = (float2*)(c->ws + c->off_pf_norm_r);
   pp.snap = (uint16_t*)(c->ws + c->off_pf_snap);
+  pp.wvt = (uint16_t*)(c->ws + c->off_pf_wvt);
   pp.B = c->plan.B;
   pp.Hq = c->plan.Hq;
   pp.Hkv = c->plan.Hkv;

@@ -50,7 +50,9 @@ struct PrefillParams {
   uint16_t* out;       // [B][T][Hq][d] or null
   float2* norm_w;      // [B*Hkv][T]   (max, 1/sum) of each write row
   float2* norm_r;      // [B*Hkv][T*G] (max, 1/sum) of each read row
-  uint16_t* snap;      // [ceil(T/128)-1][B*Hkv][M][d]: MV at the start of sub-chunks 1, 2, ...
+  uint16_t* snap;      // [ceil(T/128)][B*Hkv][d][M]: MV at the start of each sub-chunk, transposed
+  uint16_t* wvt;       // [B*Hkv][d][Tpad]: WV transposed, zero beyond T
+  uint32_t Tpad;       // T rounded up to whole sub-chunks
   uint32_t B, Hq, Hkv, G, M, d, T;
   uint32_t has_write, has_read, mk_per_seq;
   float rscale_l2e, wscale_l2e;

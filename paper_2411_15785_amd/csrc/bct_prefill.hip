@@ -13,12 +13,14 @@
 //     out_c = RW_c . MV_c + tril(RW_c . WW_c^T) . WV_c,   MV_c = MV at the start of the sub-chunk,
 // where the state kernel, which walks the sub-chunks in order with its MV tile
 // in fp32 registers, leaves MV_c (rounded to bf16, as an MFMA operand has to be)
-// in the workspace.  Launches: stats -> read(c = 0) -> state -> read(c >= 1).
+// in the workspace.  Launches: transposes -> stats -> read(c = 0) -> state ->
+// read(c >= 1).
 //
 // All matrix products use v_mfma_f32_32x32x16_bf16 with both operands read from
 // LDS tiles whose rows run along the contraction index (C[i][j] += sum_k
-// A[i][k] B[j][k]); tiles whose memory layout runs the other way (MV, WV) are
-// transposed on their way into LDS.  Rows are padded by 16 bytes so that the 32
+// A[i][k] B[j][k]); the two operands whose memory layout runs the other way
+// (MV over slots, WV over tokens) are transposed once per chunk into the
+// workspace, and the MV snapshots are written transposed in the first place.  Rows are padded by 16 bytes so that the 32
 // lanes of an operand read fall into different banks.  The accumulator of lane
 // l holds column j = l % 32 and rows i = 8*(v/4) + 4*(l/32) + v%4; each product
 // is oriented so that a lane's four consecutive v run along the NEXT product's
@@ -53,38 +55,54 @@ __device__ __forceinline__ f32x16 zero16() {
 __device__ __forceinline__ uint16_t bf16_bits(float x) { return __builtin_bit_cast(uint16_t, (__bf16)x); }
 __device__ __forceinline__ float bf16_val(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
 
-// NROWS rows of D bf16 from global memory into an LDS tile, row r at
-// dst + r*ld.  rowptr(r) gives the row's address or nullptr for a zero row.
-template <int D, int NROWS, typename F>
-__device__ __forceinline__ void rows_to_lds(uint16_t* dst, int ld, F rowptr) {
-  constexpr int CPR = D / 8, RPP = 256 / CPR;
-  const int ch = threadIdx.x % CPR;
-  for (int r = threadIdx.x / CPR; r < NROWS; r += RPP) {
-    const uint16_t* src = rowptr(r);
-    u32x4 v = {0u, 0u, 0u, 0u};
-    if (src) v = *(const u32x4*)(src + ch * 8);
-    *(u32x4*)(dst + r * ld + ch * 8) = v;
+// Global -> LDS tile copies in two halves, so that the loads of the next tile
+// can be in flight while the current one is used: fetch() issues all of a
+// thread's 16-byte loads into registers, put() writes them to LDS.
+// A tile is NROWS rows of NCOLS bf16; thread t handles 16-byte chunk t % CPR of
+// rows t / CPR, t / CPR + RPP, ...
+template <int NROWS, int NCOLS>
+struct Tile {
+  static constexpr int CPR = NCOLS / 8, RPP = 256 / CPR, N = NROWS / RPP;
+  static_assert(NROWS % RPP == 0, "whole passes");
+  u32x4 v[N];
+
+  // rowptr(r): address of row r, or nullptr for a zero row.  A missing row is a
+  // load from `safe` (any valid 16-byte aligned address) that is then zeroed,
+  // so the loads carry no branches and overlap each other.
+  template <typename F>
+  __device__ __forceinline__ void fetch_rows(const uint16_t* safe, F rowptr) {
+    const int ch = threadIdx.x % CPR, r0 = threadIdx.x / CPR;
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      const uint16_t* src = rowptr(r0 + i * RPP);
+      const bool ok = src != nullptr;
+      v[i] = *(const u32x4*)((ok ? src : safe) + (ok ? ch * 8 : 0));
+      if (!ok) v[i] = (u32x4){0u, 0u, 0u, 0u};
+    }
   }
+  // rows at src + r * src_ld, all present
+  __device__ __forceinline__ void fetch_block(const uint16_t* src, size_t src_ld) {
+    const int ch = threadIdx.x % CPR, r0 = threadIdx.x / CPR;
+#pragma unroll
+    for (int i = 0; i < N; ++i) v[i] = *(const u32x4*)(src + (size_t)(r0 + i * RPP) * src_ld + ch * 8);
+  }
+  __device__ __forceinline__ void put(uint16_t* dst, int ld) const {
+    const int ch = threadIdx.x % CPR, r0 = threadIdx.x / CPR;
+#pragma unroll
+    for (int i = 0; i < N; ++i) *(u32x4*)(dst + (r0 + i * RPP) * ld + ch * 8) = v[i];
+  }
+};
+template <int D, int NROWS, typename F>
+__device__ __forceinline__ void rows_to_lds(uint16_t* dst, int ld, const uint16_t* safe, F rowptr) {
+  Tile<NROWS, D> t;
+  t.fetch_rows(safe, rowptr);
+  t.put(dst, ld);
 }
-// The same rows, transposed: element (r, j) lands at dst + j*ld + r.
-template <int D, int NROWS, typename F>
-__device__ __forceinline__ void rows_to_lds_t(uint16_t* dst, int ld, F rowptr) {
-  constexpr int CPR = D / 8, RPP = 256 / CPR;
-  const int ch = threadIdx.x % CPR;
-  for (int r = threadIdx.x / CPR; r < NROWS; r += RPP) {
-    const uint16_t* src = rowptr(r);
-    u32x4 v = {0u, 0u, 0u, 0u};
-    if (src) v = *(const u32x4*)(src + ch * 8);
-    uint16_t* d = dst + (ch * 8) * ld + r;
-    d[0 * ld] = (uint16_t)(v.x & 0xFFFFu);
-    d[1 * ld] = (uint16_t)(v.x >> 16);
-    d[2 * ld] = (uint16_t)(v.y & 0xFFFFu);
-    d[3 * ld] = (uint16_t)(v.y >> 16);
-    d[4 * ld] = (uint16_t)(v.z & 0xFFFFu);
-    d[5 * ld] = (uint16_t)(v.z >> 16);
-    d[6 * ld] = (uint16_t)(v.w & 0xFFFFu);
-    d[7 * ld] = (uint16_t)(v.w >> 16);
-  }
+template <int NROWS, int NCOLS>
+__device__ __forceinline__ void block_to_lds(uint16_t* dst, int ld, const uint16_t* src, size_t src_ld) {
+  Tile<NROWS, NCOLS> t;
+  t.fetch_block(src, src_ld);
+  t.put(dst, ld);
 }
 __device__ __forceinline__ void store4_bf16(uint16_t* dst, float a, float b, float c, float d) {
   uint2 w;
@@ -100,6 +118,39 @@ __device__ __forceinline__ void merge_stat(float& m, float& s, float mo, float s
 }
 
 }  // namespace
+
+// ------------------------------------------------------------------ transposes
+
+// MFMA operands must run along the contraction index, and two of them do not
+// in memory: WV [token][column] is contracted over tokens and MV [slot][column]
+// over slots.  This kernel writes the transposed copies once per chunk:
+//   which = 0:  WVt[unit][column][token]  (tokens >= T zero-filled up to Tpad)
+//   which = 1:  snap[0][unit][column][slot] = MV at the start of the chunk
+// One workgroup transposes 64 rows through LDS.
+template <int D>
+__global__ __launch_bounds__(256) void prefill_transpose_kernel(const PrefillParams p, int which) {
+  constexpr int LD = D + 8;
+  __shared__ __attribute__((aligned(16))) uint16_t sT[64 * LD];
+  const uint32_t unit = blockIdx.y, b = unit / p.Hkv, h = unit % p.Hkv;
+  const uint32_t r0 = blockIdx.x * 64;
+  const uint32_t rows = which == 0 ? p.Tpad : p.M;
+  rows_to_lds<D, 64>(sT, LD, p.mv, [&](int r) -> const uint16_t* {
+    if (which == 0) return r0 + r < p.T ? p.wv + (((size_t)b * p.T + r0 + r) * p.Hkv + h) * D : nullptr;
+    return p.mv + ((size_t)unit * p.M + r0 + r) * D;
+  });
+  __syncthreads();
+  uint16_t* dst = (which == 0 ? p.wvt : p.snap) + (size_t)unit * D * rows + r0;
+  // thread -> (column j, 8 consecutive rows)
+  for (int i = threadIdx.x; i < D * 8; i += 256) {
+    const int j = i / 8, rr = (i % 8) * 8;
+    u32x4 v;
+    v.x = (uint32_t)sT[(rr + 0) * LD + j] | ((uint32_t)sT[(rr + 1) * LD + j] << 16);
+    v.y = (uint32_t)sT[(rr + 2) * LD + j] | ((uint32_t)sT[(rr + 3) * LD + j] << 16);
+    v.z = (uint32_t)sT[(rr + 4) * LD + j] | ((uint32_t)sT[(rr + 5) * LD + j] << 16);
+    v.w = (uint32_t)sT[(rr + 6) * LD + j] | ((uint32_t)sT[(rr + 7) * LD + j] << 16);
+    *(u32x4*)(dst + (size_t)j * rows + rr) = v;
+  }
+}
 
 // ------------------------------------------------------------------ stats
 
@@ -119,7 +170,7 @@ __global__ __launch_bounds__(256) void prefill_stats_kernel(const PrefillParams 
   const uint32_t row0 = blockIdx.x * kTC;
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64, col = lane % 32, half = lane / 32;
 
-  rows_to_lds<D, kTC>(sX, LD, [&](int r) -> const uint16_t* {
+  rows_to_lds<D, kTC>(sX, LD, p.mk, [&](int r) -> const uint16_t* {
     uint32_t row = row0 + r;
     if (row < nw) return p.wq + (((size_t)b * p.T + row) * p.Hkv + h) * D;
     row -= nw;
@@ -135,11 +186,15 @@ __global__ __launch_bounds__(256) void prefill_stats_kernel(const PrefillParams 
     m[jt] = kNegBig;
     s[jt] = 0.f;
   }
+  Tile<128, D> tk;
+  auto fetch_keys = [&](uint32_t m0) {
+    tk.fetch_rows(p.mk, [&](int r) -> const uint16_t* { return (m0 + r < p.M) ? mk + (size_t)(m0 + r) * D : nullptr; });
+  };
+  fetch_keys(0);
   for (uint32_t m0 = 0; m0 < p.M; m0 += 128) {
     __syncthreads();
-    rows_to_lds<D, 128>(sK, LD, [&](int r) -> const uint16_t* {
-      return (m0 + r < p.M) ? mk + (size_t)(m0 + r) * D : nullptr;
-    });
+    tk.put(sK, LD);
+    if (m0 + 128 < p.M) fetch_keys(m0 + 128);  // in flight during this tile's products
     __syncthreads();
     if (m0 + 32 * wave < p.M) {  // M is a multiple of 64: a wavefront's 32 slots are all in or all out
       f32x16 acc[4];
@@ -219,18 +274,18 @@ __global__ __launch_bounds__(256) void prefill_read_kernel(const PrefillParams p
   constexpr bool intra = INTRA;  // the chunk also writes: add the within-sub-chunk term
   const size_t units = (size_t)p.B * p.Hkv;
 
-  rows_to_lds<D, kTC>(sXr, LD, [&](int r) -> const uint16_t* {
+  rows_to_lds<D, kTC>(sXr, LD, p.mk, [&](int r) -> const uint16_t* {
     const uint32_t rho = rho0 + r, t = t0 + rho / G;
     return t < T ? p.q + (((size_t)b * T + t) * p.Hq + h * G + rho % G) * D : nullptr;
   });
   if (intra) {
-    rows_to_lds<D, kTC>(sXw, LD, [&](int r) -> const uint16_t* {
+    rows_to_lds<D, kTC>(sXw, LD, p.mk, [&](int r) -> const uint16_t* {
       return t0 + r < T ? p.wq + (((size_t)b * T + t0 + r) * p.Hkv + h) * D : nullptr;
     });
   }
   const uint16_t* mk = p.mk + (size_t)(p.mk_per_seq ? unit : h) * p.M * D;
-  const uint16_t* mvsrc = ((c == 0 || !intra) ? p.mv : p.snap + (size_t)(c - 1) * units * p.M * D) +
-                          (size_t)unit * p.M * D;
+  // MV at the start of the sub-chunk, transposed: [column][slot]
+  const uint16_t* mvt = p.snap + ((size_t)(intra ? c : 0u) * units + unit) * p.M * D;
 
   // score step: wavefront = (slot half si, row half rj); lane column = row
   const int si = wave & 1, rj = wave >> 1;
@@ -256,10 +311,18 @@ __global__ __launch_bounds__(256) void prefill_read_kernel(const PrefillParams p
 #pragma unroll
     for (int jt = 0; jt < 2; ++jt) aacc[it][jt] = zero16();
 
+  Tile<64, D> tk;
+  Tile<D, 64> tv;
+  tk.fetch_block(mk, D);
+  tv.fetch_block(mvt, p.M);
   for (uint32_t m0 = 0; m0 < p.M; m0 += 64) {
     __syncthreads();
-    rows_to_lds<D, 64>(sK, LD, [&](int r) -> const uint16_t* { return mk + (size_t)(m0 + r) * D; });
-    rows_to_lds_t<D, 64>(sVt, LP, [&](int r) -> const uint16_t* { return mvsrc + (size_t)(m0 + r) * D; });
+    tk.put(sK, LD);
+    tv.put(sVt, LP);
+    if (m0 + 64 < p.M) {  // next tiles, in flight during this tile's products
+      tk.fetch_block(mk + (size_t)(m0 + 64) * D, D);
+      tv.fetch_block(mvt + m0 + 64, p.M);
+    }
     __syncthreads();
     {
       f32x16 sr[2], sw[2];
@@ -343,9 +406,7 @@ __global__ __launch_bounds__(256) void prefill_read_kernel(const PrefillParams p
           store4_bf16(sA + r * LA + s0, e[0], e[1], e[2], e[3]);
         }
     }
-    rows_to_lds_t<D, kTC>(sWVt, LA, [&](int r) -> const uint16_t* {
-      return t0 + r < T ? p.wv + (((size_t)b * T + t0 + r) * p.Hkv + h) * D : nullptr;
-    });
+    block_to_lds<D, kTC>(sWVt, LA, p.wvt + (size_t)unit * D * p.Tpad + t0, p.Tpad);
     __syncthreads();
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
@@ -399,7 +460,7 @@ __global__ __launch_bounds__(256) void prefill_state_kernel(const PrefillParams 
   const uint16_t* mk = p.mk + (size_t)(p.mk_per_seq ? unit : h) * p.M * D;
   uint16_t* mv = p.mv + ((size_t)unit * p.M + m0) * D;
 
-  rows_to_lds<D, 64>(sK, LD, [&](int r) -> const uint16_t* { return mk + (size_t)(m0 + r) * D; });
+  rows_to_lds<D, 64>(sK, LD, p.mk, [&](int r) -> const uint16_t* { return mk + (size_t)(m0 + r) * D; });
 
   // state product: wavefront = (slot half, column block); lane column = value column
   const int mslot = 32 * (wave & 1), mcol = (D / 2) * (wave >> 1);
@@ -411,25 +472,35 @@ __global__ __launch_bounds__(256) void prefill_state_kernel(const PrefillParams 
       macc[jt][v] = bf16_val(mv[(size_t)(mslot + 8 * (v / 4) + 4 * half + (v % 4)) * D + mcol + 32 * jt + col]);
 
   const uint32_t nb = (T + kTC - 1) / kTC;
+  Tile<kTC, D> tx;
+  Tile<D, kTC> tw;
+  float2 tn = make_float2(0.f, 0.f);
+  auto fetch_tokens = [&](uint32_t t0) {
+    tx.fetch_rows(p.mk, [&](int r) -> const uint16_t* {
+      return t0 + r < T ? p.wq + (((size_t)b * T + t0 + r) * p.Hkv + h) * D : nullptr;
+    });
+    tw.fetch_block(p.wvt + (size_t)unit * D * p.Tpad + t0, p.Tpad);
+    if (threadIdx.x < kTC)
+      tn = (t0 + threadIdx.x < T) ? p.norm_w[(size_t)unit * T + t0 + threadIdx.x] : make_float2(0.f, 0.f);
+  };
+  fetch_tokens(0);
   for (uint32_t c = 0; c < nb; ++c) {
     const uint32_t t0 = c * kTC;
     if (p.has_read && c > 0) {
-      uint16_t* sn = p.snap + ((size_t)(c - 1) * units + unit) * p.M * D + (size_t)m0 * D;
+      // MV at the start of sub-chunk c, transposed ([column][slot]) for the read kernel
+      uint16_t* sn = p.snap + ((size_t)c * units + unit) * p.M * D + m0 + mslot + 4 * half;
 #pragma unroll
       for (int jt = 0; jt < SNJ; ++jt)
 #pragma unroll
-        for (int v = 0; v < 16; ++v)
-          sn[(size_t)(mslot + 8 * (v / 4) + 4 * half + (v % 4)) * D + mcol + 32 * jt + col] = bf16_bits(macc[jt][v]);
+        for (int q4 = 0; q4 < 4; ++q4)
+          store4_bf16(sn + (size_t)(mcol + 32 * jt + col) * p.M + 8 * q4, macc[jt][4 * q4 + 0], macc[jt][4 * q4 + 1],
+                      macc[jt][4 * q4 + 2], macc[jt][4 * q4 + 3]);
     }
     __syncthreads();
-    rows_to_lds<D, kTC>(sXw, LD, [&](int r) -> const uint16_t* {
-      return t0 + r < T ? p.wq + (((size_t)b * T + t0 + r) * p.Hkv + h) * D : nullptr;
-    });
-    rows_to_lds_t<D, kTC>(sWVt, LT, [&](int r) -> const uint16_t* {
-      return t0 + r < T ? p.wv + (((size_t)b * T + t0 + r) * p.Hkv + h) * D : nullptr;
-    });
-    if (threadIdx.x < kTC)
-      sNorm[threadIdx.x] = (t0 + threadIdx.x < T) ? p.norm_w[(size_t)unit * T + t0 + threadIdx.x] : make_float2(0.f, 0.f);
+    tx.put(sXw, LD);
+    tw.put(sWVt, LT);
+    if (threadIdx.x < kTC) sNorm[threadIdx.x] = tn;
+    if (c + 1 < nb) fetch_tokens(t0 + kTC);  // next sub-chunk, in flight during this one's products
     __syncthreads();
     {
       // scores: rows = tokens (64 per wavefront), columns = slots (32 per wavefront)
@@ -491,6 +562,16 @@ hipError_t launch_prefill_bf16(const PrefillParams& p0, hipStream_t s) {
   const bool d128 = p.d == 128;
   const dim3 block(256);
   hipError_t e;
+
+  p.Tpad = nb * kTC;
+  auto transpose = [&](int which) -> hipError_t {
+    const dim3 g((which == 0 ? p.Tpad : p.M) / 64, units);
+    if (d128) hipLaunchKernelGGL(prefill_transpose_kernel<128>, g, block, 0, s, p, which);
+    else hipLaunchKernelGGL(prefill_transpose_kernel<64>, g, block, 0, s, p, which);
+    return hipGetLastError();
+  };
+  if (p.has_write && (e = transpose(0)) != hipSuccess) return e;
+  if (p.has_read && (e = transpose(1)) != hipSuccess) return e;
 
   const dim3 gs((rows + kTC - 1) / kTC, units);
   if (d128) hipLaunchKernelGGL(prefill_stats_kernel<128>, gs, block, 0, s, p);
