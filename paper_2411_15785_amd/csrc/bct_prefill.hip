@@ -59,10 +59,10 @@ __device__ __forceinline__ float bf16_val(uint16_t b) { return __uint_as_float((
 // can be in flight while the current one is used: fetch() issues all of a
 // thread's 16-byte loads into registers, put() writes them to LDS.
 // A tile is NROWS rows of NCOLS bf16; thread t handles 16-byte chunk t % CPR of
-// rows t / CPR, t / CPR + RPP, ...
-template <int NROWS, int NCOLS>
+// rows t / CPR, t / CPR + RPP, ... of a workgroup of NT threads
+template <int NROWS, int NCOLS, int NT = 256>
 struct Tile {
-  static constexpr int CPR = NCOLS / 8, RPP = 256 / CPR, N = NROWS / RPP;
+  static constexpr int CPR = NCOLS / 8, RPP = NT / CPR, N = NROWS / RPP;
   static_assert(NROWS % RPP == 0, "whole passes");
   u32x4 v[N];
 
@@ -442,10 +442,12 @@ __global__ __launch_bounds__(256) void prefill_read_kernel(const PrefillParams p
 // MV tile of 64 slots: acc = MV_start; for each sub-chunk c: (if reads follow)
 // leave round(acc) as MV_c for c >= 1, then acc += WW_c^T . WV_c; finally
 // MV = round(acc).  The write weights are recomputed per sub-chunk.
+// Eight wavefronts (two per SIMD, so that one's softmax arithmetic and LDS
+// traffic overlap the other's MFMAs): for the scores each takes 32 tokens x 32
+// slots, for the state product 32 slots x 32 value columns.
 template <int D>
-__global__ __launch_bounds__(256) void prefill_state_kernel(const PrefillParams p) {
-  constexpr int LD = D + 8, KS = D / 16, LT = kTC + 8;
-  constexpr int SNJ = D / 64;  // 32-column tiles per wavefront in the state product
+__global__ __launch_bounds__(512) void prefill_state_kernel(const PrefillParams p) {
+  constexpr int LD = D + 8, KS = D / 16, LT = kTC + 8, NT = 512;
   __shared__ __attribute__((aligned(16))) uint16_t sK[64 * LD];
   __shared__ __attribute__((aligned(16))) uint16_t sXw[kTC * LD];
   __shared__ __attribute__((aligned(16))) uint16_t sWVt[D * LT];
@@ -460,20 +462,25 @@ __global__ __launch_bounds__(256) void prefill_state_kernel(const PrefillParams 
   const uint16_t* mk = p.mk + (size_t)(p.mk_per_seq ? unit : h) * p.M * D;
   uint16_t* mv = p.mv + ((size_t)unit * p.M + m0) * D;
 
-  rows_to_lds<D, 64>(sK, LD, p.mk, [&](int r) -> const uint16_t* { return mk + (size_t)(m0 + r) * D; });
+  {
+    Tile<64, D, NT> t;
+    t.fetch_block(mk + (size_t)m0 * D, D);
+    t.put(sK, LD);
+  }
 
-  // state product: wavefront = (slot half, column block); lane column = value column
-  const int mslot = 32 * (wave & 1), mcol = (D / 2) * (wave >> 1);
-  f32x16 macc[SNJ];
-#pragma unroll
-  for (int jt = 0; jt < SNJ; ++jt)
+  // state product: wavefront = (slot half, 32-column block); lane column = value column
+  const int mslot = 32 * (wave & 1), mcol = 32 * (wave >> 1);
+  const bool has_cols = mcol < D;  // with d = 64 only four wavefronts have columns
+  f32x16 macc = zero16();
+  if (has_cols) {
 #pragma unroll
     for (int v = 0; v < 16; ++v)
-      macc[jt][v] = bf16_val(mv[(size_t)(mslot + 8 * (v / 4) + 4 * half + (v % 4)) * D + mcol + 32 * jt + col]);
+      macc[v] = bf16_val(mv[(size_t)(mslot + 8 * (v / 4) + 4 * half + (v % 4)) * D + mcol + col]);
+  }
 
   const uint32_t nb = (T + kTC - 1) / kTC;
-  Tile<kTC, D> tx;
-  Tile<D, kTC> tw;
+  Tile<kTC, D, NT> tx;
+  Tile<D, kTC, NT> tw;
   float2 tn = make_float2(0.f, 0.f);
   auto fetch_tokens = [&](uint32_t t0) {
     tx.fetch_rows(p.mk, [&](int r) -> const uint16_t* {
@@ -486,15 +493,13 @@ __global__ __launch_bounds__(256) void prefill_state_kernel(const PrefillParams 
   fetch_tokens(0);
   for (uint32_t c = 0; c < nb; ++c) {
     const uint32_t t0 = c * kTC;
-    if (p.has_read && c > 0) {
+    if (p.has_read && c > 0 && has_cols) {
       // MV at the start of sub-chunk c, transposed ([column][slot]) for the read kernel
       uint16_t* sn = p.snap + ((size_t)c * units + unit) * p.M * D + m0 + mslot + 4 * half;
 #pragma unroll
-      for (int jt = 0; jt < SNJ; ++jt)
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4)
-          store4_bf16(sn + (size_t)(mcol + 32 * jt + col) * p.M + 8 * q4, macc[jt][4 * q4 + 0], macc[jt][4 * q4 + 1],
-                      macc[jt][4 * q4 + 2], macc[jt][4 * q4 + 3]);
+      for (int q4 = 0; q4 < 4; ++q4)
+        store4_bf16(sn + (size_t)(mcol + col) * p.M + 8 * q4, macc[4 * q4 + 0], macc[4 * q4 + 1], macc[4 * q4 + 2],
+                    macc[4 * q4 + 3]);
     }
     __syncthreads();
     tx.put(sXw, LD);
@@ -503,53 +508,45 @@ __global__ __launch_bounds__(256) void prefill_state_kernel(const PrefillParams 
     if (c + 1 < nb) fetch_tokens(t0 + kTC);  // next sub-chunk, in flight during this one's products
     __syncthreads();
     {
-      // scores: rows = tokens (64 per wavefront), columns = slots (32 per wavefront)
-      const int tok0 = 64 * (wave & 1), sl0 = 32 * (wave >> 1);
-      f32x16 sc[2];
-      sc[0] = zero16();
-      sc[1] = zero16();
+      // scores: rows = tokens (32 per wavefront), columns = slots (32 per wavefront)
+      const int tok0 = 32 * (wave & 3), sl0 = 32 * (wave >> 2);
+      f32x16 sc = zero16();
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
         const int k = ks * 16 + half * 8;
-        const bf16x8 bk = frag(sK, LD, sl0 + col, k);
-#pragma unroll
-        for (int it = 0; it < 2; ++it) sc[it] = mfma_bf16(frag(sXw, LD, tok0 + 32 * it + col, k), bk, sc[it]);
+        sc = mfma_bf16(frag(sXw, LD, tok0 + col, k), frag(sK, LD, sl0 + col, k), sc);
       }
 #pragma unroll
-      for (int it = 0; it < 2; ++it)
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const int tl = tok0 + 8 * q4 + 4 * half;
+        float hi[4], lo[4];
 #pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-          const int tl = tok0 + 32 * it + 8 * q4 + 4 * half;
-          float hi[4], lo[4];
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const float2 n = sNorm[tl + i];
-            const float w = fast_exp2(sc[it][4 * q4 + i] * p.wscale_l2e - n.x) * n.y;
-            hi[i] = bf16_val(bf16_bits(w));
-            lo[i] = w - hi[i];
-          }
-          store4_bf16(sPh + (sl0 + col) * LT + tl, hi[0], hi[1], hi[2], hi[3]);
-          store4_bf16(sPl + (sl0 + col) * LT + tl, lo[0], lo[1], lo[2], lo[3]);
+        for (int i = 0; i < 4; ++i) {
+          const float2 n = sNorm[tl + i];
+          const float w = fast_exp2(sc[4 * q4 + i] * p.wscale_l2e - n.x) * n.y;
+          hi[i] = bf16_val(bf16_bits(w));
+          lo[i] = w - hi[i];
         }
+        store4_bf16(sPh + (sl0 + col) * LT + tl, hi[0], hi[1], hi[2], hi[3]);
+        store4_bf16(sPl + (sl0 + col) * LT + tl, lo[0], lo[1], lo[2], lo[3]);
+      }
     }
     __syncthreads();
+    if (has_cols) {
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      const int k = ks * 16 + half * 8;
-      const bf16x8 ah = frag(sPh, LT, mslot + col, k), al = frag(sPl, LT, mslot + col, k);
-#pragma unroll
-      for (int jt = 0; jt < SNJ; ++jt) {
-        const bf16x8 bv = frag(sWVt, LT, mcol + 32 * jt + col, k);
-        macc[jt] = mfma_bf16(ah, bv, macc[jt]);
-        macc[jt] = mfma_bf16(al, bv, macc[jt]);
+      for (int ks = 0; ks < 8; ++ks) {
+        const int k = ks * 16 + half * 8;
+        const bf16x8 bv = frag(sWVt, LT, mcol + col, k);
+        macc = mfma_bf16(frag(sPh, LT, mslot + col, k), bv, macc);
+        macc = mfma_bf16(frag(sPl, LT, mslot + col, k), bv, macc);
       }
     }
   }
-#pragma unroll
-  for (int jt = 0; jt < SNJ; ++jt)
+  if (has_cols) {
 #pragma unroll
     for (int v = 0; v < 16; ++v)
-      mv[(size_t)(mslot + 8 * (v / 4) + 4 * half + (v % 4)) * D + mcol + 32 * jt + col] = bf16_bits(macc[jt][v]);
+      mv[(size_t)(mslot + 8 * (v / 4) + 4 * half + (v % 4)) * D + mcol + col] = bf16_bits(macc[v]);
+  }
 }
 
 // ------------------------------------------------------------------ host side
@@ -597,8 +594,8 @@ hipError_t launch_prefill_bf16(const PrefillParams& p0, hipStream_t s) {
   }
   if (p.has_write) {
     const dim3 g(p.M / 64, units);
-    if (d128) hipLaunchKernelGGL(prefill_state_kernel<128>, g, block, 0, s, p);
-    else hipLaunchKernelGGL(prefill_state_kernel<64>, g, block, 0, s, p);
+    if (d128) hipLaunchKernelGGL(prefill_state_kernel<128>, g, dim3(512), 0, s, p);
+    else hipLaunchKernelGGL(prefill_state_kernel<64>, g, dim3(512), 0, s, p);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (p.has_read && nb > 1 && (e = read(1, nb - 1)) != hipSuccess) return e;
   }
