@@ -1,0 +1,108 @@
+"""CPU-only checks of the C ABI: libbct.so loads without a GPU, exports every symbol
+include/bct.h declares, and validates its arguments before the first HIP call."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2411_15785_amd as P
+from paper_2411_15785_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2411_15785_amd import build
+        build.build()
+    return P.lib()
+
+
+def declared_functions():
+    src = open(os.path.join(ROOT, "include", "bct.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(bct_[a-z_]+)\s*\(", src)))
+
+
+def test_every_declared_symbol_is_exported_and_bound(L):
+    names = declared_functions()
+    assert {"bct_cache_init", "bct_decode_step", "bct_prefill"} <= set(names)
+    for n in names:
+        assert hasattr(L, n), f"{n} is declared in include/bct.h but not exported by libbct.so"
+    assert sorted(binding.EXPORTS) == names      # the binding names exactly the header's functions
+
+
+def desc(**kw):
+    d = dict(capacity_M=4096, batch=32, n_q_heads=32, n_kv_heads=32, head_dim=128, dtype=P.BCT_BF16,
+             read_scale=0.0884, write_scale=0.0884, flags=0)
+    d.update(kw)
+    return P.make_desc(**d)
+
+
+def test_query_sizes_are_exact_and_constant(L):
+    st, cb, wb = P.bct_cache_query(desc(), 0)
+    assert st == P.BCT_OK
+    assert cb == 32 * 4096 * 128 * 2 + 32 * 32 * 4096 * 128 * 2      # MK + MV, nothing else
+    st, cb2, wb2 = P.bct_cache_query(desc(), 512)
+    assert st == P.BCT_OK and cb2 == cb and wb2 > wb                # prefill only adds workspace
+    st, cbp, _ = P.bct_cache_query(desc(flags=P.BCT_MK_PER_SEQUENCE), 0)
+    assert st == P.BCT_OK and cbp == 2 * 32 * 32 * 4096 * 128 * 2
+    st, cbf, _ = P.bct_cache_query(desc(dtype=P.BCT_F32, head_dim=64, capacity_M=64, batch=1, n_q_heads=4,
+                                        n_kv_heads=4), 0)
+    assert st == P.BCT_OK and cbf == 2 * 4 * 64 * 64 * 4
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(capacity_M=0), P.BCT_ERR_INVALID_ARG),
+    (dict(batch=0), P.BCT_ERR_INVALID_ARG),
+    (dict(n_q_heads=30), P.BCT_ERR_INVALID_ARG),            # not a multiple of n_kv_heads
+    (dict(read_scale=float("nan")), P.BCT_ERR_INVALID_ARG),
+    (dict(capacity_M=100), P.BCT_ERR_UNSUPPORTED),          # not a multiple of 64
+    (dict(capacity_M=131072), P.BCT_ERR_UNSUPPORTED),
+    (dict(head_dim=96), P.BCT_ERR_UNSUPPORTED),
+    (dict(dtype=7), P.BCT_ERR_UNSUPPORTED),
+    (dict(flags=8), P.BCT_ERR_UNSUPPORTED),
+    (dict(n_q_heads=32, n_kv_heads=2), P.BCT_ERR_UNSUPPORTED),   # 16 query heads per KV head
+])
+def test_bad_descriptors_are_rejected(L, kw, status):
+    st, _, _ = P.bct_cache_query(desc(**kw), 0)
+    assert st == status
+    assert P.bct_last_error() != ""
+    st, h = P.bct_cache_init(desc(**kw), 0, ctypes.c_void_p(0x1000), 1 << 40, ctypes.c_void_p(0x2000), 1 << 40, None)
+    assert st == status and not h.value
+
+
+def test_init_checks_pointers_and_sizes_before_touching_the_gpu(L):
+    d = desc()
+    _, cb, wb = P.bct_cache_query(d, 0)
+    ok_c, ok_w = ctypes.c_void_p(0x10000), ctypes.c_void_p(0x20000)
+    assert L.bct_cache_query(None, 0, None, None) == P.BCT_ERR_INVALID_ARG
+    assert P.bct_cache_init(d, 0, None, cb, ok_w, wb, None)[0] == P.BCT_ERR_INVALID_ARG
+    assert P.bct_cache_init(d, 0, ok_c, cb, None, wb, None)[0] == P.BCT_ERR_INVALID_ARG
+    assert P.bct_cache_init(d, 0, ctypes.c_void_p(0x10010), cb, ok_w, wb, None)[0] == P.BCT_ERR_MISALIGNED
+    assert P.bct_cache_init(d, 0, ok_c, cb - 1, ok_w, wb, None)[0] == P.BCT_ERR_BUFFER_TOO_SMALL
+    assert P.bct_cache_init(d, 0, ok_c, cb, ok_w, wb - 1, None)[0] == P.BCT_ERR_BUFFER_TOO_SMALL
+    assert P.bct_cache_init(d, 512, ok_c, cb, ok_w, wb, None)[0] == P.BCT_ERR_BUFFER_TOO_SMALL  # prefill needs more
+
+
+def test_null_handles_and_messages(L):
+    vp = ctypes.c_void_p
+    assert L.bct_decode_step(None, vp(16), vp(16), vp(16), vp(16), None) == P.BCT_ERR_INVALID_ARG
+    assert L.bct_prefill(None, vp(16), vp(16), vp(16), 4, vp(16), None) == P.BCT_ERR_INVALID_ARG
+    assert L.bct_cache_set_keys(None, vp(16), None) == P.BCT_ERR_INVALID_ARG
+    assert L.bct_cache_steps(None, None) == P.BCT_ERR_INVALID_ARG
+    assert L.bct_stream_copy(vp(16), vp(16), 24, None) == P.BCT_ERR_INVALID_ARG   # not a multiple of 16
+    assert L.bct_stream_copy(vp(8), vp(16), 32, None) == P.BCT_ERR_MISALIGNED
+    L.bct_cache_destroy(None)                                                     # harmless
+    for st in range(7):
+        assert P.bct_strerror(st) not in ("", "unknown status")
+    assert P.bct_strerror(99) == "unknown status"
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "one GPU" in r.stderr
