@@ -65,19 +65,23 @@ struct Tile {
   static constexpr int CPR = NCOLS / 8, RPP = NT / CPR, N = NROWS / RPP;
   static_assert(NROWS % RPP == 0, "whole passes");
   u32x4 v[N];
+  uint32_t missing = 0;  // bit i: row i of this thread is a zero row
 
   // rowptr(r): address of row r, or nullptr for a zero row.  A missing row is a
-  // load from `safe` (any valid 16-byte aligned address) that is then zeroed,
-  // so the loads carry no branches and overlap each other.
+  // load from `safe` (any valid 16-byte aligned address) whose result put()
+  // replaces by zeros: the loads carry no branches, and nothing touches the
+  // loaded registers until put(), so the loads stay in flight across the
+  // products of the current tile.
   template <typename F>
   __device__ __forceinline__ void fetch_rows(const uint16_t* safe, F rowptr) {
     const int ch = threadIdx.x % CPR, r0 = threadIdx.x / CPR;
+    missing = 0;
 #pragma unroll
     for (int i = 0; i < N; ++i) {
       const uint16_t* src = rowptr(r0 + i * RPP);
       const bool ok = src != nullptr;
       v[i] = *(const u32x4*)((ok ? src : safe) + (ok ? ch * 8 : 0));
-      if (!ok) v[i] = (u32x4){0u, 0u, 0u, 0u};
+      missing |= ok ? 0u : (1u << i);
     }
   }
   // rows at src + r * src_ld, all present
@@ -85,11 +89,13 @@ struct Tile {
     const int ch = threadIdx.x % CPR, r0 = threadIdx.x / CPR;
 #pragma unroll
     for (int i = 0; i < N; ++i) v[i] = *(const u32x4*)(src + (size_t)(r0 + i * RPP) * src_ld + ch * 8);
+    missing = 0;
   }
   __device__ __forceinline__ void put(uint16_t* dst, int ld) const {
     const int ch = threadIdx.x % CPR, r0 = threadIdx.x / CPR;
 #pragma unroll
-    for (int i = 0; i < N; ++i) *(u32x4*)(dst + (r0 + i * RPP) * ld + ch * 8) = v[i];
+    for (int i = 0; i < N; ++i)
+      *(u32x4*)(dst + (r0 + i * RPP) * ld + ch * 8) = ((missing >> i) & 1u) ? (u32x4){0u, 0u, 0u, 0u} : v[i];
   }
 };
 template <int D, int NROWS, typename F>
@@ -186,6 +192,13 @@ __global__ __launch_bounds__(256) void prefill_stats_kernel(const PrefillParams 
     m[jt] = kNegBig;
     s[jt] = 0.f;
   }
+  // the query rows do not change over the loop: keep their operand fragments in registers
+  __syncthreads();
+  bf16x8 xb[4][KS];
+#pragma unroll
+  for (int jt = 0; jt < 4; ++jt)
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) xb[jt][ks] = frag(sX, LD, 32 * jt + col, ks * 16 + half * 8);
   Tile<128, D> tk;
   auto fetch_keys = [&](uint32_t m0) {
     tk.fetch_rows(p.mk, [&](int r) -> const uint16_t* { return (m0 + r < p.M) ? mk + (size_t)(m0 + r) * D : nullptr; });
@@ -204,7 +217,7 @@ __global__ __launch_bounds__(256) void prefill_stats_kernel(const PrefillParams 
       for (int ks = 0; ks < KS; ++ks) {
         const bf16x8 a = frag(sK, LD, 32 * wave + col, ks * 16 + half * 8);
 #pragma unroll
-        for (int jt = 0; jt < 4; ++jt) acc[jt] = mfma_bf16(a, frag(sX, LD, 32 * jt + col, ks * 16 + half * 8), acc[jt]);
+        for (int jt = 0; jt < 4; ++jt) acc[jt] = mfma_bf16(a, xb[jt][ks], acc[jt]);
       }
 #pragma unroll
       for (int jt = 0; jt < 4; ++jt) {
@@ -311,6 +324,17 @@ __global__ __launch_bounds__(256) void prefill_read_kernel(const PrefillParams p
 #pragma unroll
     for (int jt = 0; jt < 2; ++jt) aacc[it][jt] = zero16();
 
+  // the query rows (and write-query rows) do not change over the loop: keep
+  // their operand fragments in registers instead of re-reading LDS per tile
+  __syncthreads();
+  bf16x8 xr[2][KS], xw[2][KS];
+#pragma unroll
+  for (int jt = 0; jt < 2; ++jt)
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      xr[jt][ks] = frag(sXr, LD, 64 * rj + 32 * jt + col, ks * 16 + half * 8);
+      if (intra) xw[jt][ks] = frag(sXw, LD, 64 * rj + 32 * jt + col, ks * 16 + half * 8);
+    }
   Tile<64, D> tk;
   Tile<D, 64> tv;
   tk.fetch_block(mk, D);
@@ -337,8 +361,8 @@ __global__ __launch_bounds__(256) void prefill_read_kernel(const PrefillParams p
         const bf16x8 a = frag(sK, LD, 32 * si + col, k);
 #pragma unroll
         for (int jt = 0; jt < 2; ++jt) {
-          sr[jt] = mfma_bf16(a, frag(sXr, LD, 64 * rj + 32 * jt + col, k), sr[jt]);
-          if (intra) sw[jt] = mfma_bf16(a, frag(sXw, LD, 64 * rj + 32 * jt + col, k), sw[jt]);
+          sr[jt] = mfma_bf16(a, xr[jt][ks], sr[jt]);
+          if (intra) sw[jt] = mfma_bf16(a, xw[jt][ks], sw[jt]);
         }
       }
 #pragma unroll
@@ -478,6 +502,13 @@ __global__ __launch_bounds__(512) void prefill_state_kernel(const PrefillParams 
       macc[v] = bf16_val(mv[(size_t)(mslot + 8 * (v / 4) + 4 * half + (v % 4)) * D + mcol + col]);
   }
 
+  // the key tile does not change over the loop: keep this wavefront's key
+  // fragments (32 slots) in registers
+  __syncthreads();
+  bf16x8 kb[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) kb[ks] = frag(sK, LD, 32 * (wave >> 2) + col, ks * 16 + half * 8);
+
   const uint32_t nb = (T + kTC - 1) / kTC;
   Tile<kTC, D, NT> tx;
   Tile<D, kTC, NT> tw;
@@ -514,7 +545,7 @@ __global__ __launch_bounds__(512) void prefill_state_kernel(const PrefillParams 
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
         const int k = ks * 16 + half * 8;
-        sc = mfma_bf16(frag(sXw, LD, tok0 + col, k), frag(sK, LD, sl0 + col, k), sc);
+        sc = mfma_bf16(frag(sXw, LD, tok0 + col, k), kb[ks], sc);
       }
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
