@@ -463,90 +463,95 @@ __global__ __launch_bounds__(256) void prefill_read_kernel(const PrefillParams p
 
 // ------------------------------------------------------------------ state
 
-// MV tile of 64 slots: acc = MV_start; for each sub-chunk c: (if reads follow)
-// leave round(acc) as MV_c for c >= 1, then acc += WW_c^T . WV_c; finally
-// MV = round(acc).  The write weights are recomputed per sub-chunk.
-// Eight wavefronts (two per SIMD, so that one's softmax arithmetic and LDS
-// traffic overlap the other's MFMAs): for the scores each takes 32 tokens x 32
-// slots, for the state product 32 slots x 32 value columns.
+// MV tile of 128 slots: acc = MV_start; tokens are walked 64 at a time; at the
+// start of every sub-chunk c >= 1 (if reads follow) round(acc) is left as MV_c;
+// acc += WW^T . WV; finally MV = round(acc).  The write weights are recomputed
+// per token tile.  Eight wavefronts; the workgroup needs 72 KB of LDS and at
+// most 128 registers per lane, so two workgroups share a CU and one's memory
+// round trips and barriers overlap the other's products.  Each wavefront keeps
+// the key fragments of its 32 slots in registers (loaded straight from memory
+// in operand layout); for the scores it takes 32 tokens x 32 slots, for the
+// state product 32 slots x d/2 value columns.
 template <int D>
-__global__ __launch_bounds__(512) void prefill_state_kernel(const PrefillParams p) {
-  constexpr int LD = D + 8, KS = D / 16, LT = kTC + 8, NT = 512;
-  __shared__ __attribute__((aligned(16))) uint16_t sK[64 * LD];
-  __shared__ __attribute__((aligned(16))) uint16_t sXw[kTC * LD];
-  __shared__ __attribute__((aligned(16))) uint16_t sWVt[D * LT];
-  __shared__ __attribute__((aligned(16))) uint16_t sPh[64 * LT];
-  __shared__ __attribute__((aligned(16))) uint16_t sPl[64 * LT];
-  __shared__ float2 sNorm[kTC];
+__global__ __launch_bounds__(512, 4) void prefill_state_kernel(const PrefillParams p) {
+  constexpr int LD = D + 8, KS = D / 16, NT = 512;
+  constexpr int TT = 64;        // tokens per tile
+  constexpr int LP = TT + 8;    // row length of tiles contracted over the tile's tokens
+  constexpr int SNJ = D / 64;   // 32-column tiles per wavefront in the state product
+  __shared__ __attribute__((aligned(16))) uint16_t sXw[TT * LD];
+  __shared__ __attribute__((aligned(16))) uint16_t sWVt[D * LP];
+  __shared__ __attribute__((aligned(16))) uint16_t sPh[128 * LP];
+  __shared__ __attribute__((aligned(16))) uint16_t sPl[128 * LP];
+  __shared__ float2 sNorm[TT];
 
   const uint32_t unit = blockIdx.y, b = unit / p.Hkv, h = unit % p.Hkv;
-  const uint32_t m0 = blockIdx.x * 64, T = p.T;
+  const uint32_t m0 = blockIdx.x * 128, T = p.T;
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64, col = lane % 32, half = lane / 32;
   const size_t units = (size_t)p.B * p.Hkv;
   const uint16_t* mk = p.mk + (size_t)(p.mk_per_seq ? unit : h) * p.M * D;
   uint16_t* mv = p.mv + ((size_t)unit * p.M + m0) * D;
 
-  {
-    Tile<64, D, NT> t;
-    t.fetch_block(mk + (size_t)m0 * D, D);
-    t.put(sK, LD);
-  }
-
-  // state product: wavefront = (slot half, 32-column block); lane column = value column
-  const int mslot = 32 * (wave & 1), mcol = 32 * (wave >> 1);
-  const bool has_cols = mcol < D;  // with d = 64 only four wavefronts have columns
-  f32x16 macc = zero16();
-  if (has_cols) {
-#pragma unroll
-    for (int v = 0; v < 16; ++v)
-      macc[v] = bf16_val(mv[(size_t)(mslot + 8 * (v / 4) + 4 * half + (v % 4)) * D + mcol + col]);
-  }
-
-  // the key tile does not change over the loop: keep this wavefront's key
-  // fragments (32 slots) in registers
-  __syncthreads();
+  // both roles of a wavefront use the same 32 slots; M is a multiple of 64, so
+  // the 32 slots are all inside the memory or all outside
+  const int sg = wave & 3, hi2 = wave >> 2;
+  const bool live = m0 + 32 * sg < p.M;
   bf16x8 kb[KS];
 #pragma unroll
-  for (int ks = 0; ks < KS; ++ks) kb[ks] = frag(sK, LD, 32 * (wave >> 2) + col, ks * 16 + half * 8);
+  for (int ks = 0; ks < KS; ++ks) {
+    u32x4 v = {0u, 0u, 0u, 0u};
+    if (live) v = *(const u32x4*)(mk + (size_t)(m0 + 32 * sg + col) * D + ks * 16 + half * 8);
+    kb[ks] = __builtin_bit_cast(bf16x8, v);
+  }
+  // state product: lane column = value column, accumulator rows = slots
+  const int mslot = 32 * sg, mcol = (D / 2) * hi2;
+  f32x16 macc[SNJ];
+#pragma unroll
+  for (int jt = 0; jt < SNJ; ++jt) {
+    macc[jt] = zero16();
+    if (live) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v)
+        macc[jt][v] = bf16_val(mv[(size_t)(mslot + 8 * (v / 4) + 4 * half + (v % 4)) * D + mcol + 32 * jt + col]);
+    }
+  }
 
-  const uint32_t nb = (T + kTC - 1) / kTC;
-  Tile<kTC, D, NT> tx;
-  Tile<D, kTC, NT> tw;
+  const uint32_t ntile = (T + TT - 1) / TT;
+  Tile<TT, D, NT> tx;
+  Tile<D, TT, NT> tw;
   float2 tn = make_float2(0.f, 0.f);
   auto fetch_tokens = [&](uint32_t t0) {
     tx.fetch_rows(p.mk, [&](int r) -> const uint16_t* {
       return t0 + r < T ? p.wq + (((size_t)b * T + t0 + r) * p.Hkv + h) * D : nullptr;
     });
     tw.fetch_block(p.wvt + (size_t)unit * D * p.Tpad + t0, p.Tpad);
-    if (threadIdx.x < kTC)
-      tn = (t0 + threadIdx.x < T) ? p.norm_w[(size_t)unit * T + t0 + threadIdx.x] : make_float2(0.f, 0.f);
+    if (threadIdx.x < TT)
+      tn = p.norm_w[(size_t)unit * T + (t0 + threadIdx.x < T ? t0 + threadIdx.x : 0u)];
   };
   fetch_tokens(0);
-  for (uint32_t c = 0; c < nb; ++c) {
-    const uint32_t t0 = c * kTC;
-    if (p.has_read && c > 0 && has_cols) {
+  for (uint32_t tt = 0; tt < ntile; ++tt) {
+    const uint32_t t0 = tt * TT;
+    if (p.has_read && tt > 0 && (t0 % kTC) == 0 && live) {
       // MV at the start of sub-chunk c, transposed ([column][slot]) for the read kernel
-      uint16_t* sn = p.snap + ((size_t)c * units + unit) * p.M * D + m0 + mslot + 4 * half;
+      uint16_t* sn = p.snap + ((size_t)(t0 / kTC) * units + unit) * p.M * D + m0 + mslot + 4 * half;
 #pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4)
-        store4_bf16(sn + (size_t)(mcol + col) * p.M + 8 * q4, macc[4 * q4 + 0], macc[4 * q4 + 1], macc[4 * q4 + 2],
-                    macc[4 * q4 + 3]);
+      for (int jt = 0; jt < SNJ; ++jt)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4)
+          store4_bf16(sn + (size_t)(mcol + 32 * jt + col) * p.M + 8 * q4, macc[jt][4 * q4 + 0], macc[jt][4 * q4 + 1],
+                      macc[jt][4 * q4 + 2], macc[jt][4 * q4 + 3]);
     }
     __syncthreads();
     tx.put(sXw, LD);
-    tw.put(sWVt, LT);
-    if (threadIdx.x < kTC) sNorm[threadIdx.x] = tn;
-    if (c + 1 < nb) fetch_tokens(t0 + kTC);  // next sub-chunk, in flight during this one's products
+    tw.put(sWVt, LP);
+    if (threadIdx.x < TT) sNorm[threadIdx.x] = (t0 + threadIdx.x < T) ? tn : make_float2(0.f, 0.f);
+    if (tt + 1 < ntile) fetch_tokens(t0 + TT);  // next tile, in flight during this one's products
     __syncthreads();
     {
-      // scores: rows = tokens (32 per wavefront), columns = slots (32 per wavefront)
-      const int tok0 = 32 * (wave & 3), sl0 = 32 * (wave >> 2);
+      // scores: rows = tokens (32 per wavefront), columns = this wavefront's 32 slots
+      const int tok0 = 32 * hi2;
       f32x16 sc = zero16();
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        const int k = ks * 16 + half * 8;
-        sc = mfma_bf16(frag(sXw, LD, tok0 + col, k), kb[ks], sc);
-      }
+      for (int ks = 0; ks < KS; ++ks) sc = mfma_bf16(frag(sXw, LD, tok0 + col, ks * 16 + half * 8), kb[ks], sc);
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
         const int tl = tok0 + 8 * q4 + 4 * half;
@@ -558,25 +563,29 @@ __global__ __launch_bounds__(512) void prefill_state_kernel(const PrefillParams 
           hi[i] = bf16_val(bf16_bits(w));
           lo[i] = w - hi[i];
         }
-        store4_bf16(sPh + (sl0 + col) * LT + tl, hi[0], hi[1], hi[2], hi[3]);
-        store4_bf16(sPl + (sl0 + col) * LT + tl, lo[0], lo[1], lo[2], lo[3]);
+        store4_bf16(sPh + (mslot + col) * LP + tl, hi[0], hi[1], hi[2], hi[3]);
+        store4_bf16(sPl + (mslot + col) * LP + tl, lo[0], lo[1], lo[2], lo[3]);
       }
     }
     __syncthreads();
-    if (has_cols) {
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-        const int k = ks * 16 + half * 8;
-        const bf16x8 bv = frag(sWVt, LT, mcol + col, k);
-        macc = mfma_bf16(frag(sPh, LT, mslot + col, k), bv, macc);
-        macc = mfma_bf16(frag(sPl, LT, mslot + col, k), bv, macc);
+    for (int ks = 0; ks < TT / 16; ++ks) {
+      const int k = ks * 16 + half * 8;
+      const bf16x8 ah = frag(sPh, LP, mslot + col, k), al = frag(sPl, LP, mslot + col, k);
+#pragma unroll
+      for (int jt = 0; jt < SNJ; ++jt) {
+        const bf16x8 bv = frag(sWVt, LP, mcol + 32 * jt + col, k);
+        macc[jt] = mfma_bf16(ah, bv, macc[jt]);
+        macc[jt] = mfma_bf16(al, bv, macc[jt]);
       }
     }
   }
-  if (has_cols) {
+  if (live) {
 #pragma unroll
-    for (int v = 0; v < 16; ++v)
-      mv[(size_t)(mslot + 8 * (v / 4) + 4 * half + (v % 4)) * D + mcol + col] = bf16_bits(macc[v]);
+    for (int jt = 0; jt < SNJ; ++jt)
+#pragma unroll
+      for (int v = 0; v < 16; ++v)
+        mv[(size_t)(mslot + 8 * (v / 4) + 4 * half + (v % 4)) * D + mcol + 32 * jt + col] = bf16_bits(macc[jt][v]);
   }
 }
 
@@ -624,7 +633,7 @@ hipError_t launch_prefill_bf16(const PrefillParams& p0, hipStream_t s) {
     if ((e = read(0, p.has_write ? 1u : nb)) != hipSuccess) return e;
   }
   if (p.has_write) {
-    const dim3 g(p.M / 64, units);
+    const dim3 g((p.M + 127) / 128, units);
     if (d128) hipLaunchKernelGGL(prefill_state_kernel<128>, g, dim3(512), 0, s, p);
     else hipLaunchKernelGGL(prefill_state_kernel<64>, g, dim3(512), 0, s, p);
     if ((e = hipGetLastError()) != hipSuccess) return e;
