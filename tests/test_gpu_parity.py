@@ -107,6 +107,9 @@ SMALL = [
     ("bf16_d128_gqa3", 2, 6, 2, 128, 64, "bf16"),
     ("f32_d64_gqa5", 1, 5, 1, 64, 64, "f32"),
     ("bf16_d128_m2112", 2, 2, 2, 128, 2112, "bf16"),   # 33 chunks of 64: ragged split of the MV pass
+    ("bf16_m65536", 1, 1, 1, 128, 65536, "bf16"),       # the largest capacity the library accepts
+    ("f32_d128_m65536", 1, 1, 1, 128, 65536, "f32"),
+    ("bf16_gqa8_m4160", 1, 8, 1, 128, 4160, "bf16"),    # 8 query heads per KV head, 65 chunks of 64
 ]
 
 

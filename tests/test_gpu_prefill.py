@@ -86,6 +86,8 @@ CASES = [
     ("bf16_gqa4_T300", 1, 8, 2, 128, 192, "bf16", 300),
     ("bf16_gqa3_T70", 1, 3, 1, 128, 64, "bf16", 70),
     ("bf16_T512", 1, 2, 2, 128, 1024, "bf16", 512),
+    ("bf16_m65536_T64", 1, 1, 1, 128, 65536, "bf16", 64),     # the largest capacity
+    ("bf16_m192_T257", 1, 2, 1, 128, 192, "bf16", 257),        # last state workgroup half empty, one token in the last sub-chunk
 ]
 
 
