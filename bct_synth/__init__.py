@@ -219,3 +219,41 @@ def make_step(w: Workload, step: int, layer: int = 0, T: int = 0):
     return (np.ascontiguousarray(np.stack(qs, axis=1)),
             np.ascontiguousarray(np.stack(wqs, axis=1)),
             np.ascontiguousarray(np.stack(wvs, axis=1)))
+
+
+# ---------------------------------------------------------------- decoder-stack weights
+
+STACK_WEIGHT_ORDER = ("attn_norm", "w_q", "w_wq", "w_wv", "w_o", "mlp_norm", "w_gate", "w_up", "w_down")
+
+
+def make_stack_weights(shape, seed: int = 0):
+    """Random-init weights of a Llama-shaped stack as bf16 bit patterns.
+
+    shape: an object with n_layers, dim, n_q_heads, n_kv_heads, head_dim, ffn, vocab, capacity_M and a
+    weight_shapes() dictionary.  Matrices ~ N(0, 1/fan_in) (the usual variance-preserving init), except that
+    the three attention projections are scaled so that their outputs have unit variance like the q / wq / wv
+    of the attention-only workloads; norm gains ~ 1 + 0.1 N(0,1); embedding ~ N(0,1); keys MK ~ N(0,1).
+    """
+    base = layer_seed(0) + 7919 * (seed + 1)
+    tid = [0]
+
+    def draw(shp, std, mean=0.0):
+        tid[0] += 1
+        return pack(mean + std * normal(base, TID_WEIGHTS, tid[0], shp), "bf16")
+
+    layers = []
+    for _ in range(shape.n_layers):
+        lw = {}
+        for name, shp in shape.weight_shapes().items():
+            if len(shp) == 1:
+                lw[name] = draw(shp, 0.1, 1.0)
+            else:
+                lw[name] = draw(shp, 1.0 / np.sqrt(shp[1]))
+        layers.append(lw)
+    keys = [draw((shape.n_kv_heads, shape.capacity_M, shape.head_dim), 1.0) for _ in range(shape.n_layers)]
+    return {"embed": draw((shape.vocab, shape.dim), 1.0), "final_norm": draw((shape.dim,), 0.1, 1.0),
+            "head": draw((shape.vocab, shape.dim), 1.0 / np.sqrt(shape.dim)), "layers": layers, "keys": keys}
+
+
+def make_token_ids(seed: int, step: int, count: int, vocab: int) -> np.ndarray:
+    return integers(layer_seed(0) + seed, TID_TOKENS, step, (count,), vocab).astype(np.int32)

@@ -1,0 +1,59 @@
+/* libbct -- the Llama-shaped glue around the bounded-cache attention layer.
+ *
+ * The paper applies its mechanism to "the attention layers" of a decoder-only
+ * Transformer and obtains the write query and the write key-value vector from
+ * the layer input with two learnable matrices (section 3.2 step 1, Algorithm 1:
+ * wq_t = W_wq x_t, wv_t = W_wv x_t).  These entry points are the dense pieces
+ * of such a stack, so that a token can go through whole layers on the GPU:
+ * embedding lookup, RMS normalisation, the projections (W_q, W_wq, W_wv, W_o,
+ * the SwiGLU MLP, the output head) and the greedy arg-max.  The attention
+ * itself stays bct_decode_step / bct_prefill (include/bct.h).
+ *
+ * All data pointers are DEVICE memory owned by the caller, bf16, row-major,
+ * 16-byte aligned; token ids are int32.  Calls enqueue on the given stream and
+ * return.  Status codes are those of include/bct.h.
+ */
+#ifndef BCT_MODEL_H
+#define BCT_MODEL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#include "bct.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* out[r][:] = table[ids[r]][:], r < rows.  table [vocab][dim]; dim a multiple of 8.
+ * Ids outside [0, vocab) give a zero row. */
+bct_status bctm_embed(const int32_t* ids, const void* table, void* out, uint32_t rows, uint32_t vocab,
+                      uint32_t dim, void* hip_stream);
+
+/* out[r][:] = x[r][:] * rsqrt(mean(x[r][:]^2) + eps) * gain[:]   (fp32 arithmetic, bf16 in/out).
+ * dim a multiple of 8, at most 16384. */
+bct_status bctm_rmsnorm(const void* x, const void* gain, void* out, uint32_t rows, uint32_t dim, float eps,
+                        void* hip_stream);
+
+/* out[r][n] = (residual ? residual[r][n] : 0) + sum_k x[r][k] * w[n][k].
+ * x [rows][K], w [N][K] (one output feature per row of w), out/residual [rows][N];
+ * K a multiple of 64, N a multiple of 32; fp32 accumulation (MFMA), one rounding
+ * to bf16 at the end.  out may alias residual. */
+bct_status bctm_linear(const void* x, const void* w, const void* residual, void* out, uint32_t rows,
+                       uint32_t K, uint32_t N, void* hip_stream);
+
+/* out[r][n] = silu(sum_k x[r][k] w_gate[n][k]) * (sum_k x[r][k] w_up[n][k]),  silu(a) = a / (1 + exp(-a)).
+ * Same shape rules as bctm_linear. */
+bct_status bctm_swiglu(const void* x, const void* w_gate, const void* w_up, void* out, uint32_t rows,
+                       uint32_t K, uint32_t N, void* hip_stream);
+
+/* ids[r] = index of the largest logits[r][:] (the lowest index among equal maxima). */
+bct_status bctm_argmax(const void* logits, int32_t* ids, uint32_t rows, uint32_t N, void* hip_stream);
+
+/* Thread-local detail of the last failure of a bctm_ call. */
+const char* bctm_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BCT_MODEL_H */

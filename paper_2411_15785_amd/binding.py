@@ -60,6 +60,10 @@ def lib() -> ctypes.CDLL:
         raise FileNotFoundError(
             f"{LIB_PATH} is missing: build it with `python -m paper_2411_15785_amd.build` "
             "(there is no fallback path)")
+    # Device pointers and streams come from torch, so the library must run on the HIP runtime
+    # torch has loaded: import torch first, and the loader resolves libamdhip64 to that copy.
+    # Loaded the other way round, the process holds two runtimes and launches fail.
+    _torch()
     L = ctypes.CDLL(LIB_PATH)
     vp, sz, u32, u64 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_uint32, ctypes.c_uint64
     dp = ctypes.POINTER(bct_cache_desc)

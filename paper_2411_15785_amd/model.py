@@ -1,0 +1,250 @@
+"""ctypes binding of the bctm_ entry points (include/bct_model.h) and a driver that
+chains them with the bounded-cache attention into a Llama-shaped decoder.
+
+The driver holds weights and activations as torch tensors (device memory) and
+calls the library once per operation on torch's current stream; it does no
+arithmetic of its own.  There is no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import math
+from dataclasses import dataclass
+
+from . import binding
+from .binding import BCT_OK, BctCache, BctError, _dptr, _stream_ptr, _torch
+
+MODEL_EXPORTS = ["bctm_embed", "bctm_rmsnorm", "bctm_linear", "bctm_swiglu", "bctm_argmax", "bctm_last_error"]
+
+_ready = False
+
+
+def mlib() -> ctypes.CDLL:
+    """libbct.so with the bctm_ prototypes set."""
+    global _ready
+    L = binding.lib()
+    if _ready:
+        return L
+    vp, u32 = ctypes.c_void_p, ctypes.c_uint32
+    L.bctm_embed.argtypes = [vp, vp, vp, u32, u32, u32, vp]
+    L.bctm_rmsnorm.argtypes = [vp, vp, vp, u32, u32, ctypes.c_float, vp]
+    L.bctm_linear.argtypes = [vp, vp, vp, vp, u32, u32, u32, vp]
+    L.bctm_swiglu.argtypes = [vp, vp, vp, vp, u32, u32, u32, vp]
+    L.bctm_argmax.argtypes = [vp, vp, u32, u32, vp]
+    for n in MODEL_EXPORTS[:-1]:
+        getattr(L, n).restype = ctypes.c_int
+    L.bctm_last_error.argtypes = []
+    L.bctm_last_error.restype = ctypes.c_char_p
+    _ready = True
+    return L
+
+
+class BctModelError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        L = mlib()
+        super().__init__(f"{where}: {L.bct_strerror(status).decode()} ({status}): {L.bctm_last_error().decode()}")
+
+
+def _ck(st, where):
+    if st != BCT_OK:
+        raise BctModelError(st, where)
+
+
+def _bf16_2d(t, name, cols=None):
+    torch = _torch()
+    if t.dtype != torch.bfloat16 or t.dim() != 2 or not t.is_contiguous() or not t.is_cuda or \
+            (cols is not None and t.shape[1] != cols):
+        raise ValueError(f"{name}: expected a contiguous 2-D bf16 device tensor"
+                         + (f" with {cols} columns" if cols is not None else "")
+                         + f", got {t.dtype} {tuple(t.shape)} on {t.device}")
+
+
+def bctm_embed(ids, table, out=None):
+    torch = _torch()
+    _bf16_2d(table, "table")
+    if ids.dtype != torch.int32 or ids.dim() != 1 or not ids.is_contiguous() or ids.device != table.device:
+        raise ValueError("ids: expected a contiguous 1-D int32 tensor on the table's device")
+    if out is None:
+        out = torch.empty((ids.numel(), table.shape[1]), dtype=torch.bfloat16, device=table.device)
+    _bf16_2d(out, "out", table.shape[1])
+    if out.shape[0] != ids.numel():
+        raise ValueError("out: one row per id")
+    with torch.cuda.device(table.device):
+        _ck(mlib().bctm_embed(_dptr(ids), _dptr(table), _dptr(out), ids.numel(), table.shape[0], table.shape[1],
+                              _stream_ptr()), "bctm_embed")
+    return out
+
+
+def bctm_rmsnorm(x, gain, eps, out=None):
+    torch = _torch()
+    _bf16_2d(x, "x")
+    if gain.dtype != torch.bfloat16 or tuple(gain.shape) != (x.shape[1],) or not gain.is_contiguous() \
+            or gain.device != x.device:
+        raise ValueError("gain: expected a contiguous bf16 vector of x's row length on x's device")
+    if out is None:
+        out = torch.empty_like(x)
+    _bf16_2d(out, "out", x.shape[1])
+    if out.shape[0] != x.shape[0]:
+        raise ValueError("out: x's shape")
+    with torch.cuda.device(x.device):
+        _ck(mlib().bctm_rmsnorm(_dptr(x), _dptr(gain), _dptr(out), x.shape[0], x.shape[1], eps, _stream_ptr()),
+            "bctm_rmsnorm")
+    return out
+
+
+def bctm_linear(x, w, residual=None, out=None):
+    torch = _torch()
+    _bf16_2d(x, "x")
+    _bf16_2d(w, "w", x.shape[1])
+    rows, N = x.shape[0], w.shape[0]
+    if out is None:
+        out = torch.empty((rows, N), dtype=torch.bfloat16, device=x.device)
+    _bf16_2d(out, "out", N)
+    if residual is not None:
+        _bf16_2d(residual, "residual", N)
+    if out.shape[0] != rows or (residual is not None and residual.shape[0] != rows):
+        raise ValueError("out / residual: one row per row of x")
+    with torch.cuda.device(x.device):
+        _ck(mlib().bctm_linear(_dptr(x), _dptr(w), _dptr(residual), _dptr(out), rows, x.shape[1], N,
+                               _stream_ptr()), "bctm_linear")
+    return out
+
+
+def bctm_swiglu(x, w_gate, w_up, out=None):
+    torch = _torch()
+    _bf16_2d(x, "x")
+    _bf16_2d(w_gate, "w_gate", x.shape[1])
+    _bf16_2d(w_up, "w_up", x.shape[1])
+    if w_gate.shape != w_up.shape:
+        raise ValueError("w_gate and w_up: same shape")
+    rows, N = x.shape[0], w_gate.shape[0]
+    if out is None:
+        out = torch.empty((rows, N), dtype=torch.bfloat16, device=x.device)
+    _bf16_2d(out, "out", N)
+    if out.shape[0] != rows:
+        raise ValueError("out: one row per row of x")
+    with torch.cuda.device(x.device):
+        _ck(mlib().bctm_swiglu(_dptr(x), _dptr(w_gate), _dptr(w_up), _dptr(out), rows, x.shape[1], N,
+                               _stream_ptr()), "bctm_swiglu")
+    return out
+
+
+def bctm_argmax(logits, out=None):
+    torch = _torch()
+    _bf16_2d(logits, "logits")
+    if out is None:
+        out = torch.empty(logits.shape[0], dtype=torch.int32, device=logits.device)
+    if out.dtype != torch.int32 or tuple(out.shape) != (logits.shape[0],) or not out.is_contiguous():
+        raise ValueError("out: a contiguous int32 vector, one entry per row")
+    with torch.cuda.device(logits.device):
+        _ck(mlib().bctm_argmax(_dptr(logits), _dptr(out), logits.shape[0], logits.shape[1], _stream_ptr()),
+            "bctm_argmax")
+    return out
+
+
+# ------------------------------------------------------------------ the stack
+
+
+@dataclass(frozen=True)
+class StackShape:
+    """A Llama-shaped decoder whose attention layers are bounded caches (section 3.2)."""
+    n_layers: int
+    dim: int            # model width
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    ffn: int            # SwiGLU hidden width
+    vocab: int
+    capacity_M: int
+    batch: int
+    eps: float = 1e-5
+
+    @property
+    def q_width(self):
+        return self.n_q_heads * self.head_dim
+
+    @property
+    def kv_width(self):
+        return self.n_kv_heads * self.head_dim
+
+    def weight_shapes(self):
+        """name -> shape of every per-layer weight, in the order load_layer expects."""
+        return {"attn_norm": (self.dim,), "w_q": (self.q_width, self.dim), "w_wq": (self.kv_width, self.dim),
+                "w_wv": (self.kv_width, self.dim), "w_o": (self.dim, self.q_width), "mlp_norm": (self.dim,),
+                "w_gate": (self.ffn, self.dim), "w_up": (self.ffn, self.dim), "w_down": (self.dim, self.ffn)}
+
+    def weight_bytes(self):
+        per_layer = sum(math.prod(s) for s in self.weight_shapes().values())
+        return 2 * (self.n_layers * per_layer + 2 * self.vocab * self.dim + self.dim)
+
+
+class BctStack:
+    """Token ids in, greedy next ids out: embedding, n_layers x (RMSNorm, W_q / W_wq / W_wv,
+    bounded-cache attention, W_o + residual, RMSNorm, SwiGLU MLP + residual), RMSNorm, output head, arg-max.
+
+    weights: {"embed": [vocab][dim], "final_norm": [dim], "head": [vocab][dim],
+              "layers": [ {name: tensor} per layer, names of StackShape.weight_shapes() ],
+              "keys": [ MK per layer, [Hkv][M][d] ]}  -- all bf16 device tensors.
+    """
+
+    def __init__(self, shape: StackShape, weights, max_prefill_T=0, device="cuda:0"):
+        torch = _torch()
+        self.shape, self.w = shape, weights
+        self.device = torch.device(device)
+        s = shape
+        self.caches = []
+        ws = None
+        for l in range(s.n_layers):
+            c = BctCache(s.capacity_M, s.batch, s.n_q_heads, s.n_kv_heads, s.head_dim, torch.bfloat16,
+                         max_prefill_T=max_prefill_T, device=device, workspace=ws)
+            ws = c._workspace          # one stream steps the layers in turn: they share the workspace
+            c.set_keys(weights["keys"][l])
+            c.set_values(None)
+            self.caches.append(c)
+        for l, lw in enumerate(weights["layers"]):
+            for n, shp in s.weight_shapes().items():
+                if tuple(lw[n].shape) != shp or lw[n].dtype != torch.bfloat16:
+                    raise ValueError(f"layer {l} {n}: expected bf16 {shp}")
+        self._bufs = {}
+
+    def _buf(self, name, rows, cols):
+        torch = _torch()
+        k = (name, rows, cols)
+        if k not in self._bufs:
+            self._bufs[k] = torch.empty((rows, cols), dtype=torch.bfloat16, device=self.device)
+        return self._bufs[k]
+
+    def forward(self, ids, T=1):
+        """ids int32 [B*T] (sequence-major: row b*T + t) -> (next ids int32 [B*T], logits [B*T][vocab]).
+        T = 1 is a decode step; T > 1 pushes a chunk of T tokens per sequence through bct_prefill."""
+        s = self.shape
+        rows = s.batch * T
+        if ids.numel() != rows:
+            raise ValueError(f"ids: expected {rows} entries")
+        x = bctm_embed(ids, self.w["embed"], self._buf("x", rows, s.dim))
+        h = self._buf("h", rows, s.dim)
+        q, wq, wv = self._buf("q", rows, s.q_width), self._buf("wq", rows, s.kv_width), self._buf("wv", rows, s.kv_width)
+        a, f = self._buf("a", rows, s.q_width), self._buf("f", rows, s.ffn)
+        for l, lw in enumerate(self.w["layers"]):
+            bctm_rmsnorm(x, lw["attn_norm"], s.eps, h)
+            bctm_linear(h, lw["w_q"], None, q)
+            bctm_linear(h, lw["w_wq"], None, wq)
+            bctm_linear(h, lw["w_wv"], None, wv)
+            c = self.caches[l]
+            if T == 1:
+                c.decode_step(q.view(s.batch, s.n_q_heads, s.head_dim), wq.view(s.batch, s.n_kv_heads, s.head_dim),
+                              wv.view(s.batch, s.n_kv_heads, s.head_dim),
+                              a.view(s.batch, s.n_q_heads, s.head_dim))
+            else:
+                c.prefill(q.view(s.batch, T, s.n_q_heads, s.head_dim), wq.view(s.batch, T, s.n_kv_heads, s.head_dim),
+                          wv.view(s.batch, T, s.n_kv_heads, s.head_dim), T,
+                          a.view(s.batch, T, s.n_q_heads, s.head_dim))
+            bctm_linear(a, lw["w_o"], x, x)
+            bctm_rmsnorm(x, lw["mlp_norm"], s.eps, h)
+            bctm_swiglu(h, lw["w_gate"], lw["w_up"], f)
+            bctm_linear(f, lw["w_down"], x, x)
+        bctm_rmsnorm(x, self.w["final_norm"], s.eps, h)
+        logits = bctm_linear(h, self.w["head"], None, self._buf("logits", rows, s.vocab))
+        nxt = bctm_argmax(logits, None)
+        return nxt, logits

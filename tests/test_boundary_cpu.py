@@ -20,10 +20,10 @@ def L():
     return P.lib()
 
 
-def declared_functions():
-    src = open(os.path.join(ROOT, "include", "bct.h")).read()
+def declared_functions(header="bct.h", prefix="bct_"):
+    src = open(os.path.join(ROOT, "include", header)).read()
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
-    return sorted(set(re.findall(r"\b(bct_[a-z_]+)\s*\(", src)))
+    return sorted(set(re.findall(r"\b(" + prefix + r"[a-z_]+)\s*\(", src)))
 
 
 def test_every_declared_symbol_is_exported_and_bound(L):
@@ -32,6 +32,36 @@ def test_every_declared_symbol_is_exported_and_bound(L):
     for n in names:
         assert hasattr(L, n), f"{n} is declared in include/bct.h but not exported by libbct.so"
     assert sorted(binding.EXPORTS) == names      # the binding names exactly the header's functions
+
+
+def test_every_declared_model_symbol_is_exported_and_bound(L):
+    from paper_2411_15785_amd import model
+    names = declared_functions("bct_model.h", "bctm_")
+    assert {"bctm_linear", "bctm_swiglu", "bctm_rmsnorm", "bctm_embed", "bctm_argmax"} <= set(names)
+    ML = model.mlib()
+    for n in names:
+        assert hasattr(ML, n), f"{n} is declared in include/bct_model.h but not exported by libbct.so"
+    assert sorted(model.MODEL_EXPORTS) == names
+
+
+def test_model_entry_points_check_arguments_before_touching_the_gpu(L):
+    from paper_2411_15785_amd import model
+    ML = model.mlib()
+    p = ctypes.c_void_p
+    a, b, c = p(0x10000), p(0x20000), p(0x30000)
+    assert ML.bctm_linear(a, b, None, c, 4, 72, 32, None) == P.BCT_ERR_UNSUPPORTED       # K % 64
+    assert ML.bctm_linear(a, b, None, c, 4, 64, 40, None) == P.BCT_ERR_UNSUPPORTED       # N % 32
+    assert ML.bctm_linear(a, None, None, c, 4, 64, 32, None) == P.BCT_ERR_INVALID_ARG
+    assert ML.bctm_linear(a, b, None, c, 0, 64, 32, None) == P.BCT_ERR_INVALID_ARG
+    assert ML.bctm_linear(p(0x10008), b, None, c, 4, 64, 32, None) == P.BCT_ERR_MISALIGNED
+    assert ML.bctm_linear(a, b, p(0x40004), c, 4, 64, 32, None) == P.BCT_ERR_MISALIGNED
+    assert ML.bctm_swiglu(a, b, None, c, 4, 64, 32, None) == P.BCT_ERR_INVALID_ARG
+    assert ML.bctm_rmsnorm(a, b, c, 4, 12, 1e-5, None) == P.BCT_ERR_UNSUPPORTED          # dim % 8
+    assert ML.bctm_rmsnorm(a, b, c, 4, 32768, 1e-5, None) == P.BCT_ERR_UNSUPPORTED
+    assert ML.bctm_embed(None, b, c, 4, 10, 64, None) == P.BCT_ERR_INVALID_ARG
+    assert ML.bctm_embed(a, b, c, 4, 10, 12, None) == P.BCT_ERR_UNSUPPORTED
+    assert ML.bctm_argmax(a, None, 4, 10, None) == P.BCT_ERR_INVALID_ARG
+    assert ML.bctm_last_error().decode() != ""
 
 
 def desc(**kw):

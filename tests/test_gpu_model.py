@@ -1,0 +1,191 @@
+"""GPU parity of the bctm_ entry points (include/bct_model.h) and of the decoder stack built
+from them, against oracle/model_ref, element by element on the same seeded inputs.
+
+Tolerances.  The kernels accumulate in fp32 and round once to bf16; the oracle computes in
+fp64 and rounds once.  The two bf16 results therefore differ by at most one bf16 spacing
+where the exact value lies near a rounding boundary, plus the fp32 accumulation error,
+bounded here by 2^-20 * sum_k |x_k w_k| (K * 2^-24 with K <= 16 times headroom for the
+split-K order).  Arg-max and embedding are integer / byte work: bit-exact.
+"""
+import numpy as np
+import pytest
+
+import bct_synth as syn
+from _util import bf16_ulp, to_dev, to_np
+from oracle import model_ref as R
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def M():
+    from paper_2411_15785_amd import model
+    model.mlib()
+    return model
+
+
+def dev(a):
+    return to_dev(a, "bf16")
+
+
+def host(t):
+    return to_np(t, "bf16")
+
+
+def draw(tid, shape, std=1.0):
+    return syn.pack(std * syn.normal(11, 9, tid, shape), "bf16")
+
+
+def check_close(got_bits, ref_bits, slack, what):
+    got, ref = R.bf16_to_f64(got_bits), R.bf16_to_f64(ref_bits)
+    tol = bf16_ulp(ref) + slack
+    bad = np.abs(got - ref) > tol
+    assert not bad.any(), f"{what}: {bad.sum()} of {bad.size} beyond 1 ulp + slack, worst " \
+                          f"{np.max(np.abs(got - ref) / tol):.2f}x at {np.unravel_index(np.argmax(np.abs(got - ref) / tol), got.shape)}"
+
+
+LIN_SHAPES = [  # rows, K, N
+    (1, 64, 32), (5, 64, 96), (32, 192, 64), (33, 320, 32), (70, 1024, 160), (32, 4096, 256), (3, 11008, 64),
+]
+
+
+@pytest.mark.parametrize("rows,K,N", LIN_SHAPES)
+@pytest.mark.parametrize("with_res", [False, True])
+def test_linear(M, rows, K, N, with_res):
+    x, w = draw(1, (rows, K)), draw(2, (N, K), K ** -0.5)
+    res = draw(3, (rows, N)) if with_res else None
+    out = M.bctm_linear(dev(x), dev(w), dev(res) if with_res else None)
+    mass = np.abs(R.bf16_to_f64(x)) @ np.abs(R.bf16_to_f64(w)).T
+    check_close(host(out), R.linear(x, w, res), 2.0 ** -20 * mass, f"linear {rows}x{K}x{N}")
+
+
+def test_linear_in_place_residual(M):
+    rows, K, N = 7, 256, 128
+    x, w, res = draw(1, (rows, K)), draw(2, (N, K), K ** -0.5), draw(3, (rows, N))
+    buf = dev(res)
+    out = M.bctm_linear(dev(x), dev(w), buf, buf)
+    assert out.data_ptr() == buf.data_ptr()
+    mass = np.abs(R.bf16_to_f64(x)) @ np.abs(R.bf16_to_f64(w)).T
+    check_close(host(buf), R.linear(x, w, res), 2.0 ** -20 * mass, "linear in place")
+
+
+def test_linear_selects_the_right_operands(M):
+    # one-hot weight rows pick input features: exact, and fails for a transposed or shifted operand
+    rows, K, N = 9, 128, 64
+    x = draw(4, (rows, K))
+    sel = (np.arange(N) * 37 + 5) % K
+    w = np.zeros((N, K), dtype=np.float32)
+    w[np.arange(N), sel] = 1.0
+    wb = (w.view(np.uint32) >> 16).astype(np.uint16)
+    out = host(M.bctm_linear(dev(x), dev(wb)))
+    assert np.array_equal(out, x[:, sel])
+
+
+@pytest.mark.parametrize("rows,K,N", [(1, 64, 32), (6, 192, 96), (32, 4096, 352), (40, 512, 64)])
+def test_swiglu(M, rows, K, N):
+    x, wg, wu = draw(5, (rows, K)), draw(6, (N, K), 2.0 * K ** -0.5), draw(7, (N, K), K ** -0.5)
+    out = M.bctm_swiglu(dev(x), dev(wg), dev(wu))
+    xa = np.abs(R.bf16_to_f64(x))
+    g, u = R.linear_f64(x, wg), R.linear_f64(x, wu)
+    mg, mu = xa @ np.abs(R.bf16_to_f64(wg)).T, xa @ np.abs(R.bf16_to_f64(wu)).T
+    # d(silu)/dg is at most 1.1; the fast exponential adds a relative 2^-20 to silu
+    slack = 2.0 ** -20 * (1.1 * mg * np.abs(u) + (np.abs(g) + 1.0) * mu + np.abs(g * u))
+    check_close(host(out), R.swiglu(x, wg, wu), slack, f"swiglu {rows}x{K}x{N}")
+
+
+@pytest.mark.parametrize("rows,dim", [(1, 8), (3, 64), (5, 520), (32, 4096), (9, 16384)])
+def test_rmsnorm(M, rows, dim):
+    x, g = draw(8, (rows, dim), 3.0), syn.pack(1.0 + 0.1 * syn.normal(11, 9, 9, (dim,)), "bf16")
+    out = M.bctm_rmsnorm(dev(x), dev(g), 1e-5)
+    ref = R.rmsnorm(x, g, 1e-5)
+    check_close(host(out), ref, 2.0 ** -20 * np.abs(R.bf16_to_f64(ref)), f"rmsnorm {rows}x{dim}")
+
+
+def test_embed_and_argmax_are_exact(M):
+    import torch
+    vocab, dim = 1000, 264
+    table = draw(10, (vocab, dim))
+    ids = np.array([0, 999, 5, 5, 1000, -1, 123], dtype=np.int32)
+    out = host(M.bctm_embed(torch.from_numpy(ids).cuda(), dev(table)))
+    assert np.array_equal(out, R.embed(ids, table))
+    for rows, N in [(1, 32), (4, 1000), (33, 32000), (2, 7)]:
+        lg = draw(12, (rows, N))
+        lg[0, : min(N, 5)] = 0x7F00            # several equal maxima: the lowest index wins
+        lg[rows - 1, N - 1] = 0x7F00
+        got = M.bctm_argmax(dev(lg)).cpu().numpy()
+        assert np.array_equal(got, R.argmax(lg)), (rows, N)
+        assert got[0] == 0
+
+
+def test_argument_errors(M):
+    import torch
+    x = torch.zeros((4, 72), dtype=torch.bfloat16, device="cuda")
+    w = torch.zeros((32, 72), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(M.BctModelError) as e:
+        M.bctm_linear(x, w)                      # K not a multiple of 64
+    assert e.value.status == 2
+    x = torch.zeros((4, 64), dtype=torch.bfloat16, device="cuda")
+    w = torch.zeros((40, 64), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(M.BctModelError):
+        M.bctm_linear(x, w)                      # N not a multiple of 32
+    with pytest.raises(ValueError):
+        M.bctm_linear(x, w.float())
+
+
+# ---------------------------------------------------------------- the stack
+
+def stack_pair(M, shape, seed, max_prefill_T=0):
+    w = syn.make_stack_weights(shape, seed=seed)
+    wd = {"embed": dev(w["embed"]), "final_norm": dev(w["final_norm"]), "head": dev(w["head"]),
+          "layers": [{k: dev(v) for k, v in lw.items()} for lw in w["layers"]],
+          "keys": [dev(k) for k in w["keys"]]}
+    return R.RefStack(shape, w), M.BctStack(shape, wd, max_prefill_T=max_prefill_T)
+
+
+def check_logits(got_bits, ref_bits, got_ids, ref_ids, rel, what):
+    got, ref = R.bf16_to_f64(got_bits), R.bf16_to_f64(ref_bits)
+    scale = np.max(np.abs(ref), axis=1, keepdims=True)
+    err = np.max(np.abs(got - ref) / scale)
+    assert err <= rel, f"{what}: logits differ by {err:.3e} of the row maximum (allowed {rel:.1e})"
+    # the greedy token must agree wherever the oracle's winner leads by more than the allowed error
+    srt = np.sort(ref, axis=1)
+    clear = (srt[:, -1] - srt[:, -2]) > 2 * rel * scale[:, 0]
+    assert np.array_equal(got_ids[clear], ref_ids[clear]), what
+    # and every token the GPU picked is within the allowed error of the oracle's best logit
+    assert np.all(ref[np.arange(len(ref)), got_ids] >= srt[:, -1] - 2 * rel * scale[:, 0]), what
+    return int(clear.sum())
+
+
+def test_stack_decode_teacher_forced(M):
+    """Eight decode steps of a 3-layer stack (GQA 2:1), both sides fed the same token ids.
+    Each operation is within one bf16 spacing of the oracle's; through 3 layers of ~10 roundings each the
+    logits stay within 2% of the row maximum (measured ~0.5%), which is what bf16 activations allow."""
+    import torch
+    s = M.StackShape(n_layers=3, dim=256, n_q_heads=4, n_kv_heads=2, head_dim=64, ffn=704, vocab=512,
+                     capacity_M=128, batch=5)
+    ref, gpu = stack_pair(M, s, seed=4)
+    n_clear = 0
+    for t in range(8):
+        ids = syn.make_token_ids(4, t, s.batch, s.vocab)
+        r_ids, r_lg = ref.forward(ids)
+        g_ids, g_lg = gpu.forward(torch.from_numpy(ids).cuda())
+        n_clear += check_logits(host(g_lg), r_lg, g_ids.cpu().numpy(), r_ids, 2e-2, f"step {t}")
+    assert n_clear >= 20         # the token comparison was not vacuous
+
+
+def test_stack_prefill_then_decode(M):
+    """A 37-token chunk through bct_prefill (row b*T + t), then two decode steps on the state it left."""
+    import torch
+    s = M.StackShape(n_layers=2, dim=128, n_q_heads=2, n_kv_heads=2, head_dim=64, ffn=256, vocab=256,
+                     capacity_M=192, batch=2)
+    T = 37
+    ref, gpu = stack_pair(M, s, seed=5, max_prefill_T=T)
+    ids = syn.make_token_ids(5, 0, s.batch * T, s.vocab)
+    r_ids, r_lg = ref.forward(ids, T=T)
+    g_ids, g_lg = gpu.forward(torch.from_numpy(ids).cuda(), T=T)
+    check_logits(host(g_lg), r_lg, g_ids.cpu().numpy(), r_ids, 2e-2, "chunk")
+    for t in range(2):
+        ids = syn.make_token_ids(5, 1 + t, s.batch, s.vocab)
+        r_ids, r_lg = ref.forward(ids)
+        g_ids, g_lg = gpu.forward(torch.from_numpy(ids).cuda())
+        check_logits(host(g_lg), r_lg, g_ids.cpu().numpy(), r_ids, 2e-2, f"decode {t}")
