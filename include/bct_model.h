@@ -35,16 +35,24 @@ bct_status bctm_embed(const int32_t* ids, const void* table, void* out, uint32_t
 bct_status bctm_rmsnorm(const void* x, const void* gain, void* out, uint32_t rows, uint32_t dim, float eps,
                         void* hip_stream);
 
+/* Repacks a row-major weight matrix w [N][K] (one output feature per row) into the streaming layout
+ * bctm_linear and bctm_swiglu read: 1 KB tiles of 16 features x 32 inputs, tile (n / 16, k / 32) at tile
+ * index (n / 16) * (K / 32) + k / 32; inside a tile, element (n, k) sits at bf16 offset
+ * 8 * (16 * ((k % 32) / 8) + n % 16) + k % 8.  Done once when weights are loaded.
+ * N a multiple of 16, K a multiple of 32; packed holds N * K bf16 and must not be w. */
+bct_status bctm_pack_weight(const void* w, void* packed, uint32_t N, uint32_t K, void* hip_stream);
+
 /* out[r][n] = (residual ? residual[r][n] : 0) + sum_k x[r][k] * w[n][k].
- * x [rows][K], w [N][K] (one output feature per row of w), out/residual [rows][N];
- * K a multiple of 64, N a multiple of 32; fp32 accumulation (MFMA), one rounding
- * to bf16 at the end.  out may alias residual. */
-bct_status bctm_linear(const void* x, const void* w, const void* residual, void* out, uint32_t rows,
+ * x [rows][K] row-major; w_packed = bctm_pack_weight of w [N][K]; out/residual [rows][N] row-major;
+ * K a multiple of 32, N a multiple of 16; fp32 accumulation (MFMA), one rounding to bf16 at the end.
+ * out may alias residual; x must not alias out.  Built for few rows (a decode batch): every 32 rows
+ * stream the weights once more. */
+bct_status bctm_linear(const void* x, const void* w_packed, const void* residual, void* out, uint32_t rows,
                        uint32_t K, uint32_t N, void* hip_stream);
 
 /* out[r][n] = silu(sum_k x[r][k] w_gate[n][k]) * (sum_k x[r][k] w_up[n][k]),  silu(a) = a / (1 + exp(-a)).
- * Same shape rules as bctm_linear. */
-bct_status bctm_swiglu(const void* x, const void* w_gate, const void* w_up, void* out, uint32_t rows,
+ * Both weights packed; same shape rules as bctm_linear. */
+bct_status bctm_swiglu(const void* x, const void* w_gate_packed, const void* w_up_packed, void* out, uint32_t rows,
                        uint32_t K, uint32_t N, void* hip_stream);
 
 /* ids[r] = index of the largest logits[r][:] (the lowest index among equal maxima). */

@@ -5,12 +5,13 @@
 //
 // The projections multiply a handful of token rows (the decode batch) by a
 // large weight matrix, so they are bound by streaming the weights from HBM
-// once.  A workgroup owns 32 output features and all K inputs: its eight
-// wavefronts split K, each keeps a 32 x 32 fp32 accumulator
-// (v_mfma_f32_32x32x16_bf16, rows = token rows, columns = output features) and
-// reads its operands straight from memory in operand layout (lane l: row or
-// feature l % 32, the 8 consecutive k at 8 * (l / 32)); the eight partial
-// accumulators are summed through LDS in a fixed order.
+// once.  The weights are repacked once, when they are loaded, into 1 KB tiles
+// in MFMA operand order, so that every wavefront load instruction reads one
+// contiguous tile.  A workgroup owns 16 output features and all K inputs: its
+// eight wavefronts split K, each keeps two 16 x 16 fp32 accumulators
+// (v_mfma_f32_16x16x32_bf16; rows = token rows, columns = output features) for
+// 32 token rows and reads the activations straight from memory (they stay in
+// L2); the eight partial accumulators are summed through LDS in a fixed order.
 #include "../../include/bct_model.h"
 
 #include <stdio.h>
@@ -22,73 +23,109 @@ namespace bct {
 namespace {
 
 constexpr int kLinWaves = 8;
+constexpr int kLinUnroll = 8;  // weight tiles a wavefront has in flight
 
 __device__ __forceinline__ float bf16f(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
 __device__ __forceinline__ uint16_t f2bf16(float x) { return __builtin_bit_cast(uint16_t, (__bf16)x); }
 
+// Row-major w [N][K] -> tiles of 16 features x 32 inputs, 1 KB each, tile (n / 16, k / 32) at index
+// (n / 16) * (K / 32) + k / 32.  Inside a tile the 16 bytes of lane l = 16 * ((k % 32) / 8) + n % 16 hold
+// the 8 consecutive inputs k % 8 = 0..7: the B operand of v_mfma_f32_16x16x32_bf16, so that one wavefront
+// load instruction reads one whole tile, contiguously.
+__global__ __launch_bounds__(256) void pack_weight_kernel(const uint16_t* __restrict__ w, u32x4* __restrict__ packed,
+                                                          uint32_t N, uint32_t K) {
+  const size_t c = (size_t)blockIdx.x * 256 + threadIdx.x;  // 16-byte chunk of the packed array
+  if (c >= (size_t)N * K / 8) return;
+  const uint32_t KT = K / 32, l = (uint32_t)(c % 64);
+  const size_t tile = c / 64;
+  const uint32_t nt = (uint32_t)(tile / KT), kt = (uint32_t)(tile % KT);
+  const uint32_t n = nt * 16 + l % 16, k = kt * 32 + (l / 16) * 8;
+  packed[c] = *(const u32x4*)(w + (size_t)n * K + k);
+}
+
 template <bool SWIGLU>
 __global__ __launch_bounds__(64 * kLinWaves) void linear_kernel(const uint16_t* __restrict__ x,
-                                                                const uint16_t* __restrict__ w,
-                                                                const uint16_t* __restrict__ w2,
+                                                                const u32x4* __restrict__ w,
+                                                                const u32x4* __restrict__ w2,
                                                                 const uint16_t* residual, uint16_t* out,
                                                                 uint32_t rows, uint32_t K, uint32_t N) {
-  __shared__ float sC[kLinWaves][32][33];
-  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64, col = lane % 32, half = lane / 32;
-  const uint32_t n0 = blockIdx.x * 32, r0 = blockIdx.y * 32;
-  const uint32_t kper = K / kLinWaves, k0 = wave * kper;  // K is a multiple of 64: kper a multiple of 8
-  const bool row_ok = r0 + col < rows;
-  const uint16_t* xp = x + (size_t)(row_ok ? r0 + col : 0) * K + k0 + half * 8;
-  const uint16_t* wp = w + (size_t)(n0 + col) * K + k0 + half * 8;
-  const uint16_t* wp2 = SWIGLU ? w2 + (size_t)(n0 + col) * K + k0 + half * 8 : nullptr;
-  f32x16 acc, acc2;
+  __shared__ float sC[kLinWaves][32][17];
+  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64, jl = lane % 16, kg = lane / 16;
+  const uint32_t nt = blockIdx.x, r0 = blockIdx.y * 32, KT = K / 32;
+  // this wavefront's share of the K tiles
+  const uint32_t kt0 = (uint32_t)((uint64_t)wave * KT / kLinWaves), kt1 = (uint32_t)((uint64_t)(wave + 1) * KT / kLinWaves);
+  const u32x4* wt = w + ((size_t)nt * KT + kt0) * 64 + lane;
+  const u32x4* wt2 = SWIGLU ? w2 + ((size_t)nt * KT + kt0) * 64 + lane : nullptr;
+  // A operand: lane holds token row jl (+16 for the second row tile), inputs 8 * kg .. + 8 of the K tile.
+  // Rows past the end load a valid row instead; their results are never stored.
+  const uint32_t ra = min(r0 + jl, rows - 1), rb = min(r0 + 16 + jl, rows - 1);
+  const uint16_t* xa = x + (size_t)ra * K + (size_t)kt0 * 32 + kg * 8;
+  const uint16_t* xb = x + (size_t)rb * K + (size_t)kt0 * 32 + kg * 8;
+  f32x4 acc[2][2];
 #pragma unroll
-  for (int v = 0; v < 16; ++v) acc[v] = acc2[v] = 0.f;
-  auto step = [&](uint32_t s, bool in) {
-    u32x4 a = {0u, 0u, 0u, 0u}, b = {0u, 0u, 0u, 0u}, b2 = {0u, 0u, 0u, 0u};
-    if (in) {
-      b = __builtin_nontemporal_load((const u32x4*)(wp + s * 16));
-      if (SWIGLU) b2 = __builtin_nontemporal_load((const u32x4*)(wp2 + s * 16));
-      if (row_ok) a = *(const u32x4*)(xp + s * 16);
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const uint32_t n_t = kt1 - kt0;
+  uint32_t t = 0;
+  for (; t + kLinUnroll <= n_t; t += kLinUnroll) {
+    u32x4 b[kLinUnroll], b2[kLinUnroll], a0[kLinUnroll], a1[kLinUnroll];
+#pragma unroll
+    for (int u = 0; u < kLinUnroll; ++u) {
+      b[u] = __builtin_nontemporal_load(wt + (size_t)(t + u) * 64);
+      if (SWIGLU) b2[u] = __builtin_nontemporal_load(wt2 + (size_t)(t + u) * 64);
     }
-    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc,
-                                                  0, 0, 0);
-    if (SWIGLU)
-      acc2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b2),
-                                                     acc2, 0, 0, 0);
-  };
-  // kper / 16 whole steps of 16 k; kper is a multiple of 8, so a remainder of 8
-  // is one more step in which only the lower half-wavefront has data
-  const uint32_t full = kper / 16;
-#pragma unroll 8
-  for (uint32_t s = 0; s < full; ++s) step(s, true);
-  if (kper % 16) step(full, half == 0);
-  // accumulator: lane column = feature n0 + col, rows = token rows 8*(v/4) + 4*half + v%4.
-  // Each thread then owns two of the 32 x 32 outputs and adds the eight partials in wave order;
-  // the SwiGLU variant sends its second accumulator through the same buffer afterwards.
-  float sum[2][2];
+#pragma unroll
+    for (int u = 0; u < kLinUnroll; ++u) {
+      a0[u] = *(const u32x4*)(xa + (size_t)(t + u) * 32);
+      a1[u] = *(const u32x4*)(xb + (size_t)(t + u) * 32);
+    }
+#pragma unroll
+    for (int u = 0; u < kLinUnroll; ++u) {
+      const bf16x8 va = __builtin_bit_cast(bf16x8, a0[u]), vb = __builtin_bit_cast(bf16x8, a1[u]);
+      acc[0][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, __builtin_bit_cast(bf16x8, b[u]), acc[0][0], 0, 0, 0);
+      acc[0][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vb, __builtin_bit_cast(bf16x8, b[u]), acc[0][1], 0, 0, 0);
+      if (SWIGLU) {
+        acc[1][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, __builtin_bit_cast(bf16x8, b2[u]), acc[1][0], 0, 0, 0);
+        acc[1][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vb, __builtin_bit_cast(bf16x8, b2[u]), acc[1][1], 0, 0, 0);
+      }
+    }
+  }
+  for (; t < n_t; ++t) {
+    const u32x4 b = __builtin_nontemporal_load(wt + (size_t)t * 64);
+    const bf16x8 va = __builtin_bit_cast(bf16x8, *(const u32x4*)(xa + (size_t)t * 32));
+    const bf16x8 vb = __builtin_bit_cast(bf16x8, *(const u32x4*)(xb + (size_t)t * 32));
+    acc[0][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, __builtin_bit_cast(bf16x8, b), acc[0][0], 0, 0, 0);
+    acc[0][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vb, __builtin_bit_cast(bf16x8, b), acc[0][1], 0, 0, 0);
+    if (SWIGLU) {
+      const u32x4 b2 = __builtin_nontemporal_load(wt2 + (size_t)t * 64);
+      acc[1][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, __builtin_bit_cast(bf16x8, b2), acc[1][0], 0, 0, 0);
+      acc[1][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vb, __builtin_bit_cast(bf16x8, b2), acc[1][1], 0, 0, 0);
+    }
+  }
+  // accumulator element v of a lane: token row 4 * kg + v of the row tile, feature jl.
+  // Each thread then owns one of the 32 x 16 outputs and adds the eight partials in wave order;
+  // the SwiGLU variant sends its second accumulator pair through the same buffer afterwards.
+  const uint32_t oi = threadIdx.x / 16, oj = threadIdx.x % 16;
+  float sum[2];
 #pragma unroll
   for (int pass = 0; pass < (SWIGLU ? 2 : 1); ++pass) {
     if (pass) __syncthreads();
 #pragma unroll
-    for (int v = 0; v < 16; ++v) sC[wave][8 * (v / 4) + 4 * half + (v % 4)][col] = pass ? acc2[v] : acc[v];
+    for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) sC[wave][16 * rt + 4 * kg + v][jl] = acc[pass][rt][v];
     __syncthreads();
+    float a = 0.f;
 #pragma unroll
-    for (int e = 0; e < 2; ++e) {
-      const uint32_t t = threadIdx.x + e * 64 * kLinWaves, i = t / 32, j = t % 32;
-      float a = 0.f;
-#pragma unroll
-      for (int k = 0; k < kLinWaves; ++k) a += sC[k][i][j];
-      sum[pass][e] = a;
-    }
+    for (int k = 0; k < kLinWaves; ++k) a += sC[k][oi][oj];
+    sum[pass] = a;
   }
-#pragma unroll
-  for (int e = 0; e < 2; ++e) {
-    const uint32_t t = threadIdx.x + e * 64 * kLinWaves, i = t / 32, j = t % 32;
-    if (r0 + i >= rows) continue;
-    const size_t o = (size_t)(r0 + i) * N + n0 + j;
-    const float g = sum[0][e];
+  if (r0 + oi < rows) {
+    const size_t o = (size_t)(r0 + oi) * N + nt * 16 + oj;
+    const float g = sum[0];
     float y;
-    if (SWIGLU) y = g / (1.0f + __expf(-g)) * sum[1][e];
+    if (SWIGLU) y = g / (1.0f + __expf(-g)) * sum[1];
     else y = residual ? g + bf16f(residual[o]) : g;
     out[o] = f2bf16(y);
   }
@@ -177,7 +214,7 @@ bool al16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
 bct_status check_linear(const void* x, const void* w, const void* out, uint32_t rows, uint32_t K, uint32_t N) {
   if (!x || !w || !out || rows == 0 || K == 0 || N == 0) return mfail(BCT_ERR_INVALID_ARG, "NULL pointer or zero size");
-  if (K % 64 != 0 || N % 32 != 0) return mfail(BCT_ERR_UNSUPPORTED, "K must be a multiple of 64 and N of 32");
+  if (K % 32 != 0 || N % 16 != 0) return mfail(BCT_ERR_UNSUPPORTED, "K must be a multiple of 32 and N of 16");
   if (!al16(x) || !al16(w) || !al16(out)) return mfail(BCT_ERR_MISALIGNED, "pointers must be 16-byte aligned");
   return BCT_OK;
 }
@@ -211,13 +248,25 @@ bct_status bctm_rmsnorm(const void* x, const void* gain, void* out, uint32_t row
   return launched("rmsnorm");
 }
 
+bct_status bctm_pack_weight(const void* w, void* packed, uint32_t N, uint32_t K, void* hip_stream) {
+  if (!w || !packed || N == 0 || K == 0) return mfail(BCT_ERR_INVALID_ARG, "NULL pointer or zero size");
+  if (w == packed) return mfail(BCT_ERR_INVALID_ARG, "packing in place is not possible");
+  if (K % 32 != 0 || N % 16 != 0) return mfail(BCT_ERR_UNSUPPORTED, "K must be a multiple of 32 and N of 16");
+  if (!al16(w) || !al16(packed)) return mfail(BCT_ERR_MISALIGNED, "pointers must be 16-byte aligned");
+  const size_t chunks = (size_t)N * K / 8;
+  if ((chunks + 255) / 256 > 0x7FFFFFFFu) return mfail(BCT_ERR_UNSUPPORTED, "matrix too large");
+  hipLaunchKernelGGL(pack_weight_kernel, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, (hipStream_t)hip_stream,
+                     (const uint16_t*)w, (u32x4*)packed, N, K);
+  return launched("pack_weight");
+}
+
 bct_status bctm_linear(const void* x, const void* w, const void* residual, void* out, uint32_t rows, uint32_t K,
                        uint32_t N, void* hip_stream) {
   const bct_status st = check_linear(x, w, out, rows, K, N);
   if (st != BCT_OK) return st;
   if (!al16(residual)) return mfail(BCT_ERR_MISALIGNED, "pointers must be 16-byte aligned");
-  hipLaunchKernelGGL((linear_kernel<false>), dim3(N / 32, (rows + 31) / 32), dim3(64 * kLinWaves), 0,
-                     (hipStream_t)hip_stream, (const uint16_t*)x, (const uint16_t*)w, (const uint16_t*)nullptr,
+  hipLaunchKernelGGL((linear_kernel<false>), dim3(N / 16, (rows + 31) / 32), dim3(64 * kLinWaves), 0,
+                     (hipStream_t)hip_stream, (const uint16_t*)x, (const u32x4*)w, (const u32x4*)nullptr,
                      (const uint16_t*)residual, (uint16_t*)out, rows, K, N);
   return launched("linear");
 }
@@ -228,8 +277,8 @@ bct_status bctm_swiglu(const void* x, const void* w_gate, const void* w_up, void
   if (st != BCT_OK) return st;
   if (!w_up) return mfail(BCT_ERR_INVALID_ARG, "NULL pointer or zero size");
   if (!al16(w_up)) return mfail(BCT_ERR_MISALIGNED, "pointers must be 16-byte aligned");
-  hipLaunchKernelGGL((linear_kernel<true>), dim3(N / 32, (rows + 31) / 32), dim3(64 * kLinWaves), 0,
-                     (hipStream_t)hip_stream, (const uint16_t*)x, (const uint16_t*)w_gate, (const uint16_t*)w_up,
+  hipLaunchKernelGGL((linear_kernel<true>), dim3(N / 16, (rows + 31) / 32), dim3(64 * kLinWaves), 0,
+                     (hipStream_t)hip_stream, (const uint16_t*)x, (const u32x4*)w_gate, (const u32x4*)w_up,
                      (const uint16_t*)nullptr, (uint16_t*)out, rows, K, N);
   return launched("swiglu");
 }

@@ -14,7 +14,8 @@ from dataclasses import dataclass
 from . import binding
 from .binding import BCT_OK, BctCache, BctError, _dptr, _stream_ptr, _torch
 
-MODEL_EXPORTS = ["bctm_embed", "bctm_rmsnorm", "bctm_linear", "bctm_swiglu", "bctm_argmax", "bctm_last_error"]
+MODEL_EXPORTS = ["bctm_embed", "bctm_rmsnorm", "bctm_pack_weight", "bctm_linear", "bctm_swiglu", "bctm_argmax",
+                 "bctm_last_error"]
 
 _ready = False
 
@@ -28,6 +29,7 @@ def mlib() -> ctypes.CDLL:
     vp, u32 = ctypes.c_void_p, ctypes.c_uint32
     L.bctm_embed.argtypes = [vp, vp, vp, u32, u32, u32, vp]
     L.bctm_rmsnorm.argtypes = [vp, vp, vp, u32, u32, ctypes.c_float, vp]
+    L.bctm_pack_weight.argtypes = [vp, vp, u32, u32, vp]
     L.bctm_linear.argtypes = [vp, vp, vp, vp, u32, u32, u32, vp]
     L.bctm_swiglu.argtypes = [vp, vp, vp, vp, u32, u32, u32, vp]
     L.bctm_argmax.argtypes = [vp, vp, u32, u32, vp]
@@ -93,11 +95,35 @@ def bctm_rmsnorm(x, gain, eps, out=None):
     return out
 
 
+class PackedWeight:
+    """A weight matrix [N][K] in the tiled layout bctm_linear / bctm_swiglu stream (bctm_pack_weight)."""
+
+    def __init__(self, data, N, K):
+        self.data, self.N, self.K = data, N, K
+
+
+def bctm_pack_weight(w):
+    torch = _torch()
+    _bf16_2d(w, "w")
+    N, K = w.shape
+    data = torch.empty(N * K, dtype=torch.bfloat16, device=w.device)
+    with torch.cuda.device(w.device):
+        _ck(mlib().bctm_pack_weight(_dptr(w), _dptr(data), N, K, _stream_ptr()), "bctm_pack_weight")
+    return PackedWeight(data, N, K)
+
+
+def _packed(w, name, K):
+    if not isinstance(w, PackedWeight):
+        raise ValueError(f"{name}: expected a PackedWeight (bctm_pack_weight)")
+    if w.K != K:
+        raise ValueError(f"{name}: packed for {w.K} inputs, x has {K}")
+
+
 def bctm_linear(x, w, residual=None, out=None):
     torch = _torch()
     _bf16_2d(x, "x")
-    _bf16_2d(w, "w", x.shape[1])
-    rows, N = x.shape[0], w.shape[0]
+    _packed(w, "w", x.shape[1])
+    rows, N = x.shape[0], w.N
     if out is None:
         out = torch.empty((rows, N), dtype=torch.bfloat16, device=x.device)
     _bf16_2d(out, "out", N)
@@ -105,8 +131,10 @@ def bctm_linear(x, w, residual=None, out=None):
         _bf16_2d(residual, "residual", N)
     if out.shape[0] != rows or (residual is not None and residual.shape[0] != rows):
         raise ValueError("out / residual: one row per row of x")
+    if out.data_ptr() == x.data_ptr():
+        raise ValueError("out must not be x")
     with torch.cuda.device(x.device):
-        _ck(mlib().bctm_linear(_dptr(x), _dptr(w), _dptr(residual), _dptr(out), rows, x.shape[1], N,
+        _ck(mlib().bctm_linear(_dptr(x), _dptr(w.data), _dptr(residual), _dptr(out), rows, x.shape[1], N,
                                _stream_ptr()), "bctm_linear")
     return out
 
@@ -114,18 +142,18 @@ def bctm_linear(x, w, residual=None, out=None):
 def bctm_swiglu(x, w_gate, w_up, out=None):
     torch = _torch()
     _bf16_2d(x, "x")
-    _bf16_2d(w_gate, "w_gate", x.shape[1])
-    _bf16_2d(w_up, "w_up", x.shape[1])
-    if w_gate.shape != w_up.shape:
+    _packed(w_gate, "w_gate", x.shape[1])
+    _packed(w_up, "w_up", x.shape[1])
+    if w_gate.N != w_up.N:
         raise ValueError("w_gate and w_up: same shape")
-    rows, N = x.shape[0], w_gate.shape[0]
+    rows, N = x.shape[0], w_gate.N
     if out is None:
         out = torch.empty((rows, N), dtype=torch.bfloat16, device=x.device)
     _bf16_2d(out, "out", N)
     if out.shape[0] != rows:
         raise ValueError("out: one row per row of x")
     with torch.cuda.device(x.device):
-        _ck(mlib().bctm_swiglu(_dptr(x), _dptr(w_gate), _dptr(w_up), _dptr(out), rows, x.shape[1], N,
+        _ck(mlib().bctm_swiglu(_dptr(x), _dptr(w_gate.data), _dptr(w_up.data), _dptr(out), rows, x.shape[1], N,
                                _stream_ptr()), "bctm_swiglu")
     return out
 
@@ -190,7 +218,7 @@ class BctStack:
 
     def __init__(self, shape: StackShape, weights, max_prefill_T=0, device="cuda:0"):
         torch = _torch()
-        self.shape, self.w = shape, weights
+        self.shape = shape
         self.device = torch.device(device)
         s = shape
         self.caches = []
@@ -202,10 +230,17 @@ class BctStack:
             c.set_keys(weights["keys"][l])
             c.set_values(None)
             self.caches.append(c)
+        # matrices are repacked once into the streaming layout; the row-major copies are not kept
+        self.layers = []
         for l, lw in enumerate(weights["layers"]):
+            pl = {}
             for n, shp in s.weight_shapes().items():
                 if tuple(lw[n].shape) != shp or lw[n].dtype != torch.bfloat16:
                     raise ValueError(f"layer {l} {n}: expected bf16 {shp}")
+                pl[n] = bctm_pack_weight(lw[n]) if len(shp) == 2 else lw[n]
+            self.layers.append(pl)
+        self.embed, self.final_norm = weights["embed"], weights["final_norm"]
+        self.head = bctm_pack_weight(weights["head"])
         self._bufs = {}
 
     def _buf(self, name, rows, cols):
@@ -222,11 +257,11 @@ class BctStack:
         rows = s.batch * T
         if ids.numel() != rows:
             raise ValueError(f"ids: expected {rows} entries")
-        x = bctm_embed(ids, self.w["embed"], self._buf("x", rows, s.dim))
+        x = bctm_embed(ids, self.embed, self._buf("x", rows, s.dim))
         h = self._buf("h", rows, s.dim)
         q, wq, wv = self._buf("q", rows, s.q_width), self._buf("wq", rows, s.kv_width), self._buf("wv", rows, s.kv_width)
         a, f = self._buf("a", rows, s.q_width), self._buf("f", rows, s.ffn)
-        for l, lw in enumerate(self.w["layers"]):
+        for l, lw in enumerate(self.layers):
             bctm_rmsnorm(x, lw["attn_norm"], s.eps, h)
             bctm_linear(h, lw["w_q"], None, q)
             bctm_linear(h, lw["w_wq"], None, wq)
@@ -244,7 +279,7 @@ class BctStack:
             bctm_rmsnorm(x, lw["mlp_norm"], s.eps, h)
             bctm_swiglu(h, lw["w_gate"], lw["w_up"], f)
             bctm_linear(f, lw["w_down"], x, x)
-        bctm_rmsnorm(x, self.w["final_norm"], s.eps, h)
-        logits = bctm_linear(h, self.w["head"], None, self._buf("logits", rows, s.vocab))
+        bctm_rmsnorm(x, self.final_norm, s.eps, h)
+        logits = bctm_linear(h, self.head, None, self._buf("logits", rows, s.vocab))
         nxt = bctm_argmax(logits, None)
         return nxt, logits

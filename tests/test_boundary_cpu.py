@@ -37,7 +37,7 @@ def test_every_declared_symbol_is_exported_and_bound(L):
 def test_every_declared_model_symbol_is_exported_and_bound(L):
     from paper_2411_15785_amd import model
     names = declared_functions("bct_model.h", "bctm_")
-    assert {"bctm_linear", "bctm_swiglu", "bctm_rmsnorm", "bctm_embed", "bctm_argmax"} <= set(names)
+    assert {"bctm_linear", "bctm_swiglu", "bctm_rmsnorm", "bctm_embed", "bctm_argmax", "bctm_pack_weight"} <= set(names)
     ML = model.mlib()
     for n in names:
         assert hasattr(ML, n), f"{n} is declared in include/bct_model.h but not exported by libbct.so"
@@ -49,8 +49,11 @@ def test_model_entry_points_check_arguments_before_touching_the_gpu(L):
     ML = model.mlib()
     p = ctypes.c_void_p
     a, b, c = p(0x10000), p(0x20000), p(0x30000)
-    assert ML.bctm_linear(a, b, None, c, 4, 72, 32, None) == P.BCT_ERR_UNSUPPORTED       # K % 64
-    assert ML.bctm_linear(a, b, None, c, 4, 64, 40, None) == P.BCT_ERR_UNSUPPORTED       # N % 32
+    assert ML.bctm_linear(a, b, None, c, 4, 72, 32, None) == P.BCT_ERR_UNSUPPORTED       # K % 32
+    assert ML.bctm_linear(a, b, None, c, 4, 64, 40, None) == P.BCT_ERR_UNSUPPORTED       # N % 16
+    assert ML.bctm_pack_weight(a, b, 40, 64, None) == P.BCT_ERR_UNSUPPORTED
+    assert ML.bctm_pack_weight(a, a, 32, 64, None) == P.BCT_ERR_INVALID_ARG              # in place
+    assert ML.bctm_pack_weight(a, None, 32, 64, None) == P.BCT_ERR_INVALID_ARG
     assert ML.bctm_linear(a, None, None, c, 4, 64, 32, None) == P.BCT_ERR_INVALID_ARG
     assert ML.bctm_linear(a, b, None, c, 0, 64, 32, None) == P.BCT_ERR_INVALID_ARG
     assert ML.bctm_linear(p(0x10008), b, None, c, 4, 64, 32, None) == P.BCT_ERR_MISALIGNED

@@ -4,8 +4,8 @@ from them, against oracle/model_ref, element by element on the same seeded input
 Tolerances.  The kernels accumulate in fp32 and round once to bf16; the oracle computes in
 fp64 and rounds once.  The two bf16 results therefore differ by at most one bf16 spacing
 where the exact value lies near a rounding boundary, plus the fp32 accumulation error,
-bounded here by 2^-20 * sum_k |x_k w_k| (K * 2^-24 with K <= 16 times headroom for the
-split-K order).  Arg-max and embedding are integer / byte work: bit-exact.
+bounded here by 2^-20 * sum_k |x_k w_k| (a pairwise-like split-K sum of fp32 products is
+far inside it).  Arg-max and embedding are integer / byte work: bit-exact.
 """
 import numpy as np
 import pytest
@@ -45,7 +45,8 @@ def check_close(got_bits, ref_bits, slack, what):
 
 
 LIN_SHAPES = [  # rows, K, N
-    (1, 64, 32), (5, 64, 96), (32, 192, 64), (33, 320, 32), (70, 1024, 160), (32, 4096, 256), (3, 11008, 64),
+    (1, 32, 16), (5, 64, 96), (32, 192, 48), (33, 320, 32), (70, 1024, 160), (32, 4096, 256), (3, 11008, 64),
+    (17, 2336, 16),    # 73 K tiles: uneven shares for the eight wavefronts, unrolled part plus remainder
 ]
 
 
@@ -54,7 +55,7 @@ LIN_SHAPES = [  # rows, K, N
 def test_linear(M, rows, K, N, with_res):
     x, w = draw(1, (rows, K)), draw(2, (N, K), K ** -0.5)
     res = draw(3, (rows, N)) if with_res else None
-    out = M.bctm_linear(dev(x), dev(w), dev(res) if with_res else None)
+    out = M.bctm_linear(dev(x), M.bctm_pack_weight(dev(w)), dev(res) if with_res else None)
     mass = np.abs(R.bf16_to_f64(x)) @ np.abs(R.bf16_to_f64(w)).T
     check_close(host(out), R.linear(x, w, res), 2.0 ** -20 * mass, f"linear {rows}x{K}x{N}")
 
@@ -63,10 +64,23 @@ def test_linear_in_place_residual(M):
     rows, K, N = 7, 256, 128
     x, w, res = draw(1, (rows, K)), draw(2, (N, K), K ** -0.5), draw(3, (rows, N))
     buf = dev(res)
-    out = M.bctm_linear(dev(x), dev(w), buf, buf)
+    out = M.bctm_linear(dev(x), M.bctm_pack_weight(dev(w)), buf, buf)
     assert out.data_ptr() == buf.data_ptr()
     mass = np.abs(R.bf16_to_f64(x)) @ np.abs(R.bf16_to_f64(w)).T
     check_close(host(buf), R.linear(x, w, res), 2.0 ** -20 * mass, "linear in place")
+
+
+def test_pack_weight_layout(M):
+    # the documented layout, element by element: tile (n/16, k/32), lane 16*((k%32)/8) + n%16, 8 inputs per lane
+    N, K = 48, 96
+    w = np.arange(N * K, dtype=np.uint16).reshape(N, K)          # every element distinct
+    got = M.bctm_pack_weight(dev(w)).data
+    got = host(got.view(1, -1))[0]
+    n, k = np.meshgrid(np.arange(N), np.arange(K), indexing="ij")
+    off = ((n // 16) * (K // 32) + k // 32) * 512 + 8 * (16 * ((k % 32) // 8) + n % 16) + k % 8
+    want = np.empty(N * K, dtype=np.uint16)
+    want[off.ravel()] = w.ravel()
+    assert np.array_equal(got, want)
 
 
 def test_linear_selects_the_right_operands(M):
@@ -77,14 +91,14 @@ def test_linear_selects_the_right_operands(M):
     w = np.zeros((N, K), dtype=np.float32)
     w[np.arange(N), sel] = 1.0
     wb = (w.view(np.uint32) >> 16).astype(np.uint16)
-    out = host(M.bctm_linear(dev(x), dev(wb)))
+    out = host(M.bctm_linear(dev(x), M.bctm_pack_weight(dev(wb))))
     assert np.array_equal(out, x[:, sel])
 
 
-@pytest.mark.parametrize("rows,K,N", [(1, 64, 32), (6, 192, 96), (32, 4096, 352), (40, 512, 64)])
+@pytest.mark.parametrize("rows,K,N", [(1, 32, 16), (6, 192, 96), (32, 4096, 352), (40, 544, 64)])
 def test_swiglu(M, rows, K, N):
     x, wg, wu = draw(5, (rows, K)), draw(6, (N, K), 2.0 * K ** -0.5), draw(7, (N, K), K ** -0.5)
-    out = M.bctm_swiglu(dev(x), dev(wg), dev(wu))
+    out = M.bctm_swiglu(dev(x), M.bctm_pack_weight(dev(wg)), M.bctm_pack_weight(dev(wu)))
     xa = np.abs(R.bf16_to_f64(x))
     g, u = R.linear_f64(x, wg), R.linear_f64(x, wu)
     mg, mu = xa @ np.abs(R.bf16_to_f64(wg)).T, xa @ np.abs(R.bf16_to_f64(wu)).T
@@ -119,17 +133,18 @@ def test_embed_and_argmax_are_exact(M):
 
 def test_argument_errors(M):
     import torch
-    x = torch.zeros((4, 72), dtype=torch.bfloat16, device="cuda")
     w = torch.zeros((32, 72), dtype=torch.bfloat16, device="cuda")
     with pytest.raises(M.BctModelError) as e:
-        M.bctm_linear(x, w)                      # K not a multiple of 64
+        M.bctm_pack_weight(w)                    # K not a multiple of 32
     assert e.value.status == 2
-    x = torch.zeros((4, 64), dtype=torch.bfloat16, device="cuda")
     w = torch.zeros((40, 64), dtype=torch.bfloat16, device="cuda")
     with pytest.raises(M.BctModelError):
-        M.bctm_linear(x, w)                      # N not a multiple of 32
+        M.bctm_pack_weight(w)                    # N not a multiple of 16
+    x = torch.zeros((4, 64), dtype=torch.bfloat16, device="cuda")
     with pytest.raises(ValueError):
-        M.bctm_linear(x, w.float())
+        M.bctm_linear(x, w)                      # a row-major tensor where a packed weight is expected
+    with pytest.raises(ValueError):
+        M.bctm_linear(x, M.bctm_pack_weight(torch.zeros((32, 96), dtype=torch.bfloat16, device="cuda")))
 
 
 # ---------------------------------------------------------------- the stack
