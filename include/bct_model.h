@@ -30,10 +30,22 @@ extern "C" {
 bct_status bctm_embed(const int32_t* ids, const void* table, void* out, uint32_t rows, uint32_t vocab,
                       uint32_t dim, void* hip_stream);
 
+/* Tiled activations.  A [rows][K] activation matrix that feeds a projection can be kept in the order the
+ * projection's MFMA reads it, so that every wavefront load is one contiguous kilobyte: rows in groups of
+ * 32, columns in groups of 32; group (r / 32, k / 32) is the 2 KB block number (r / 32) * (K / 32) + k / 32,
+ * made of two 1 KB halves (rows 0-15, rows 16-31 of the group); in a half, element (r, k) sits at bf16
+ * offset 8 * (16 * ((k % 32) / 8) + r % 16) + k % 8.  K must be a multiple of 32 and the buffer holds
+ * 32 * ceil(rows / 32) * K bf16; rows past the end are never read for a stored result. */
+#define BCTM_X_TILED 1u   /* the input x is tiled */
+#define BCTM_OUT_TILED 2u /* the output is written tiled */
+
+/* Row-major x [rows][K] -> tiled (above).  tiled must not be x. */
+bct_status bctm_pack_rows(const void* x, void* tiled, uint32_t rows, uint32_t K, void* hip_stream);
+
 /* out[r][:] = x[r][:] * rsqrt(mean(x[r][:]^2) + eps) * gain[:]   (fp32 arithmetic, bf16 in/out).
- * dim a multiple of 8, at most 16384. */
+ * dim a multiple of 8, at most 16384.  flags: BCTM_OUT_TILED (then dim a multiple of 32, out not x). */
 bct_status bctm_rmsnorm(const void* x, const void* gain, void* out, uint32_t rows, uint32_t dim, float eps,
-                        void* hip_stream);
+                        uint32_t flags, void* hip_stream);
 
 /* Repacks a row-major weight matrix w [N][K] (one output feature per row) into the streaming layout
  * bctm_linear and bctm_swiglu read: 1 KB tiles of 16 features x 32 inputs, tile (n / 16, k / 32) at tile
@@ -43,17 +55,19 @@ bct_status bctm_rmsnorm(const void* x, const void* gain, void* out, uint32_t row
 bct_status bctm_pack_weight(const void* w, void* packed, uint32_t N, uint32_t K, void* hip_stream);
 
 /* out[r][n] = (residual ? residual[r][n] : 0) + sum_k x[r][k] * w[n][k].
- * x [rows][K] row-major; w_packed = bctm_pack_weight of w [N][K]; out/residual [rows][N] row-major;
+ * x [rows][K] row-major, or tiled with flags = BCTM_X_TILED; w_packed = bctm_pack_weight of w [N][K];
+ * out/residual [rows][N] row-major;
  * K a multiple of 32, N a multiple of 16; fp32 accumulation (MFMA), one rounding to bf16 at the end.
  * out may alias residual; x must not alias out.  Built for few rows (a decode batch): every 32 rows
  * stream the weights once more. */
 bct_status bctm_linear(const void* x, const void* w_packed, const void* residual, void* out, uint32_t rows,
-                       uint32_t K, uint32_t N, void* hip_stream);
+                       uint32_t K, uint32_t N, uint32_t flags, void* hip_stream);
 
 /* out[r][n] = silu(sum_k x[r][k] w_gate[n][k]) * (sum_k x[r][k] w_up[n][k]),  silu(a) = a / (1 + exp(-a)).
- * Both weights packed; same shape rules as bctm_linear. */
+ * Both weights packed; same shape rules as bctm_linear.  flags: BCTM_X_TILED, BCTM_OUT_TILED (the output
+ * as tiled activations of N columns, N a multiple of 32, ready to feed the next projection). */
 bct_status bctm_swiglu(const void* x, const void* w_gate_packed, const void* w_up_packed, void* out, uint32_t rows,
-                       uint32_t K, uint32_t N, void* hip_stream);
+                       uint32_t K, uint32_t N, uint32_t flags, void* hip_stream);
 
 /* ids[r] = index of the largest logits[r][:] (the lowest index among equal maxima). */
 bct_status bctm_argmax(const void* logits, int32_t* ids, uint32_t rows, uint32_t N, void* hip_stream);

@@ -43,12 +43,28 @@ __global__ __launch_bounds__(256) void pack_weight_kernel(const uint16_t* __rest
   packed[c] = *(const u32x4*)(w + (size_t)n * K + k);
 }
 
-template <bool SWIGLU>
+// Tiled activations: rows in groups of 32, inputs in groups of 32; group (r / 32, k / 32) is 2 KB, two A
+// operands of v_mfma_f32_16x16x32_bf16 (rows 0-15 and 16-31 of the group), each 64 lanes x 16 bytes with
+// lane 16 * ((k % 32) / 8) + r % 16 holding the inputs k % 8 = 0..7.  Returns the 16-byte chunk index.
+__device__ __forceinline__ size_t tiled_chunk(uint32_t r, uint32_t k, uint32_t K) {
+  return ((((size_t)(r / 32) * (K / 32) + k / 32) * 2 + (r % 32) / 16) * 64) + 16 * ((k % 32) / 8) + r % 16;
+}
+
+__global__ __launch_bounds__(256) void pack_rows_kernel(const uint16_t* __restrict__ x, u32x4* __restrict__ packed,
+                                                        uint32_t rows, uint32_t K) {
+  const size_t c = (size_t)blockIdx.x * 256 + threadIdx.x;  // 16-byte chunk of the row-major array
+  if (c >= (size_t)rows * K / 8) return;
+  const uint32_t r = (uint32_t)(c / (K / 8)), k = (uint32_t)(c % (K / 8)) * 8;
+  packed[tiled_chunk(r, k, K)] = *(const u32x4*)(x + (size_t)r * K + k);
+}
+
+template <bool SWIGLU, bool XT>
 __global__ __launch_bounds__(64 * kLinWaves) void linear_kernel(const uint16_t* __restrict__ x,
                                                                 const u32x4* __restrict__ w,
                                                                 const u32x4* __restrict__ w2,
                                                                 const uint16_t* residual, uint16_t* out,
-                                                                uint32_t rows, uint32_t K, uint32_t N) {
+                                                                uint32_t rows, uint32_t K, uint32_t N,
+                                                                uint32_t out_tiled) {
   __shared__ float sC[kLinWaves][32][17];
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64, jl = lane % 16, kg = lane / 16;
   const uint32_t nt = blockIdx.x, r0 = blockIdx.y * 32, KT = K / 32;
@@ -59,8 +75,13 @@ __global__ __launch_bounds__(64 * kLinWaves) void linear_kernel(const uint16_t* 
   // A operand: lane holds token row jl (+16 for the second row tile), inputs 8 * kg .. + 8 of the K tile.
   // Rows past the end load a valid row instead; their results are never stored.
   const uint32_t ra = min(r0 + jl, rows - 1), rb = min(r0 + 16 + jl, rows - 1);
-  const uint16_t* xa = x + (size_t)ra * K + (size_t)kt0 * 32 + kg * 8;
-  const uint16_t* xb = x + (size_t)rb * K + (size_t)kt0 * 32 + kg * 8;
+  // Tiled activations: the two operands of K tile kt are the consecutive 1 KB tiles 2 * kt, 2 * kt + 1
+  // of this row group (rows past the end are allocated, their content is never stored).
+  // xstep: distance in bf16 elements between a lane's chunks of consecutive K tiles.
+  const uint16_t* xa = XT ? x + (((size_t)blockIdx.y * KT + kt0) * 128 + lane) * 8
+                          : x + (size_t)ra * K + (size_t)kt0 * 32 + kg * 8;
+  const uint16_t* xb = XT ? xa + 64 * 8 : x + (size_t)rb * K + (size_t)kt0 * 32 + kg * 8;
+  constexpr size_t xstep = XT ? 128 * 8 : 32;
   f32x4 acc[2][2];
 #pragma unroll
   for (int i = 0; i < 2; ++i)
@@ -77,8 +98,8 @@ __global__ __launch_bounds__(64 * kLinWaves) void linear_kernel(const uint16_t* 
     }
 #pragma unroll
     for (int u = 0; u < kLinUnroll; ++u) {
-      a0[u] = *(const u32x4*)(xa + (size_t)(t + u) * 32);
-      a1[u] = *(const u32x4*)(xb + (size_t)(t + u) * 32);
+      a0[u] = *(const u32x4*)(xa + (size_t)(t + u) * xstep);
+      a1[u] = *(const u32x4*)(xb + (size_t)(t + u) * xstep);
     }
 #pragma unroll
     for (int u = 0; u < kLinUnroll; ++u) {
@@ -93,8 +114,8 @@ __global__ __launch_bounds__(64 * kLinWaves) void linear_kernel(const uint16_t* 
   }
   for (; t < n_t; ++t) {
     const u32x4 b = __builtin_nontemporal_load(wt + (size_t)t * 64);
-    const bf16x8 va = __builtin_bit_cast(bf16x8, *(const u32x4*)(xa + (size_t)t * 32));
-    const bf16x8 vb = __builtin_bit_cast(bf16x8, *(const u32x4*)(xb + (size_t)t * 32));
+    const bf16x8 va = __builtin_bit_cast(bf16x8, *(const u32x4*)(xa + (size_t)t * xstep));
+    const bf16x8 vb = __builtin_bit_cast(bf16x8, *(const u32x4*)(xb + (size_t)t * xstep));
     acc[0][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, __builtin_bit_cast(bf16x8, b), acc[0][0], 0, 0, 0);
     acc[0][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vb, __builtin_bit_cast(bf16x8, b), acc[0][1], 0, 0, 0);
     if (SWIGLU) {
@@ -122,17 +143,19 @@ __global__ __launch_bounds__(64 * kLinWaves) void linear_kernel(const uint16_t* 
     sum[pass] = a;
   }
   if (r0 + oi < rows) {
-    const size_t o = (size_t)(r0 + oi) * N + nt * 16 + oj;
+    const uint32_t n = nt * 16 + oj;
+    const size_t o = (size_t)(r0 + oi) * N + n;
     const float g = sum[0];
     float y;
     if (SWIGLU) y = g / (1.0f + __expf(-g)) * sum[1];
     else y = residual ? g + bf16f(residual[o]) : g;
-    out[o] = f2bf16(y);
+    // the output has N columns: as tiled activations it is the input of a projection with K = N
+    out[out_tiled ? tiled_chunk(r0 + oi, n, N) * 8 + n % 8 : o] = f2bf16(y);
   }
 }
 
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const uint16_t* x, const uint16_t* gain, uint16_t* out,
-                                                      uint32_t rows, uint32_t dim, float eps) {
+                                                      uint32_t rows, uint32_t dim, float eps, uint32_t out_tiled) {
   const uint32_t row = blockIdx.x * 4 + threadIdx.x / 64, lane = threadIdx.x % 64;
   if (row >= rows) return;
   const uint16_t* xr = x + (size_t)row * dim;
@@ -151,7 +174,9 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const uint16_t* x, const u
     unpack16<BF16>(*(const u32x4*)(gain + c), g);
 #pragma unroll
     for (int e = 0; e < 8; ++e) f[e] = f[e] * r * g[e];
-    *(u32x4*)(out + (size_t)row * dim + c) = pack16_round<BF16>(f);
+    const u32x4 v = pack16_round<BF16>(f);
+    if (out_tiled) ((u32x4*)out)[tiled_chunk(row, c, dim)] = v;
+    else *(u32x4*)(out + (size_t)row * dim + c) = v;
   }
 }
 
@@ -239,13 +264,29 @@ bct_status bctm_embed(const int32_t* ids, const void* table, void* out, uint32_t
 }
 
 bct_status bctm_rmsnorm(const void* x, const void* gain, void* out, uint32_t rows, uint32_t dim, float eps,
-                        void* hip_stream) {
+                        uint32_t flags, void* hip_stream) {
   if (!x || !gain || !out || rows == 0 || dim == 0) return mfail(BCT_ERR_INVALID_ARG, "NULL pointer or zero size");
+  if (flags & ~BCTM_OUT_TILED) return mfail(BCT_ERR_INVALID_ARG, "rmsnorm takes only BCTM_OUT_TILED");
   if (dim % 8 != 0 || dim > 16384) return mfail(BCT_ERR_UNSUPPORTED, "dim must be a multiple of 8, at most 16384");
+  if ((flags & BCTM_OUT_TILED) && dim % 32 != 0)
+    return mfail(BCT_ERR_UNSUPPORTED, "tiled activations need a multiple of 32 columns");
+  if ((flags & BCTM_OUT_TILED) && x == out) return mfail(BCT_ERR_INVALID_ARG, "a tiled output cannot overwrite x");
   if (!al16(x) || !al16(gain) || !al16(out)) return mfail(BCT_ERR_MISALIGNED, "pointers must be 16-byte aligned");
   hipLaunchKernelGGL(rmsnorm_kernel, dim3((rows + 3) / 4), dim3(256), 0, (hipStream_t)hip_stream, (const uint16_t*)x,
-                     (const uint16_t*)gain, (uint16_t*)out, rows, dim, eps);
+                     (const uint16_t*)gain, (uint16_t*)out, rows, dim, eps, flags & BCTM_OUT_TILED);
   return launched("rmsnorm");
+}
+
+bct_status bctm_pack_rows(const void* x, void* tiled, uint32_t rows, uint32_t K, void* hip_stream) {
+  if (!x || !tiled || rows == 0 || K == 0) return mfail(BCT_ERR_INVALID_ARG, "NULL pointer or zero size");
+  if (x == tiled) return mfail(BCT_ERR_INVALID_ARG, "packing in place is not possible");
+  if (K % 32 != 0) return mfail(BCT_ERR_UNSUPPORTED, "tiled activations need a multiple of 32 columns");
+  if (!al16(x) || !al16(tiled)) return mfail(BCT_ERR_MISALIGNED, "pointers must be 16-byte aligned");
+  const size_t chunks = (size_t)rows * K / 8;
+  if ((chunks + 255) / 256 > 0x7FFFFFFFu) return mfail(BCT_ERR_UNSUPPORTED, "matrix too large");
+  hipLaunchKernelGGL(pack_rows_kernel, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, (hipStream_t)hip_stream,
+                     (const uint16_t*)x, (u32x4*)tiled, rows, K);
+  return launched("pack_rows");
 }
 
 bct_status bctm_pack_weight(const void* w, void* packed, uint32_t N, uint32_t K, void* hip_stream) {
@@ -261,25 +302,40 @@ bct_status bctm_pack_weight(const void* w, void* packed, uint32_t N, uint32_t K,
 }
 
 bct_status bctm_linear(const void* x, const void* w, const void* residual, void* out, uint32_t rows, uint32_t K,
-                       uint32_t N, void* hip_stream) {
+                       uint32_t N, uint32_t flags, void* hip_stream) {
   const bct_status st = check_linear(x, w, out, rows, K, N);
   if (st != BCT_OK) return st;
+  if (flags & ~BCTM_X_TILED) return mfail(BCT_ERR_INVALID_ARG, "linear takes only BCTM_X_TILED");
+  if (x == out) return mfail(BCT_ERR_INVALID_ARG, "out must not be x");
   if (!al16(residual)) return mfail(BCT_ERR_MISALIGNED, "pointers must be 16-byte aligned");
-  hipLaunchKernelGGL((linear_kernel<false>), dim3(N / 16, (rows + 31) / 32), dim3(64 * kLinWaves), 0,
-                     (hipStream_t)hip_stream, (const uint16_t*)x, (const u32x4*)w, (const u32x4*)nullptr,
-                     (const uint16_t*)residual, (uint16_t*)out, rows, K, N);
+  const dim3 grid(N / 16, (rows + 31) / 32), block(64 * kLinWaves);
+  if (flags & BCTM_X_TILED)
+    hipLaunchKernelGGL((linear_kernel<false, true>), grid, block, 0, (hipStream_t)hip_stream, (const uint16_t*)x,
+                       (const u32x4*)w, (const u32x4*)nullptr, (const uint16_t*)residual, (uint16_t*)out, rows, K, N, 0u);
+  else
+    hipLaunchKernelGGL((linear_kernel<false, false>), grid, block, 0, (hipStream_t)hip_stream, (const uint16_t*)x,
+                       (const u32x4*)w, (const u32x4*)nullptr, (const uint16_t*)residual, (uint16_t*)out, rows, K, N, 0u);
   return launched("linear");
 }
 
 bct_status bctm_swiglu(const void* x, const void* w_gate, const void* w_up, void* out, uint32_t rows, uint32_t K,
-                       uint32_t N, void* hip_stream) {
+                       uint32_t N, uint32_t flags, void* hip_stream) {
   const bct_status st = check_linear(x, w_gate, out, rows, K, N);
   if (st != BCT_OK) return st;
+  if (flags & ~(BCTM_X_TILED | BCTM_OUT_TILED)) return mfail(BCT_ERR_INVALID_ARG, "unknown flag");
   if (!w_up) return mfail(BCT_ERR_INVALID_ARG, "NULL pointer or zero size");
+  if (x == out) return mfail(BCT_ERR_INVALID_ARG, "out must not be x");
+  if ((flags & BCTM_OUT_TILED) && N % 32 != 0)
+    return mfail(BCT_ERR_UNSUPPORTED, "tiled activations need a multiple of 32 columns");
   if (!al16(w_up)) return mfail(BCT_ERR_MISALIGNED, "pointers must be 16-byte aligned");
-  hipLaunchKernelGGL((linear_kernel<true>), dim3(N / 16, (rows + 31) / 32), dim3(64 * kLinWaves), 0,
-                     (hipStream_t)hip_stream, (const uint16_t*)x, (const u32x4*)w_gate, (const u32x4*)w_up,
-                     (const uint16_t*)nullptr, (uint16_t*)out, rows, K, N);
+  const dim3 grid(N / 16, (rows + 31) / 32), block(64 * kLinWaves);
+  const uint32_t ot = flags & BCTM_OUT_TILED ? 1u : 0u;
+  if (flags & BCTM_X_TILED)
+    hipLaunchKernelGGL((linear_kernel<true, true>), grid, block, 0, (hipStream_t)hip_stream, (const uint16_t*)x,
+                       (const u32x4*)w_gate, (const u32x4*)w_up, (const uint16_t*)nullptr, (uint16_t*)out, rows, K, N, ot);
+  else
+    hipLaunchKernelGGL((linear_kernel<true, false>), grid, block, 0, (hipStream_t)hip_stream, (const uint16_t*)x,
+                       (const u32x4*)w_gate, (const u32x4*)w_up, (const uint16_t*)nullptr, (uint16_t*)out, rows, K, N, ot);
   return launched("swiglu");
 }
 

@@ -14,8 +14,11 @@ from dataclasses import dataclass
 from . import binding
 from .binding import BCT_OK, BctCache, BctError, _dptr, _stream_ptr, _torch
 
-MODEL_EXPORTS = ["bctm_embed", "bctm_rmsnorm", "bctm_pack_weight", "bctm_linear", "bctm_swiglu", "bctm_argmax",
-                 "bctm_last_error"]
+MODEL_EXPORTS = ["bctm_embed", "bctm_rmsnorm", "bctm_pack_weight", "bctm_pack_rows", "bctm_linear", "bctm_swiglu",
+                 "bctm_argmax", "bctm_last_error"]
+
+BCTM_X_TILED = 1
+BCTM_OUT_TILED = 2
 
 _ready = False
 
@@ -28,10 +31,11 @@ def mlib() -> ctypes.CDLL:
         return L
     vp, u32 = ctypes.c_void_p, ctypes.c_uint32
     L.bctm_embed.argtypes = [vp, vp, vp, u32, u32, u32, vp]
-    L.bctm_rmsnorm.argtypes = [vp, vp, vp, u32, u32, ctypes.c_float, vp]
+    L.bctm_rmsnorm.argtypes = [vp, vp, vp, u32, u32, ctypes.c_float, u32, vp]
     L.bctm_pack_weight.argtypes = [vp, vp, u32, u32, vp]
-    L.bctm_linear.argtypes = [vp, vp, vp, vp, u32, u32, u32, vp]
-    L.bctm_swiglu.argtypes = [vp, vp, vp, vp, u32, u32, u32, vp]
+    L.bctm_pack_rows.argtypes = [vp, vp, u32, u32, vp]
+    L.bctm_linear.argtypes = [vp, vp, vp, vp, u32, u32, u32, u32, vp]
+    L.bctm_swiglu.argtypes = [vp, vp, vp, vp, u32, u32, u32, u32, vp]
     L.bctm_argmax.argtypes = [vp, vp, u32, u32, vp]
     for n in MODEL_EXPORTS[:-1]:
         getattr(L, n).restype = ctypes.c_int
@@ -78,20 +82,57 @@ def bctm_embed(ids, table, out=None):
     return out
 
 
-def bctm_rmsnorm(x, gain, eps, out=None):
+class TiledRows:
+    """A [rows][K] activation matrix in the tiled order the projections read (include/bct_model.h):
+    data holds 32 * ceil(rows / 32) * K bf16."""
+
+    def __init__(self, rows, K, device, data=None):
+        torch = _torch()
+        n = 32 * ((rows + 31) // 32) * K
+        if data is None:
+            # zeros, not empty: rows past the end are read (never stored) and should be finite
+            data = torch.zeros(n, dtype=torch.bfloat16, device=device)
+        if data.dtype != torch.bfloat16 or data.numel() != n or not data.is_contiguous():
+            raise ValueError(f"tiled data: expected {n} contiguous bf16")
+        self.data, self.rows, self.K = data, rows, K
+
+
+def bctm_pack_rows(x, out=None):
+    torch = _torch()
+    _bf16_2d(x, "x")
+    rows, K = x.shape
+    if out is None:
+        out = TiledRows(rows, K, x.device)
+    if (out.rows, out.K) != (rows, K):
+        raise ValueError("out: tiled buffer of x's shape")
+    with torch.cuda.device(x.device):
+        _ck(mlib().bctm_pack_rows(_dptr(x), _dptr(out.data), rows, K, _stream_ptr()), "bctm_pack_rows")
+    return out
+
+
+def bctm_rmsnorm(x, gain, eps, out=None, tiled=False):
+    """out: a tensor of x's shape, or (tiled=True) a TiledRows."""
     torch = _torch()
     _bf16_2d(x, "x")
     if gain.dtype != torch.bfloat16 or tuple(gain.shape) != (x.shape[1],) or not gain.is_contiguous() \
             or gain.device != x.device:
         raise ValueError("gain: expected a contiguous bf16 vector of x's row length on x's device")
-    if out is None:
-        out = torch.empty_like(x)
-    _bf16_2d(out, "out", x.shape[1])
-    if out.shape[0] != x.shape[0]:
-        raise ValueError("out: x's shape")
+    if tiled:
+        if out is None:
+            out = TiledRows(x.shape[0], x.shape[1], x.device)
+        if not isinstance(out, TiledRows) or (out.rows, out.K) != tuple(x.shape):
+            raise ValueError("out: a TiledRows of x's shape")
+        dst = out.data
+    else:
+        if out is None:
+            out = torch.empty_like(x)
+        _bf16_2d(out, "out", x.shape[1])
+        if out.shape[0] != x.shape[0]:
+            raise ValueError("out: x's shape")
+        dst = out
     with torch.cuda.device(x.device):
-        _ck(mlib().bctm_rmsnorm(_dptr(x), _dptr(gain), _dptr(out), x.shape[0], x.shape[1], eps, _stream_ptr()),
-            "bctm_rmsnorm")
+        _ck(mlib().bctm_rmsnorm(_dptr(x), _dptr(gain), _dptr(dst), x.shape[0], x.shape[1], eps,
+                                BCTM_OUT_TILED if tiled else 0, _stream_ptr()), "bctm_rmsnorm")
     return out
 
 
@@ -119,42 +160,58 @@ def _packed(w, name, K):
         raise ValueError(f"{name}: packed for {w.K} inputs, x has {K}")
 
 
-def bctm_linear(x, w, residual=None, out=None):
-    torch = _torch()
+def _x_arg(x):
+    """-> (data tensor, rows, K, flag) of a row-major tensor or a TiledRows."""
+    if isinstance(x, TiledRows):
+        return x.data, x.rows, x.K, BCTM_X_TILED
     _bf16_2d(x, "x")
-    _packed(w, "w", x.shape[1])
-    rows, N = x.shape[0], w.N
+    return x, x.shape[0], x.shape[1], 0
+
+
+def bctm_linear(x, w, residual=None, out=None):
+    """x: a [rows][K] tensor or a TiledRows; out / residual row-major [rows][N]."""
+    torch = _torch()
+    xd, rows, K, xf = _x_arg(x)
+    _packed(w, "w", K)
+    N = w.N
     if out is None:
-        out = torch.empty((rows, N), dtype=torch.bfloat16, device=x.device)
+        out = torch.empty((rows, N), dtype=torch.bfloat16, device=xd.device)
     _bf16_2d(out, "out", N)
     if residual is not None:
         _bf16_2d(residual, "residual", N)
     if out.shape[0] != rows or (residual is not None and residual.shape[0] != rows):
         raise ValueError("out / residual: one row per row of x")
-    if out.data_ptr() == x.data_ptr():
-        raise ValueError("out must not be x")
-    with torch.cuda.device(x.device):
-        _ck(mlib().bctm_linear(_dptr(x), _dptr(w.data), _dptr(residual), _dptr(out), rows, x.shape[1], N,
+    with torch.cuda.device(xd.device):
+        _ck(mlib().bctm_linear(_dptr(xd), _dptr(w.data), _dptr(residual), _dptr(out), rows, K, N, xf,
                                _stream_ptr()), "bctm_linear")
     return out
 
 
-def bctm_swiglu(x, w_gate, w_up, out=None):
+def bctm_swiglu(x, w_gate, w_up, out=None, tiled=False):
+    """x: a [rows][K] tensor or a TiledRows; out: a [rows][N] tensor, or (tiled=True) a TiledRows."""
     torch = _torch()
-    _bf16_2d(x, "x")
-    _packed(w_gate, "w_gate", x.shape[1])
-    _packed(w_up, "w_up", x.shape[1])
+    xd, rows, K, xf = _x_arg(x)
+    _packed(w_gate, "w_gate", K)
+    _packed(w_up, "w_up", K)
     if w_gate.N != w_up.N:
         raise ValueError("w_gate and w_up: same shape")
-    rows, N = x.shape[0], w_gate.N
-    if out is None:
-        out = torch.empty((rows, N), dtype=torch.bfloat16, device=x.device)
-    _bf16_2d(out, "out", N)
-    if out.shape[0] != rows:
-        raise ValueError("out: one row per row of x")
-    with torch.cuda.device(x.device):
-        _ck(mlib().bctm_swiglu(_dptr(x), _dptr(w_gate.data), _dptr(w_up.data), _dptr(out), rows, x.shape[1], N,
-                               _stream_ptr()), "bctm_swiglu")
+    N = w_gate.N
+    if tiled:
+        if out is None:
+            out = TiledRows(rows, N, xd.device)
+        if not isinstance(out, TiledRows) or (out.rows, out.K) != (rows, N):
+            raise ValueError("out: a TiledRows [rows][N]")
+        dst = out.data
+    else:
+        if out is None:
+            out = torch.empty((rows, N), dtype=torch.bfloat16, device=xd.device)
+        _bf16_2d(out, "out", N)
+        if out.shape[0] != rows:
+            raise ValueError("out: one row per row of x")
+        dst = out
+    with torch.cuda.device(xd.device):
+        _ck(mlib().bctm_swiglu(_dptr(xd), _dptr(w_gate.data), _dptr(w_up.data), _dptr(dst), rows, K, N,
+                               xf | (BCTM_OUT_TILED if tiled else 0), _stream_ptr()), "bctm_swiglu")
     return out
 
 
@@ -187,6 +244,12 @@ class StackShape:
     capacity_M: int
     batch: int
     eps: float = 1e-5
+
+    def __post_init__(self):
+        if self.dim % 32 or (self.n_q_heads * self.head_dim) % 32 or self.ffn % 32 or self.vocab % 16 or \
+                (self.n_kv_heads * self.head_dim) % 16:
+            raise ValueError("dim, n_q_heads * head_dim and ffn must be multiples of 32; vocab and "
+                             "n_kv_heads * head_dim multiples of 16")
 
     @property
     def q_width(self):
@@ -250,6 +313,12 @@ class BctStack:
             self._bufs[k] = torch.empty((rows, cols), dtype=torch.bfloat16, device=self.device)
         return self._bufs[k]
 
+    def _tiled(self, name, rows, cols):
+        k = ("tiled", name, rows, cols)
+        if k not in self._bufs:
+            self._bufs[k] = TiledRows(rows, cols, self.device)
+        return self._bufs[k]
+
     def forward(self, ids, T=1):
         """ids int32 [B*T] (sequence-major: row b*T + t) -> (next ids int32 [B*T], logits [B*T][vocab]).
         T = 1 is a decode step; T > 1 pushes a chunk of T tokens per sequence through bct_prefill."""
@@ -258,11 +327,12 @@ class BctStack:
         if ids.numel() != rows:
             raise ValueError(f"ids: expected {rows} entries")
         x = bctm_embed(ids, self.embed, self._buf("x", rows, s.dim))
-        h = self._buf("h", rows, s.dim)
+        # every input of a projection is kept tiled, so that the projections read it in whole kilobytes
+        h, at, f = self._tiled("h", rows, s.dim), self._tiled("a", rows, s.q_width), self._tiled("f", rows, s.ffn)
         q, wq, wv = self._buf("q", rows, s.q_width), self._buf("wq", rows, s.kv_width), self._buf("wv", rows, s.kv_width)
-        a, f = self._buf("a", rows, s.q_width), self._buf("f", rows, s.ffn)
+        a = self._buf("a", rows, s.q_width)
         for l, lw in enumerate(self.layers):
-            bctm_rmsnorm(x, lw["attn_norm"], s.eps, h)
+            bctm_rmsnorm(x, lw["attn_norm"], s.eps, h, tiled=True)
             bctm_linear(h, lw["w_q"], None, q)
             bctm_linear(h, lw["w_wq"], None, wq)
             bctm_linear(h, lw["w_wv"], None, wv)
@@ -275,11 +345,11 @@ class BctStack:
                 c.prefill(q.view(s.batch, T, s.n_q_heads, s.head_dim), wq.view(s.batch, T, s.n_kv_heads, s.head_dim),
                           wv.view(s.batch, T, s.n_kv_heads, s.head_dim), T,
                           a.view(s.batch, T, s.n_q_heads, s.head_dim))
-            bctm_linear(a, lw["w_o"], x, x)
-            bctm_rmsnorm(x, lw["mlp_norm"], s.eps, h)
-            bctm_swiglu(h, lw["w_gate"], lw["w_up"], f)
+            bctm_linear(bctm_pack_rows(a, at), lw["w_o"], x, x)
+            bctm_rmsnorm(x, lw["mlp_norm"], s.eps, h, tiled=True)
+            bctm_swiglu(h, lw["w_gate"], lw["w_up"], f, tiled=True)
             bctm_linear(f, lw["w_down"], x, x)
-        bctm_rmsnorm(x, self.final_norm, s.eps, h)
+        bctm_rmsnorm(x, self.final_norm, s.eps, h, tiled=True)
         logits = bctm_linear(h, self.head, None, self._buf("logits", rows, s.vocab))
         nxt = bctm_argmax(logits, None)
         return nxt, logits

@@ -37,7 +37,7 @@ def test_every_declared_symbol_is_exported_and_bound(L):
 def test_every_declared_model_symbol_is_exported_and_bound(L):
     from paper_2411_15785_amd import model
     names = declared_functions("bct_model.h", "bctm_")
-    assert {"bctm_linear", "bctm_swiglu", "bctm_rmsnorm", "bctm_embed", "bctm_argmax", "bctm_pack_weight"} <= set(names)
+    assert {"bctm_linear", "bctm_swiglu", "bctm_rmsnorm", "bctm_embed", "bctm_argmax", "bctm_pack_weight", "bctm_pack_rows"} <= set(names)
     ML = model.mlib()
     for n in names:
         assert hasattr(ML, n), f"{n} is declared in include/bct_model.h but not exported by libbct.so"
@@ -49,18 +49,27 @@ def test_model_entry_points_check_arguments_before_touching_the_gpu(L):
     ML = model.mlib()
     p = ctypes.c_void_p
     a, b, c = p(0x10000), p(0x20000), p(0x30000)
-    assert ML.bctm_linear(a, b, None, c, 4, 72, 32, None) == P.BCT_ERR_UNSUPPORTED       # K % 32
-    assert ML.bctm_linear(a, b, None, c, 4, 64, 40, None) == P.BCT_ERR_UNSUPPORTED       # N % 16
+    assert ML.bctm_linear(a, b, None, c, 4, 72, 32, 0, None) == P.BCT_ERR_UNSUPPORTED       # K % 32
+    assert ML.bctm_linear(a, b, None, c, 4, 64, 40, 0, None) == P.BCT_ERR_UNSUPPORTED       # N % 16
     assert ML.bctm_pack_weight(a, b, 40, 64, None) == P.BCT_ERR_UNSUPPORTED
     assert ML.bctm_pack_weight(a, a, 32, 64, None) == P.BCT_ERR_INVALID_ARG              # in place
     assert ML.bctm_pack_weight(a, None, 32, 64, None) == P.BCT_ERR_INVALID_ARG
-    assert ML.bctm_linear(a, None, None, c, 4, 64, 32, None) == P.BCT_ERR_INVALID_ARG
-    assert ML.bctm_linear(a, b, None, c, 0, 64, 32, None) == P.BCT_ERR_INVALID_ARG
-    assert ML.bctm_linear(p(0x10008), b, None, c, 4, 64, 32, None) == P.BCT_ERR_MISALIGNED
-    assert ML.bctm_linear(a, b, p(0x40004), c, 4, 64, 32, None) == P.BCT_ERR_MISALIGNED
-    assert ML.bctm_swiglu(a, b, None, c, 4, 64, 32, None) == P.BCT_ERR_INVALID_ARG
-    assert ML.bctm_rmsnorm(a, b, c, 4, 12, 1e-5, None) == P.BCT_ERR_UNSUPPORTED          # dim % 8
-    assert ML.bctm_rmsnorm(a, b, c, 4, 32768, 1e-5, None) == P.BCT_ERR_UNSUPPORTED
+    assert ML.bctm_linear(a, None, None, c, 4, 64, 32, 0, None) == P.BCT_ERR_INVALID_ARG
+    assert ML.bctm_linear(a, b, None, c, 0, 64, 32, 0, None) == P.BCT_ERR_INVALID_ARG
+    assert ML.bctm_linear(p(0x10008), b, None, c, 4, 64, 32, 0, None) == P.BCT_ERR_MISALIGNED
+    assert ML.bctm_linear(a, b, p(0x40004), c, 4, 64, 32, 0, None) == P.BCT_ERR_MISALIGNED
+    assert ML.bctm_swiglu(a, b, None, c, 4, 64, 32, 0, None) == P.BCT_ERR_INVALID_ARG
+    assert ML.bctm_rmsnorm(a, b, c, 4, 12, 1e-5, 0, None) == P.BCT_ERR_UNSUPPORTED          # dim % 8
+    assert ML.bctm_rmsnorm(a, b, c, 4, 32768, 1e-5, 0, None) == P.BCT_ERR_UNSUPPORTED
+    assert ML.bctm_rmsnorm(a, b, c, 4, 40, 1e-5, 2, None) == P.BCT_ERR_UNSUPPORTED           # tiled: dim % 32
+    assert ML.bctm_rmsnorm(a, b, a, 4, 64, 1e-5, 2, None) == P.BCT_ERR_INVALID_ARG           # tiled in place
+    assert ML.bctm_rmsnorm(a, b, c, 4, 64, 1e-5, 1, None) == P.BCT_ERR_INVALID_ARG           # not its flag
+    assert ML.bctm_linear(a, b, None, c, 4, 64, 32, 2, None) == P.BCT_ERR_INVALID_ARG        # no tiled output
+    assert ML.bctm_linear(a, b, None, a, 4, 64, 32, 0, None) == P.BCT_ERR_INVALID_ARG        # out is x
+    assert ML.bctm_swiglu(a, b, b, c, 4, 64, 48, 2, None) == P.BCT_ERR_UNSUPPORTED           # tiled out: N % 32
+    assert ML.bctm_swiglu(a, b, b, c, 4, 64, 32, 8, None) == P.BCT_ERR_INVALID_ARG
+    assert ML.bctm_pack_rows(a, b, 4, 40, None) == P.BCT_ERR_UNSUPPORTED
+    assert ML.bctm_pack_rows(a, a, 4, 64, None) == P.BCT_ERR_INVALID_ARG
     assert ML.bctm_embed(None, b, c, 4, 10, 64, None) == P.BCT_ERR_INVALID_ARG
     assert ML.bctm_embed(a, b, c, 4, 10, 12, None) == P.BCT_ERR_UNSUPPORTED
     assert ML.bctm_argmax(a, None, 4, 10, None) == P.BCT_ERR_INVALID_ARG

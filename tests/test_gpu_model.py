@@ -60,6 +60,50 @@ def test_linear(M, rows, K, N, with_res):
     check_close(host(out), R.linear(x, w, res), 2.0 ** -20 * mass, f"linear {rows}x{K}x{N}")
 
 
+def tiled_offsets(rows, K):
+    """bf16 offset of element (r, k) in the tiled activation layout, written out from its definition."""
+    r, k = np.meshgrid(np.arange(rows), np.arange(K), indexing="ij")
+    block = (r // 32) * (K // 32) + k // 32
+    return block * 1024 + ((r % 32) // 16) * 512 + 8 * (16 * ((k % 32) // 8) + r % 16) + k % 8
+
+
+def untile(t, rows, K):
+    return host(t.data.view(1, -1))[0][tiled_offsets(rows, K)]
+
+
+@pytest.mark.parametrize("rows,K", [(1, 32), (16, 64), (33, 96), (70, 4096)])
+def test_pack_rows_layout(M, rows, K):
+    x = draw(13, (rows, K))
+    t = M.bctm_pack_rows(dev(x))
+    assert t.data.numel() == 32 * ((rows + 31) // 32) * K
+    assert np.array_equal(untile(t, rows, K), x)
+
+
+@pytest.mark.parametrize("rows,K,N", [(1, 32, 16), (32, 4096, 256), (45, 320, 64), (3, 11008, 64), (17, 2336, 16)])
+def test_linear_tiled_input_is_bitwise_the_row_major_result(M, rows, K, N):
+    x, w, res = draw(1, (rows, K)), M.bctm_pack_weight(dev(draw(2, (N, K), K ** -0.5))), dev(draw(3, (rows, N)))
+    a = M.bctm_linear(dev(x), w, res)
+    b = M.bctm_linear(M.bctm_pack_rows(dev(x)), w, res)
+    assert np.array_equal(host(a), host(b))
+
+
+@pytest.mark.parametrize("rows,K,N", [(5, 64, 32), (32, 4096, 352), (40, 544, 64)])
+def test_swiglu_tiled_in_and_out(M, rows, K, N):
+    x = draw(5, (rows, K))
+    wg, wu = M.bctm_pack_weight(dev(draw(6, (N, K), 2.0 * K ** -0.5))), M.bctm_pack_weight(dev(draw(7, (N, K), K ** -0.5)))
+    plain = host(M.bctm_swiglu(dev(x), wg, wu))
+    t = M.bctm_swiglu(M.bctm_pack_rows(dev(x)), wg, wu, tiled=True)
+    assert np.array_equal(untile(t, rows, N), plain)
+
+
+@pytest.mark.parametrize("rows,dim", [(3, 64), (32, 4096), (37, 512)])
+def test_rmsnorm_tiled_out(M, rows, dim):
+    x, g = draw(8, (rows, dim), 3.0), syn.pack(1.0 + 0.1 * syn.normal(11, 9, 9, (dim,)), "bf16")
+    plain = host(M.bctm_rmsnorm(dev(x), dev(g), 1e-5))
+    t = M.bctm_rmsnorm(dev(x), dev(g), 1e-5, tiled=True)
+    assert np.array_equal(untile(t, rows, dim), plain)
+
+
 def test_linear_in_place_residual(M):
     rows, K, N = 7, 256, 128
     x, w, res = draw(1, (rows, K)), draw(2, (N, K), K ** -0.5), draw(3, (rows, N))
