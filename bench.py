@@ -63,6 +63,65 @@ def cpu_baseline(w, seconds_budget=20.0):
     }
 
 
+def full_stack(w, L, steps, warmup, attention_ms_per_step):
+    """Greedy decoding through the whole Llama-7B-shaped model: embedding, L x (RMSNorm, W_q / W_wq / W_wv,
+    bounded-cache attention, W_o, RMSNorm, SwiGLU MLP), RMSNorm, output head, arg-max, the next ids fed back.
+    Weights ~ N(0, 0.02) drawn on the device (their values do not change the cost); token ids start random."""
+    import torch
+
+    from paper_2411_15785_amd import model as M
+    dev = "cuda:0"
+    s = M.StackShape(n_layers=L, dim=w.Hq * w.d, n_q_heads=w.Hq, n_kv_heads=w.Hkv, head_dim=w.d, ffn=11008,
+                     vocab=32000, capacity_M=w.M, batch=w.B)
+    g = torch.Generator(device=dev)
+    g.manual_seed(20241115)
+
+    def mat(shape, std=0.02, mean=0.0):
+        return (torch.randn(shape, generator=g, device=dev) * std + mean).to(torch.bfloat16)
+
+    t0 = time.perf_counter()
+    weights = {"embed": mat((s.vocab, s.dim)), "final_norm": mat((s.dim,), 0.0, 1.0), "head": mat((s.vocab, s.dim)),
+               "layers": [{n: (mat(shp) if len(shp) == 2 else mat(shp, 0.0, 1.0)) for n, shp in s.weight_shapes().items()}
+                          for _ in range(L)],
+               "keys": [mat((s.n_kv_heads, s.capacity_M, s.head_dim), 1.0) for _ in range(L)]}
+    stack = M.BctStack(s, weights, device=dev)
+    del weights
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    log(f"full stack: {s.weight_bytes() / 2**30:.1f} GiB of weights packed in {time.perf_counter() - t0:.1f} s")
+    ids = torch.randint(0, s.vocab, (s.batch,), generator=g, device=dev, dtype=torch.int32)
+    for _ in range(warmup):
+        stack.forward(ids, next_ids=ids)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        stack.forward(ids, next_ids=ids)
+    torch.cuda.synchronize()
+    ms_eager = (time.perf_counter() - t0) * 1e3 / steps
+    # the same token-step as one HIP graph: ~550 launches replayed without a host call each
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        stack.forward(ids, next_ids=ids)
+    for _ in range(warmup):
+        graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        graph.replay()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    glue_ms = ms - attention_ms_per_step
+    # what one token-step must stream besides the caches: every matrix once (the embedding: B rows)
+    wbytes = s.weight_bytes() - 2 * s.vocab * s.dim + 2 * s.batch * s.dim
+    return {"tokens_per_s": s.batch / (ms * 1e-3), "ms_per_step": ms, "launch": "one HIP graph per token-step",
+            "ms_per_step_eager": ms_eager,
+            "model": f"Llama-7B shape: {L} layers, d_model {s.dim}, ffn {s.ffn}, vocab {s.vocab}, "
+                     f"bf16 weights N(0, 0.02), greedy decoding from random ids",
+            "glue_ms_per_step": glue_ms, "weight_bytes_per_step": wbytes,
+            "glue_GB/s": wbytes / (glue_ms * 1e-3) / 1e9 if glue_ms > 0 else None,
+            "attention_share": attention_ms_per_step / ms}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -72,6 +131,8 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (0 = the workload's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefill", action="store_true", help="start decoding from MV_0 = 0, without the prompt")
+    ap.add_argument("--no-full-stack", action="store_true",
+                    help="skip the leg that decodes through the whole Llama-shaped model (cfg3 only)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
@@ -202,6 +263,10 @@ def main():
     }
     if prefill:
         rec["prefill"] = prefill
+    if w.name == "cfg3" and not args.no_full_stack:
+        del caches, inputs, outs, workspace
+        torch.cuda.empty_cache()
+        rec["full_stack"] = full_stack(w, L, args.steps, args.warmup, ms_per_step)
     if not args.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(rec), flush=True)

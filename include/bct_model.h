@@ -63,6 +63,13 @@ bct_status bctm_pack_weight(const void* w, void* packed, uint32_t N, uint32_t K,
 bct_status bctm_linear(const void* x, const void* w_packed, const void* residual, void* out, uint32_t rows,
                        uint32_t K, uint32_t N, uint32_t flags, void* hip_stream);
 
+/* One projection with up to three row-major outputs: w_packed holds N0 + N1 + N2 features (packed as one
+ * matrix, or matrix by matrix into consecutive parts of one buffer), the first N0 go to out0 [rows][N0], the
+ * next N1 to out1 [rows][N1], the last N2 to out2 [rows][N2] (N2 may be 0, out2 then unused).  Every width a
+ * multiple of 16.  For W_q, W_wq and W_wv, which read the same input. */
+bct_status bctm_linear_split(const void* x, const void* w_packed, void* out0, uint32_t N0, void* out1, uint32_t N1,
+                             void* out2, uint32_t N2, uint32_t rows, uint32_t K, uint32_t flags, void* hip_stream);
+
 /* out[r][n] = silu(sum_k x[r][k] w_gate[n][k]) * (sum_k x[r][k] w_up[n][k]),  silu(a) = a / (1 + exp(-a)).
  * Both weights packed; same shape rules as bctm_linear.  flags: BCTM_X_TILED, BCTM_OUT_TILED (the output
  * as tiled activations of N columns, N a multiple of 32, ready to feed the next projection). */

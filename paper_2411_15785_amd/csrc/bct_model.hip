@@ -8,10 +8,10 @@
 // once.  The weights are repacked once, when they are loaded, into 1 KB tiles
 // in MFMA operand order, so that every wavefront load instruction reads one
 // contiguous tile.  A workgroup owns 16 output features and all K inputs: its
-// eight wavefronts split K, each keeps two 16 x 16 fp32 accumulators
+// wavefronts split K, each keeps two 16 x 16 fp32 accumulators
 // (v_mfma_f32_16x16x32_bf16; rows = token rows, columns = output features) for
 // 32 token rows and reads the activations straight from memory (they stay in
-// L2); the eight partial accumulators are summed through LDS in a fixed order.
+// L2); the partial accumulators are summed through LDS in a fixed order.
 #include "../../include/bct_model.h"
 
 #include <stdio.h>
@@ -22,8 +22,11 @@ namespace bct {
 
 namespace {
 
-constexpr int kLinWaves = 8;
-constexpr int kLinUnroll = 8;  // weight tiles a wavefront has in flight
+// Workgroup shapes of the projections: wavefronts that split K, and weight tiles a wavefront has in flight.
+// A plain projection uses 16 wavefronts so that K = 4096 is a single round of loads per wavefront; the
+// SwiGLU pair, with two weight streams per wavefront, uses 8 (and so may use 256 registers per lane).
+constexpr int kLinWaves = 16, kLinUnroll = 8;
+constexpr int kGluWaves = 8, kGluUnroll = 8;
 
 __device__ __forceinline__ float bf16f(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
 __device__ __forceinline__ uint16_t f2bf16(float x) { return __builtin_bit_cast(uint16_t, (__bf16)x); }
@@ -58,26 +61,31 @@ __global__ __launch_bounds__(256) void pack_rows_kernel(const uint16_t* __restri
   packed[tiled_chunk(r, k, K)] = *(const u32x4*)(x + (size_t)r * K + k);
 }
 
-template <bool SWIGLU, bool XT>
-__global__ __launch_bounds__(64 * kLinWaves) void linear_kernel(const uint16_t* __restrict__ x,
-                                                                const u32x4* __restrict__ w,
-                                                                const u32x4* __restrict__ w2,
-                                                                const uint16_t* residual, uint16_t* out,
-                                                                uint32_t rows, uint32_t K, uint32_t N,
-                                                                uint32_t out_tiled) {
-  __shared__ float sC[kLinWaves][32][17];
+// Up to three row-major outputs side by side along N: output i takes the features [start[i], start[i + 1]).
+struct LinearOut {
+  uint16_t* ptr[3];
+  uint32_t start[4];
+};
+
+template <bool SWIGLU, bool XT, int WAVES, int U>
+__global__ __launch_bounds__(64 * WAVES) void linear_kernel(const uint16_t* __restrict__ x,
+                                                            const u32x4* __restrict__ w,
+                                                            const u32x4* __restrict__ w2, const uint16_t* residual,
+                                                            LinearOut dst, uint32_t rows, uint32_t K,
+                                                            uint32_t out_tiled) {
+  __shared__ float sC[WAVES][32][17];
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64, jl = lane % 16, kg = lane / 16;
   const uint32_t nt = blockIdx.x, r0 = blockIdx.y * 32, KT = K / 32;
   // this wavefront's share of the K tiles
-  const uint32_t kt0 = (uint32_t)((uint64_t)wave * KT / kLinWaves), kt1 = (uint32_t)((uint64_t)(wave + 1) * KT / kLinWaves);
+  const uint32_t kt0 = (uint32_t)((uint64_t)wave * KT / WAVES), kt1 = (uint32_t)((uint64_t)(wave + 1) * KT / WAVES);
   const u32x4* wt = w + ((size_t)nt * KT + kt0) * 64 + lane;
   const u32x4* wt2 = SWIGLU ? w2 + ((size_t)nt * KT + kt0) * 64 + lane : nullptr;
   // A operand: lane holds token row jl (+16 for the second row tile), inputs 8 * kg .. + 8 of the K tile.
   // Rows past the end load a valid row instead; their results are never stored.
-  const uint32_t ra = min(r0 + jl, rows - 1), rb = min(r0 + 16 + jl, rows - 1);
   // Tiled activations: the two operands of K tile kt are the consecutive 1 KB tiles 2 * kt, 2 * kt + 1
   // of this row group (rows past the end are allocated, their content is never stored).
   // xstep: distance in bf16 elements between a lane's chunks of consecutive K tiles.
+  const uint32_t ra = min(r0 + jl, rows - 1), rb = min(r0 + 16 + jl, rows - 1);
   const uint16_t* xa = XT ? x + (((size_t)blockIdx.y * KT + kt0) * 128 + lane) * 8
                           : x + (size_t)ra * K + (size_t)kt0 * 32 + kg * 8;
   const uint16_t* xb = XT ? xa + 64 * 8 : x + (size_t)rb * K + (size_t)kt0 * 32 + kg * 8;
@@ -88,21 +96,34 @@ __global__ __launch_bounds__(64 * kLinWaves) void linear_kernel(const uint16_t* 
 #pragma unroll
     for (int j = 0; j < 2; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
   const uint32_t n_t = kt1 - kt0;
-  uint32_t t = 0;
-  for (; t + kLinUnroll <= n_t; t += kLinUnroll) {
-    u32x4 b[kLinUnroll], b2[kLinUnroll], a0[kLinUnroll], a1[kLinUnroll];
+  // Rounds of U tiles: all loads of a round are issued before its first MFMA, so a round costs one memory
+  // latency.  The last, partial round loads its missing tiles from the share's last tile (in bounds) and
+  // zeroes their weights, which removes them from the sum.
+  for (uint32_t t = 0; t < n_t; t += U) {
+    const bool whole = t + U <= n_t;
+    u32x4 b[U], b2[U], a0[U], a1[U];
 #pragma unroll
-    for (int u = 0; u < kLinUnroll; ++u) {
-      b[u] = __builtin_nontemporal_load(wt + (size_t)(t + u) * 64);
-      if (SWIGLU) b2[u] = __builtin_nontemporal_load(wt2 + (size_t)(t + u) * 64);
+    for (int u = 0; u < U; ++u) {
+      const size_t i = whole ? t + u : min(t + u, n_t - 1);
+      b[u] = __builtin_nontemporal_load(wt + i * 64);
+      if (SWIGLU) b2[u] = __builtin_nontemporal_load(wt2 + i * 64);
     }
 #pragma unroll
-    for (int u = 0; u < kLinUnroll; ++u) {
-      a0[u] = *(const u32x4*)(xa + (size_t)(t + u) * xstep);
-      a1[u] = *(const u32x4*)(xb + (size_t)(t + u) * xstep);
+    for (int u = 0; u < U; ++u) {
+      const size_t i = whole ? t + u : min(t + u, n_t - 1);
+      a0[u] = *(const u32x4*)(xa + i * xstep);
+      a1[u] = *(const u32x4*)(xb + i * xstep);
+    }
+    if (!whole) {
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (t + u >= n_t) {
+          b[u] = u32x4{0u, 0u, 0u, 0u};
+          if (SWIGLU) b2[u] = u32x4{0u, 0u, 0u, 0u};
+        }
     }
 #pragma unroll
-    for (int u = 0; u < kLinUnroll; ++u) {
+    for (int u = 0; u < U; ++u) {
       const bf16x8 va = __builtin_bit_cast(bf16x8, a0[u]), vb = __builtin_bit_cast(bf16x8, a1[u]);
       acc[0][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, __builtin_bit_cast(bf16x8, b[u]), acc[0][0], 0, 0, 0);
       acc[0][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vb, __builtin_bit_cast(bf16x8, b[u]), acc[0][1], 0, 0, 0);
@@ -112,22 +133,10 @@ __global__ __launch_bounds__(64 * kLinWaves) void linear_kernel(const uint16_t* 
       }
     }
   }
-  for (; t < n_t; ++t) {
-    const u32x4 b = __builtin_nontemporal_load(wt + (size_t)t * 64);
-    const bf16x8 va = __builtin_bit_cast(bf16x8, *(const u32x4*)(xa + (size_t)t * xstep));
-    const bf16x8 vb = __builtin_bit_cast(bf16x8, *(const u32x4*)(xb + (size_t)t * xstep));
-    acc[0][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, __builtin_bit_cast(bf16x8, b), acc[0][0], 0, 0, 0);
-    acc[0][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vb, __builtin_bit_cast(bf16x8, b), acc[0][1], 0, 0, 0);
-    if (SWIGLU) {
-      const u32x4 b2 = __builtin_nontemporal_load(wt2 + (size_t)t * 64);
-      acc[1][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, __builtin_bit_cast(bf16x8, b2), acc[1][0], 0, 0, 0);
-      acc[1][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vb, __builtin_bit_cast(bf16x8, b2), acc[1][1], 0, 0, 0);
-    }
-  }
   // accumulator element v of a lane: token row 4 * kg + v of the row tile, feature jl.
-  // Each thread then owns one of the 32 x 16 outputs and adds the eight partials in wave order;
+  // The first 512 threads then own one of the 32 x 16 outputs each and add the partials in wave order;
   // the SwiGLU variant sends its second accumulator pair through the same buffer afterwards.
-  const uint32_t oi = threadIdx.x / 16, oj = threadIdx.x % 16;
+  const uint32_t oi = (threadIdx.x / 16) % 32, oj = threadIdx.x % 16;
   float sum[2];
 #pragma unroll
   for (int pass = 0; pass < (SWIGLU ? 2 : 1); ++pass) {
@@ -139,44 +148,61 @@ __global__ __launch_bounds__(64 * kLinWaves) void linear_kernel(const uint16_t* 
     __syncthreads();
     float a = 0.f;
 #pragma unroll
-    for (int k = 0; k < kLinWaves; ++k) a += sC[k][oi][oj];
+    for (int k = 0; k < WAVES; ++k) a += sC[k][oi][oj];
     sum[pass] = a;
   }
-  if (r0 + oi < rows) {
+  if (threadIdx.x < 512 && r0 + oi < rows) {
     const uint32_t n = nt * 16 + oj;
-    const size_t o = (size_t)(r0 + oi) * N + n;
+    const int which = n >= dst.start[2] ? 2 : n >= dst.start[1] ? 1 : 0;
+    const uint32_t width = dst.start[which + 1] - dst.start[which], col = n - dst.start[which];
+    const size_t o = (size_t)(r0 + oi) * width + col;
     const float g = sum[0];
     float y;
     if (SWIGLU) y = g / (1.0f + __expf(-g)) * sum[1];
     else y = residual ? g + bf16f(residual[o]) : g;
-    // the output has N columns: as tiled activations it is the input of a projection with K = N
-    out[out_tiled ? tiled_chunk(r0 + oi, n, N) * 8 + n % 8 : o] = f2bf16(y);
+    // a tiled output is the input of a projection whose K is this output's width
+    dst.ptr[which][out_tiled ? tiled_chunk(r0 + oi, col, width) * 8 + col % 8 : o] = f2bf16(y);
   }
 }
 
+// One workgroup per row; a thread keeps its (up to eight) 16-byte chunks of the row in registers between
+// the sum of squares and the scaling, so the row is read once.
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const uint16_t* x, const uint16_t* gain, uint16_t* out,
                                                       uint32_t rows, uint32_t dim, float eps, uint32_t out_tiled) {
-  const uint32_t row = blockIdx.x * 4 + threadIdx.x / 64, lane = threadIdx.x % 64;
-  if (row >= rows) return;
+  __shared__ float s_part[4];
+  const uint32_t row = blockIdx.x;
   const uint16_t* xr = x + (size_t)row * dim;
+  u32x4 v[8];
   float ss = 0.f;
-  for (uint32_t c = lane * 8; c < dim; c += 512) {
-    float f[8];
-    unpack16<BF16>(*(const u32x4*)(xr + c), f);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) ss = __builtin_fmaf(f[e], f[e], ss);
+  for (int i = 0; i < 8; ++i) {
+    const uint32_t c = (threadIdx.x + i * 256) * 8;
+    if (c < dim) {
+      v[i] = *(const u32x4*)(xr + c);
+      float f[8];
+      unpack16<BF16>(v[i], f);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) ss = __builtin_fmaf(f[e], f[e], ss);
+    }
   }
   ss = xor_sum<1, 32>(ss);
+  if (threadIdx.x % 64 == 0) s_part[threadIdx.x / 64] = ss;
+  __syncthreads();
+  ss = (s_part[0] + s_part[1]) + (s_part[2] + s_part[3]);
   const float r = 1.0f / sqrtf(ss / (float)dim + eps);
-  for (uint32_t c = lane * 8; c < dim; c += 512) {
-    float f[8], g[8];
-    unpack16<BF16>(*(const u32x4*)(xr + c), f);
-    unpack16<BF16>(*(const u32x4*)(gain + c), g);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) f[e] = f[e] * r * g[e];
-    const u32x4 v = pack16_round<BF16>(f);
-    if (out_tiled) ((u32x4*)out)[tiled_chunk(row, c, dim)] = v;
-    else *(u32x4*)(out + (size_t)row * dim + c) = v;
+  for (int i = 0; i < 8; ++i) {
+    const uint32_t c = (threadIdx.x + i * 256) * 8;
+    if (c < dim) {
+      float f[8], g[8];
+      unpack16<BF16>(v[i], f);
+      unpack16<BF16>(*(const u32x4*)(gain + c), g);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) f[e] = f[e] * r * g[e];
+      const u32x4 o = pack16_round<BF16>(f);
+      if (out_tiled) ((u32x4*)out)[tiled_chunk(row, c, dim)] = o;
+      else *(u32x4*)(out + (size_t)row * dim + c) = o;
+    }
   }
 }
 
@@ -272,7 +298,7 @@ bct_status bctm_rmsnorm(const void* x, const void* gain, void* out, uint32_t row
     return mfail(BCT_ERR_UNSUPPORTED, "tiled activations need a multiple of 32 columns");
   if ((flags & BCTM_OUT_TILED) && x == out) return mfail(BCT_ERR_INVALID_ARG, "a tiled output cannot overwrite x");
   if (!al16(x) || !al16(gain) || !al16(out)) return mfail(BCT_ERR_MISALIGNED, "pointers must be 16-byte aligned");
-  hipLaunchKernelGGL(rmsnorm_kernel, dim3((rows + 3) / 4), dim3(256), 0, (hipStream_t)hip_stream, (const uint16_t*)x,
+  hipLaunchKernelGGL(rmsnorm_kernel, dim3(rows), dim3(256), 0, (hipStream_t)hip_stream, (const uint16_t*)x,
                      (const uint16_t*)gain, (uint16_t*)out, rows, dim, eps, flags & BCTM_OUT_TILED);
   return launched("rmsnorm");
 }
@@ -301,6 +327,20 @@ bct_status bctm_pack_weight(const void* w, void* packed, uint32_t N, uint32_t K,
   return launched("pack_weight");
 }
 
+static bct_status launch_linear(const void* x, const void* w, const void* residual, const LinearOut& dst,
+                                uint32_t rows, uint32_t K, uint32_t N, uint32_t flags, void* hip_stream) {
+  const dim3 grid(N / 16, (rows + 31) / 32), block(64 * kLinWaves);
+  if (flags & BCTM_X_TILED)
+    hipLaunchKernelGGL((linear_kernel<false, true, kLinWaves, kLinUnroll>), grid, block, 0, (hipStream_t)hip_stream,
+                       (const uint16_t*)x, (const u32x4*)w, (const u32x4*)nullptr, (const uint16_t*)residual, dst, rows,
+                       K, 0u);
+  else
+    hipLaunchKernelGGL((linear_kernel<false, false, kLinWaves, kLinUnroll>), grid, block, 0, (hipStream_t)hip_stream,
+                       (const uint16_t*)x, (const u32x4*)w, (const u32x4*)nullptr, (const uint16_t*)residual, dst, rows,
+                       K, 0u);
+  return launched("linear");
+}
+
 bct_status bctm_linear(const void* x, const void* w, const void* residual, void* out, uint32_t rows, uint32_t K,
                        uint32_t N, uint32_t flags, void* hip_stream) {
   const bct_status st = check_linear(x, w, out, rows, K, N);
@@ -308,14 +348,25 @@ bct_status bctm_linear(const void* x, const void* w, const void* residual, void*
   if (flags & ~BCTM_X_TILED) return mfail(BCT_ERR_INVALID_ARG, "linear takes only BCTM_X_TILED");
   if (x == out) return mfail(BCT_ERR_INVALID_ARG, "out must not be x");
   if (!al16(residual)) return mfail(BCT_ERR_MISALIGNED, "pointers must be 16-byte aligned");
-  const dim3 grid(N / 16, (rows + 31) / 32), block(64 * kLinWaves);
-  if (flags & BCTM_X_TILED)
-    hipLaunchKernelGGL((linear_kernel<false, true>), grid, block, 0, (hipStream_t)hip_stream, (const uint16_t*)x,
-                       (const u32x4*)w, (const u32x4*)nullptr, (const uint16_t*)residual, (uint16_t*)out, rows, K, N, 0u);
-  else
-    hipLaunchKernelGGL((linear_kernel<false, false>), grid, block, 0, (hipStream_t)hip_stream, (const uint16_t*)x,
-                       (const u32x4*)w, (const u32x4*)nullptr, (const uint16_t*)residual, (uint16_t*)out, rows, K, N, 0u);
-  return launched("linear");
+  const LinearOut dst = {{(uint16_t*)out, nullptr, nullptr}, {0u, N, N, N}};
+  return launch_linear(x, w, residual, dst, rows, K, N, flags, hip_stream);
+}
+
+bct_status bctm_linear_split(const void* x, const void* w, void* out0, uint32_t N0, void* out1, uint32_t N1,
+                             void* out2, uint32_t N2, uint32_t rows, uint32_t K, uint32_t flags, void* hip_stream) {
+  if (N0 == 0 || N1 == 0) return mfail(BCT_ERR_INVALID_ARG, "the first two outputs must not be empty");
+  if ((uint64_t)N0 + N1 + N2 > 0xFFFFFFF0ull) return mfail(BCT_ERR_UNSUPPORTED, "too many features");
+  const uint32_t N = N0 + N1 + N2;
+  const bct_status st = check_linear(x, w, out0, rows, K, N);
+  if (st != BCT_OK) return st;
+  if (flags & ~BCTM_X_TILED) return mfail(BCT_ERR_INVALID_ARG, "linear takes only BCTM_X_TILED");
+  if (!out1 || (N2 && !out2)) return mfail(BCT_ERR_INVALID_ARG, "NULL pointer or zero size");
+  if (N0 % 16 != 0 || N1 % 16 != 0 || N2 % 16 != 0)
+    return mfail(BCT_ERR_UNSUPPORTED, "every output width must be a multiple of 16");
+  if (x == out0 || x == out1 || x == out2) return mfail(BCT_ERR_INVALID_ARG, "out must not be x");
+  if (!al16(out1) || !al16(out2)) return mfail(BCT_ERR_MISALIGNED, "pointers must be 16-byte aligned");
+  const LinearOut dst = {{(uint16_t*)out0, (uint16_t*)out1, (uint16_t*)out2}, {0u, N0, N0 + N1, N}};
+  return launch_linear(x, w, nullptr, dst, rows, K, N, flags, hip_stream);
 }
 
 bct_status bctm_swiglu(const void* x, const void* w_gate, const void* w_up, void* out, uint32_t rows, uint32_t K,
@@ -328,14 +379,17 @@ bct_status bctm_swiglu(const void* x, const void* w_gate, const void* w_up, void
   if ((flags & BCTM_OUT_TILED) && N % 32 != 0)
     return mfail(BCT_ERR_UNSUPPORTED, "tiled activations need a multiple of 32 columns");
   if (!al16(w_up)) return mfail(BCT_ERR_MISALIGNED, "pointers must be 16-byte aligned");
-  const dim3 grid(N / 16, (rows + 31) / 32), block(64 * kLinWaves);
+  const dim3 grid(N / 16, (rows + 31) / 32), block(64 * kGluWaves);
   const uint32_t ot = flags & BCTM_OUT_TILED ? 1u : 0u;
+  const LinearOut dst = {{(uint16_t*)out, nullptr, nullptr}, {0u, N, N, N}};
   if (flags & BCTM_X_TILED)
-    hipLaunchKernelGGL((linear_kernel<true, true>), grid, block, 0, (hipStream_t)hip_stream, (const uint16_t*)x,
-                       (const u32x4*)w_gate, (const u32x4*)w_up, (const uint16_t*)nullptr, (uint16_t*)out, rows, K, N, ot);
+    hipLaunchKernelGGL((linear_kernel<true, true, kGluWaves, kGluUnroll>), grid, block, 0, (hipStream_t)hip_stream,
+                       (const uint16_t*)x, (const u32x4*)w_gate, (const u32x4*)w_up, (const uint16_t*)nullptr, dst, rows,
+                       K, ot);
   else
-    hipLaunchKernelGGL((linear_kernel<true, false>), grid, block, 0, (hipStream_t)hip_stream, (const uint16_t*)x,
-                       (const u32x4*)w_gate, (const u32x4*)w_up, (const uint16_t*)nullptr, (uint16_t*)out, rows, K, N, ot);
+    hipLaunchKernelGGL((linear_kernel<true, false, kGluWaves, kGluUnroll>), grid, block, 0, (hipStream_t)hip_stream,
+                       (const uint16_t*)x, (const u32x4*)w_gate, (const u32x4*)w_up, (const uint16_t*)nullptr, dst, rows,
+                       K, ot);
   return launched("swiglu");
 }
 

@@ -14,7 +14,8 @@ from dataclasses import dataclass
 from . import binding
 from .binding import BCT_OK, BctCache, BctError, _dptr, _stream_ptr, _torch
 
-MODEL_EXPORTS = ["bctm_embed", "bctm_rmsnorm", "bctm_pack_weight", "bctm_pack_rows", "bctm_linear", "bctm_swiglu",
+MODEL_EXPORTS = ["bctm_embed", "bctm_rmsnorm", "bctm_pack_weight", "bctm_pack_rows", "bctm_linear", "bctm_linear_split",
+                 "bctm_swiglu",
                  "bctm_argmax", "bctm_last_error"]
 
 BCTM_X_TILED = 1
@@ -35,6 +36,7 @@ def mlib() -> ctypes.CDLL:
     L.bctm_pack_weight.argtypes = [vp, vp, u32, u32, vp]
     L.bctm_pack_rows.argtypes = [vp, vp, u32, u32, vp]
     L.bctm_linear.argtypes = [vp, vp, vp, vp, u32, u32, u32, u32, vp]
+    L.bctm_linear_split.argtypes = [vp, vp, vp, u32, vp, u32, vp, u32, u32, u32, u32, vp]
     L.bctm_swiglu.argtypes = [vp, vp, vp, vp, u32, u32, u32, u32, vp]
     L.bctm_argmax.argtypes = [vp, vp, u32, u32, vp]
     for n in MODEL_EXPORTS[:-1]:
@@ -143,13 +145,20 @@ class PackedWeight:
         self.data, self.N, self.K = data, N, K
 
 
-def bctm_pack_weight(w):
+def bctm_pack_weight(*ws):
+    """One or more matrices [N_i][K] -> one PackedWeight of sum N_i features, matrix after matrix."""
     torch = _torch()
-    _bf16_2d(w, "w")
-    N, K = w.shape
-    data = torch.empty(N * K, dtype=torch.bfloat16, device=w.device)
-    with torch.cuda.device(w.device):
-        _ck(mlib().bctm_pack_weight(_dptr(w), _dptr(data), N, K, _stream_ptr()), "bctm_pack_weight")
+    for w in ws:
+        _bf16_2d(w, "w", ws[0].shape[1])
+    K = ws[0].shape[1]
+    N = sum(w.shape[0] for w in ws)
+    data = torch.empty(N * K, dtype=torch.bfloat16, device=ws[0].device)
+    off = 0
+    with torch.cuda.device(ws[0].device):
+        for w in ws:
+            _ck(mlib().bctm_pack_weight(_dptr(w), _dptr(data[off:]), w.shape[0], K, _stream_ptr()),
+                "bctm_pack_weight")
+            off += w.shape[0] * K
     return PackedWeight(data, N, K)
 
 
@@ -185,6 +194,24 @@ def bctm_linear(x, w, residual=None, out=None):
         _ck(mlib().bctm_linear(_dptr(xd), _dptr(w.data), _dptr(residual), _dptr(out), rows, K, N, xf,
                                _stream_ptr()), "bctm_linear")
     return out
+
+
+def bctm_linear_split(x, w, outs):
+    """One projection into two or three row-major outputs whose widths add up to w.N."""
+    xd, rows, K, xf = _x_arg(x)
+    _packed(w, "w", K)
+    if len(outs) not in (2, 3) or sum(o.shape[1] for o in outs) != w.N:
+        raise ValueError("outs: two or three tensors whose widths add up to the weight's features")
+    for o in outs:
+        _bf16_2d(o, "out")
+        if o.shape[0] != rows:
+            raise ValueError("outs: one row per row of x")
+    o2, n2 = (outs[2], outs[2].shape[1]) if len(outs) == 3 else (None, 0)
+    torch = _torch()
+    with torch.cuda.device(xd.device):
+        _ck(mlib().bctm_linear_split(_dptr(xd), _dptr(w.data), _dptr(outs[0]), outs[0].shape[1], _dptr(outs[1]),
+                                     outs[1].shape[1], _dptr(o2), n2, rows, K, xf, _stream_ptr()), "bctm_linear_split")
+    return outs
 
 
 def bctm_swiglu(x, w_gate, w_up, out=None, tiled=False):
@@ -300,7 +327,12 @@ class BctStack:
             for n, shp in s.weight_shapes().items():
                 if tuple(lw[n].shape) != shp or lw[n].dtype != torch.bfloat16:
                     raise ValueError(f"layer {l} {n}: expected bf16 {shp}")
-                pl[n] = bctm_pack_weight(lw[n]) if len(shp) == 2 else lw[n]
+                if len(shp) == 1:
+                    pl[n] = lw[n]
+                elif n not in ("w_q", "w_wq", "w_wv"):
+                    pl[n] = bctm_pack_weight(lw[n])
+            # the three projections of the attention input run as one launch with three outputs
+            pl["w_qkv"] = bctm_pack_weight(lw["w_q"], lw["w_wq"], lw["w_wv"])
             self.layers.append(pl)
         self.embed, self.final_norm = weights["embed"], weights["final_norm"]
         self.head = bctm_pack_weight(weights["head"])
@@ -319,23 +351,23 @@ class BctStack:
             self._bufs[k] = TiledRows(rows, cols, self.device)
         return self._bufs[k]
 
-    def forward(self, ids, T=1):
+    def forward(self, ids, T=1, next_ids=None):
         """ids int32 [B*T] (sequence-major: row b*T + t) -> (next ids int32 [B*T], logits [B*T][vocab]).
-        T = 1 is a decode step; T > 1 pushes a chunk of T tokens per sequence through bct_prefill."""
+        T = 1 is a decode step; T > 1 pushes a chunk of T tokens per sequence through bct_prefill.
+        next_ids: where to write the greedy tokens (may be ids itself: it is read first, written last).
+        After the first call of a given (B, T) no memory is allocated, so a call can be captured in a HIP graph."""
         s = self.shape
         rows = s.batch * T
         if ids.numel() != rows:
             raise ValueError(f"ids: expected {rows} entries")
         x = bctm_embed(ids, self.embed, self._buf("x", rows, s.dim))
         # every input of a projection is kept tiled, so that the projections read it in whole kilobytes
-        h, at, f = self._tiled("h", rows, s.dim), self._tiled("a", rows, s.q_width), self._tiled("f", rows, s.ffn)
+        h, f = self._tiled("h", rows, s.dim), self._tiled("f", rows, s.ffn)
         q, wq, wv = self._buf("q", rows, s.q_width), self._buf("wq", rows, s.kv_width), self._buf("wv", rows, s.kv_width)
         a = self._buf("a", rows, s.q_width)
         for l, lw in enumerate(self.layers):
             bctm_rmsnorm(x, lw["attn_norm"], s.eps, h, tiled=True)
-            bctm_linear(h, lw["w_q"], None, q)
-            bctm_linear(h, lw["w_wq"], None, wq)
-            bctm_linear(h, lw["w_wv"], None, wv)
+            bctm_linear_split(h, lw["w_qkv"], (q, wq, wv))
             c = self.caches[l]
             if T == 1:
                 c.decode_step(q.view(s.batch, s.n_q_heads, s.head_dim), wq.view(s.batch, s.n_kv_heads, s.head_dim),
@@ -345,11 +377,11 @@ class BctStack:
                 c.prefill(q.view(s.batch, T, s.n_q_heads, s.head_dim), wq.view(s.batch, T, s.n_kv_heads, s.head_dim),
                           wv.view(s.batch, T, s.n_kv_heads, s.head_dim), T,
                           a.view(s.batch, T, s.n_q_heads, s.head_dim))
-            bctm_linear(bctm_pack_rows(a, at), lw["w_o"], x, x)
+            bctm_linear(a, lw["w_o"], x, x)     # row-major: re-tiling a would cost more than it saves
             bctm_rmsnorm(x, lw["mlp_norm"], s.eps, h, tiled=True)
             bctm_swiglu(h, lw["w_gate"], lw["w_up"], f, tiled=True)
             bctm_linear(f, lw["w_down"], x, x)
         bctm_rmsnorm(x, self.final_norm, s.eps, h, tiled=True)
         logits = bctm_linear(h, self.head, None, self._buf("logits", rows, s.vocab))
-        nxt = bctm_argmax(logits, None)
+        nxt = bctm_argmax(logits, next_ids)
         return nxt, logits

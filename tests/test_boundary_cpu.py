@@ -68,6 +68,11 @@ def test_model_entry_points_check_arguments_before_touching_the_gpu(L):
     assert ML.bctm_linear(a, b, None, a, 4, 64, 32, 0, None) == P.BCT_ERR_INVALID_ARG        # out is x
     assert ML.bctm_swiglu(a, b, b, c, 4, 64, 48, 2, None) == P.BCT_ERR_UNSUPPORTED           # tiled out: N % 32
     assert ML.bctm_swiglu(a, b, b, c, 4, 64, 32, 8, None) == P.BCT_ERR_INVALID_ARG
+    d = p(0x50000)
+    assert ML.bctm_linear_split(a, b, c, 32, d, 24, None, 0, 4, 64, 0, None) == P.BCT_ERR_UNSUPPORTED   # width % 16
+    assert ML.bctm_linear_split(a, b, c, 32, None, 16, None, 0, 4, 64, 0, None) == P.BCT_ERR_INVALID_ARG
+    assert ML.bctm_linear_split(a, b, c, 32, d, 16, None, 16, 4, 64, 0, None) == P.BCT_ERR_INVALID_ARG  # out2 missing
+    assert ML.bctm_linear_split(a, b, c, 0, d, 16, None, 0, 4, 64, 0, None) == P.BCT_ERR_INVALID_ARG
     assert ML.bctm_pack_rows(a, b, 4, 40, None) == P.BCT_ERR_UNSUPPORTED
     assert ML.bctm_pack_rows(a, a, 4, 64, None) == P.BCT_ERR_INVALID_ARG
     assert ML.bctm_embed(None, b, c, 4, 10, 64, None) == P.BCT_ERR_INVALID_ARG

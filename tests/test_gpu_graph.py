@@ -60,3 +60,44 @@ def test_captured_token_step_replays_exactly():
         # unrelated eager work between replays
         junk = torch.randn(1 << 20, device="cuda:0").sum().item()
         assert np.isfinite(junk)
+
+
+def test_captured_stack_step_replays_exactly():
+    """The whole decoder token-step (glue kernels and attention, the greedy ids fed back in place) as one graph:
+    every replay gives the ids, logits and cache state of the eager stack."""
+    import torch
+    from paper_2411_15785_amd import model as M
+    s = M.StackShape(n_layers=2, dim=256, n_q_heads=4, n_kv_heads=2, head_dim=64, ffn=512, vocab=320,
+                     capacity_M=128, batch=3)
+    w = syn.make_stack_weights(s, seed=8)
+
+    def dev_weights():
+        d = lambda a: to_dev(a, "bf16")
+        return {"embed": d(w["embed"]), "final_norm": d(w["final_norm"]), "head": d(w["head"]),
+                "layers": [{k: d(v) for k, v in lw.items()} for lw in w["layers"]], "keys": [d(k) for k in w["keys"]]}
+
+    eager, graphed = M.BctStack(s, dev_weights()), M.BctStack(s, dev_weights())
+    ids0 = torch.from_numpy(syn.make_token_ids(8, 0, s.batch, s.vocab)).cuda()
+    e_ids, g_ids = ids0.clone(), ids0.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):          # warm-up on a side stream: allocates the activation buffers
+        graphed.forward(g_ids, next_ids=g_ids)
+    torch.cuda.current_stream().wait_stream(side)
+    eager.forward(e_ids, next_ids=e_ids)
+    torch.cuda.synchronize()
+    assert torch.equal(e_ids, g_ids)
+
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        _, g_logits = graphed.forward(g_ids, next_ids=g_ids)
+    for t in range(5):
+        g.replay()
+        _, e_logits = eager.forward(e_ids, next_ids=e_ids)
+        torch.cuda.synchronize()
+        assert torch.equal(g_ids, e_ids), f"replay {t}: greedy ids differ from eager"
+        assert torch.equal(g_logits, e_logits), f"replay {t}: logits differ from eager"
+        for l in range(s.n_layers):
+            assert torch.equal(graphed.caches[l].values_view(), eager.caches[l].values_view()), f"replay {t}: state"
+        junk = torch.randn(1 << 20, device="cuda:0").sum().item()
+        assert np.isfinite(junk)

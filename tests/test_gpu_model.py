@@ -104,6 +104,20 @@ def test_rmsnorm_tiled_out(M, rows, dim):
     assert np.array_equal(untile(t, rows, dim), plain)
 
 
+@pytest.mark.parametrize("rows,K,widths", [(32, 4096, (512, 128, 128)), (7, 320, (48, 16, 32)), (33, 64, (16, 64))])
+def test_linear_split_is_bitwise_the_separate_projections(M, rows, K, widths):
+    import torch
+    x = dev(draw(1, (rows, K)))
+    ws = [dev(draw(20 + i, (n, K), K ** -0.5)) for i, n in enumerate(widths)]
+    outs = [torch.empty((rows, n), dtype=torch.bfloat16, device="cuda") for n in widths]
+    for xin in (x, M.bctm_pack_rows(x)):
+        for o in outs:
+            o.zero_()
+        M.bctm_linear_split(xin, M.bctm_pack_weight(*ws), outs)
+        for o, w in zip(outs, ws):
+            assert np.array_equal(host(o), host(M.bctm_linear(x, M.bctm_pack_weight(w))))
+
+
 def test_linear_in_place_residual(M):
     rows, K, N = 7, 256, 128
     x, w, res = draw(1, (rows, K)), draw(2, (N, K), K ** -0.5), draw(3, (rows, N))
