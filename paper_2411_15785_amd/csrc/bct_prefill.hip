@@ -466,22 +466,26 @@ __global__ __launch_bounds__(256) void prefill_read_kernel(const PrefillParams p
 // MV tile of 128 slots: acc = MV_start; tokens are walked 64 at a time; at the
 // start of every sub-chunk c >= 1 (if reads follow) round(acc) is left as MV_c;
 // acc += WW^T . WV; finally MV = round(acc).  The write weights are recomputed
-// per token tile.  Eight wavefronts; the workgroup needs 72 KB of LDS and at
-// most 128 registers per lane, so two workgroups share a CU and one's memory
-// round trips and barriers overlap the other's products.  Each wavefront keeps
-// the key fragments of its 32 slots in registers (loaded straight from memory
-// in operand layout); for the scores it takes 32 tokens x 32 slots, for the
-// state product 32 slots x d/2 value columns.
+// per token tile and never leave the registers: a wavefront owns 32 slots and
+// all d value columns.  Its score product has rows = tokens, columns = slots, so
+// lane l ends up with the weights of slot l % 32 for the tokens
+// 8 q + 4 (l / 32) + i (q, i = 0..3) of a 32-token step: per 16 tokens that is
+// 4 + 4 values, which is an A operand (row = slot, 8 contraction entries per
+// lane) of the state product once the B operand (WV^T) takes its tokens in the
+// same order -- two 8-byte LDS reads instead of one 16-byte read.  Only the
+// token tiles (write queries, WV^T, row statistics) go through LDS, two
+// barriers per 64 tokens; between them the four wavefronts run on their own, so
+// one's exponentials overlap another's products.  Each wavefront keeps the key
+// fragments of its slots in registers (loaded straight from memory in operand
+// layout).
 template <int D>
-__global__ __launch_bounds__(512, 4) void prefill_state_kernel(const PrefillParams p) {
-  constexpr int LD = D + 8, KS = D / 16, NT = 512;
+__global__ __launch_bounds__(256, 2) void prefill_state_kernel(const PrefillParams p) {
+  constexpr int LD = D + 8, KS = D / 16, NT = 256;
   constexpr int TT = 64;        // tokens per tile
-  constexpr int LP = TT + 8;    // row length of tiles contracted over the tile's tokens
-  constexpr int SNJ = D / 64;   // 32-column tiles per wavefront in the state product
+  constexpr int LP = TT + 8;    // row length of the WV^T tile
+  constexpr int NJ = D / 32;    // 32-column tiles of the state product
   __shared__ __attribute__((aligned(16))) uint16_t sXw[TT * LD];
   __shared__ __attribute__((aligned(16))) uint16_t sWVt[D * LP];
-  __shared__ __attribute__((aligned(16))) uint16_t sPh[128 * LP];
-  __shared__ __attribute__((aligned(16))) uint16_t sPl[128 * LP];
   __shared__ float2 sNorm[TT];
 
   const uint32_t unit = blockIdx.y, b = unit / p.Hkv, h = unit % p.Hkv;
@@ -491,27 +495,25 @@ __global__ __launch_bounds__(512, 4) void prefill_state_kernel(const PrefillPara
   const uint16_t* mk = p.mk + (size_t)(p.mk_per_seq ? unit : h) * p.M * D;
   uint16_t* mv = p.mv + ((size_t)unit * p.M + m0) * D;
 
-  // both roles of a wavefront use the same 32 slots; M is a multiple of 64, so
-  // the 32 slots are all inside the memory or all outside
-  const int sg = wave & 3, hi2 = wave >> 2;
-  const bool live = m0 + 32 * sg < p.M;
+  // M is a multiple of 64, so a wavefront's 32 slots are all inside the memory or all outside
+  const int mslot = 32 * wave;
+  const bool live = m0 + mslot < p.M;
   bf16x8 kb[KS];
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) {
     u32x4 v = {0u, 0u, 0u, 0u};
-    if (live) v = *(const u32x4*)(mk + (size_t)(m0 + 32 * sg + col) * D + ks * 16 + half * 8);
+    if (live) v = *(const u32x4*)(mk + (size_t)(m0 + mslot + col) * D + ks * 16 + half * 8);
     kb[ks] = __builtin_bit_cast(bf16x8, v);
   }
   // state product: lane column = value column, accumulator rows = slots
-  const int mslot = 32 * sg, mcol = (D / 2) * hi2;
-  f32x16 macc[SNJ];
+  f32x16 macc[NJ];
 #pragma unroll
-  for (int jt = 0; jt < SNJ; ++jt) {
+  for (int jt = 0; jt < NJ; ++jt) {
     macc[jt] = zero16();
     if (live) {
 #pragma unroll
       for (int v = 0; v < 16; ++v)
-        macc[jt][v] = bf16_val(mv[(size_t)(mslot + 8 * (v / 4) + 4 * half + (v % 4)) * D + mcol + 32 * jt + col]);
+        macc[jt][v] = bf16_val(mv[(size_t)(mslot + 8 * (v / 4) + 4 * half + (v % 4)) * D + 32 * jt + col]);
     }
   }
 
@@ -534,10 +536,10 @@ __global__ __launch_bounds__(512, 4) void prefill_state_kernel(const PrefillPara
       // MV at the start of sub-chunk c, transposed ([column][slot]) for the read kernel
       uint16_t* sn = p.snap + ((size_t)(t0 / kTC) * units + unit) * p.M * D + m0 + mslot + 4 * half;
 #pragma unroll
-      for (int jt = 0; jt < SNJ; ++jt)
+      for (int jt = 0; jt < NJ; ++jt)
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4)
-          store4_bf16(sn + (size_t)(mcol + 32 * jt + col) * p.M + 8 * q4, macc[jt][4 * q4 + 0], macc[jt][4 * q4 + 1],
+          store4_bf16(sn + (size_t)(32 * jt + col) * p.M + 8 * q4, macc[jt][4 * q4 + 0], macc[jt][4 * q4 + 1],
                       macc[jt][4 * q4 + 2], macc[jt][4 * q4 + 3]);
     }
     __syncthreads();
@@ -546,46 +548,58 @@ __global__ __launch_bounds__(512, 4) void prefill_state_kernel(const PrefillPara
     if (threadIdx.x < TT) sNorm[threadIdx.x] = (t0 + threadIdx.x < T) ? tn : make_float2(0.f, 0.f);
     if (tt + 1 < ntile) fetch_tokens(t0 + TT);  // next tile, in flight during this one's products
     __syncthreads();
-    {
-      // scores: rows = tokens (32 per wavefront), columns = this wavefront's 32 slots
-      const int tok0 = 32 * hi2;
+#pragma unroll
+    for (int st = 0; st < TT / 32; ++st) {
+      const int tok0 = 32 * st;
+      // scores: rows = tokens, columns = this wavefront's 32 slots
       f32x16 sc = zero16();
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) sc = mfma_bf16(frag(sXw, LD, tok0 + col, ks * 16 + half * 8), kb[ks], sc);
+      // weights, split into hi + lo bf16 parts: words 0-1 of an operand from q4 = 2 ks, words 2-3 from 2 ks + 1
+      u32x4 ah[2], al[2];
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
         const int tl = tok0 + 8 * q4 + 4 * half;
-        float hi[4], lo[4];
+        float w[4], lo[4];
+        uint32_t hw[2];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const float2 n = sNorm[tl + i];
-          const float w = fast_exp2(sc[4 * q4 + i] * p.wscale_l2e - n.x) * n.y;
-          hi[i] = bf16_val(bf16_bits(w));
-          lo[i] = w - hi[i];
+          w[i] = fast_exp2(sc[4 * q4 + i] * p.wscale_l2e - n.x) * n.y;
         }
-        store4_bf16(sPh + (mslot + col) * LP + tl, hi[0], hi[1], hi[2], hi[3]);
-        store4_bf16(sPl + (mslot + col) * LP + tl, lo[0], lo[1], lo[2], lo[3]);
+        hw[0] = pack_bf16x2(w[0], w[1]);
+        hw[1] = pack_bf16x2(w[2], w[3]);
+        lo[0] = w[0] - __uint_as_float(hw[0] << 16);
+        lo[1] = w[1] - __uint_as_float(hw[0] & 0xFFFF0000u);
+        lo[2] = w[2] - __uint_as_float(hw[1] << 16);
+        lo[3] = w[3] - __uint_as_float(hw[1] & 0xFFFF0000u);
+        ah[q4 / 2][2 * (q4 % 2) + 0] = hw[0];
+        ah[q4 / 2][2 * (q4 % 2) + 1] = hw[1];
+        al[q4 / 2][2 * (q4 % 2) + 0] = pack_bf16x2(lo[0], lo[1]);
+        al[q4 / 2][2 * (q4 % 2) + 1] = pack_bf16x2(lo[2], lo[3]);
       }
-    }
-    __syncthreads();
+      // state product over the step's 32 tokens, 16 per MFMA, in the token order the weights came in:
+      // entries 0-3 of a lane's operand are tokens 16 ks + 4 half + 0..3, entries 4-7 the same + 8
 #pragma unroll
-    for (int ks = 0; ks < TT / 16; ++ks) {
-      const int k = ks * 16 + half * 8;
-      const bf16x8 ah = frag(sPh, LP, mslot + col, k), al = frag(sPl, LP, mslot + col, k);
+      for (int ks = 0; ks < 2; ++ks) {
+        const bf16x8 vh = __builtin_bit_cast(bf16x8, ah[ks]), vl = __builtin_bit_cast(bf16x8, al[ks]);
 #pragma unroll
-      for (int jt = 0; jt < SNJ; ++jt) {
-        const bf16x8 bv = frag(sWVt, LP, mcol + 32 * jt + col, k);
-        macc[jt] = mfma_bf16(ah, bv, macc[jt]);
-        macc[jt] = mfma_bf16(al, bv, macc[jt]);
+        for (int jt = 0; jt < NJ; ++jt) {
+          const uint16_t* src = sWVt + (32 * jt + col) * LP + tok0 + 16 * ks + 4 * half;
+          const uint2 b0 = *(const uint2*)src, b1 = *(const uint2*)(src + 8);
+          const bf16x8 bv = __builtin_bit_cast(bf16x8, (u32x4){b0.x, b0.y, b1.x, b1.y});
+          macc[jt] = mfma_bf16(vh, bv, macc[jt]);
+          macc[jt] = mfma_bf16(vl, bv, macc[jt]);
+        }
       }
     }
   }
   if (live) {
 #pragma unroll
-    for (int jt = 0; jt < SNJ; ++jt)
+    for (int jt = 0; jt < NJ; ++jt)
 #pragma unroll
       for (int v = 0; v < 16; ++v)
-        mv[(size_t)(mslot + 8 * (v / 4) + 4 * half + (v % 4)) * D + mcol + 32 * jt + col] = bf16_bits(macc[jt][v]);
+        mv[(size_t)(mslot + 8 * (v / 4) + 4 * half + (v % 4)) * D + 32 * jt + col] = bf16_bits(macc[jt][v]);
   }
 }
 
@@ -634,8 +648,8 @@ hipError_t launch_prefill_bf16(const PrefillParams& p0, hipStream_t s) {
   }
   if (p.has_write) {
     const dim3 g((p.M + 127) / 128, units);
-    if (d128) hipLaunchKernelGGL(prefill_state_kernel<128>, g, dim3(512), 0, s, p);
-    else hipLaunchKernelGGL(prefill_state_kernel<64>, g, dim3(512), 0, s, p);
+    if (d128) hipLaunchKernelGGL(prefill_state_kernel<128>, g, dim3(256), 0, s, p);
+    else hipLaunchKernelGGL(prefill_state_kernel<64>, g, dim3(256), 0, s, p);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (p.has_read && nb > 1 && (e = read(1, nb - 1)) != hipSuccess) return e;
   }
