@@ -39,6 +39,7 @@ namespace {
 
 constexpr int kTC = 128;          // tokens per sub-chunk = rows per tile
 constexpr float kNegBig = -1e30f;  // stands in for -inf in running maxima
+constexpr float kNoRow = 1e30f;    // shift of a row that does not exist: exp2(score - kNoRow) = 0
 
 __device__ __forceinline__ f32x16 mfma_bf16(const bf16x8 a, const bf16x8 b, const f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
@@ -161,8 +162,10 @@ __global__ __launch_bounds__(256) void prefill_transpose_kernel(const PrefillPar
 // ------------------------------------------------------------------ stats
 
 // Row statistics of the score matrix: for each write row (token t) and read
-// row (token t, query head g) of a memory, max and 1 / sum of exp2(score - max)
-// over all M slots.  One workgroup = 128 rows; it walks the keys 128 slots at
+// row (token t, query head g) of a memory, the shift max + log2(sum of
+// exp2(score - max)) over all M slots, so that a weight is exp2(score - shift)
+// with no further multiplication (stored in .x of a float2; rows that do not
+// exist use kNoRow, which makes every weight zero).  One workgroup = 128 rows; it walks the keys 128 slots at
 // a time; wavefront w scores slots 32w..32w+31 of the tile against all rows.
 template <int D>
 __global__ __launch_bounds__(256) void prefill_stats_kernel(const PrefillParams p) {
@@ -248,9 +251,9 @@ __global__ __launch_bounds__(256) void prefill_stats_kernel(const PrefillParams 
     for (int w = 1; w < 4; ++w) merge_stat(mm, ss, sRed[w][threadIdx.x].x, sRed[w][threadIdx.x].y);
     uint32_t row = row0 + threadIdx.x;
     if (row < nw) {
-      p.norm_w[(size_t)unit * p.T + row] = make_float2(mm, 1.0f / ss);
+      p.norm_w[(size_t)unit * p.T + row] = make_float2(mm + __log2f(ss), 0.f);
     } else if (row - nw < nr) {
-      p.norm_r[(size_t)unit * p.T * p.G + (row - nw)] = make_float2(mm, 1.0f / ss);
+      p.norm_r[(size_t)unit * p.T * p.G + (row - nw)] = make_float2(mm + __log2f(ss), 0.f);
     }
   }
 }
@@ -261,8 +264,13 @@ __global__ __launch_bounds__(256) void prefill_stats_kernel(const PrefillParams 
 // sub-chunk = token rho / G, query head rho % G):
 //     out = RW . MV_c  +  mask(RW . WW_c^T) . WV_c ,  mask: write token s <= the row's token.
 // The workgroup walks the M slots 64 at a time, recomputing the score tiles.
+// Eight wavefronts: for the scores each takes 32 rows x 32 slots of the tile,
+// for the products 32 output rows x d/2 value columns and 32 write tokens x 64
+// read rows of the within-sub-chunk matrix; that keeps a lane under 256
+// registers, so two wavefronts share a SIMD.
 template <int D, bool INTRA>
-__global__ __launch_bounds__(256) void prefill_read_kernel(const PrefillParams p) {
+__global__ __launch_bounds__(512) void prefill_read_kernel(const PrefillParams p) {
+  constexpr int NT = 512;
   constexpr int LD = D + 8, KS = D / 16;
   constexpr int LP = 64 + 8;    // row length of tiles contracted over 64 slots
   constexpr int LA = kTC + 8;   // row length of tiles contracted over 128 tokens
@@ -287,56 +295,56 @@ __global__ __launch_bounds__(256) void prefill_read_kernel(const PrefillParams p
   constexpr bool intra = INTRA;  // the chunk also writes: add the within-sub-chunk term
   const size_t units = (size_t)p.B * p.Hkv;
 
-  rows_to_lds<D, kTC>(sXr, LD, p.mk, [&](int r) -> const uint16_t* {
-    const uint32_t rho = rho0 + r, t = t0 + rho / G;
-    return t < T ? p.q + (((size_t)b * T + t) * p.Hq + h * G + rho % G) * D : nullptr;
-  });
+  {
+    Tile<kTC, D, NT> t;
+    t.fetch_rows(p.mk, [&](int r) -> const uint16_t* {
+      const uint32_t rho = rho0 + r, tk = t0 + rho / G;
+      return tk < T ? p.q + (((size_t)b * T + tk) * p.Hq + h * G + rho % G) * D : nullptr;
+    });
+    t.put(sXr, LD);
+  }
   if (intra) {
-    rows_to_lds<D, kTC>(sXw, LD, p.mk, [&](int r) -> const uint16_t* {
+    Tile<kTC, D, NT> t;
+    t.fetch_rows(p.mk, [&](int r) -> const uint16_t* {
       return t0 + r < T ? p.wq + (((size_t)b * T + t0 + r) * p.Hkv + h) * D : nullptr;
     });
+    t.put(sXw, LD);
   }
   const uint16_t* mk = p.mk + (size_t)(p.mk_per_seq ? unit : h) * p.M * D;
   // MV at the start of the sub-chunk, transposed: [column][slot]
   const uint16_t* mvt = p.snap + ((size_t)(intra ? c : 0u) * units + unit) * p.M * D;
 
-  // score step: wavefront = (slot half si, row half rj); lane column = row
+  // score step: wavefront = (slot half si, row group rj of 32); lane column = row
   const int si = wave & 1, rj = wave >> 1;
-  float2 nrm_r[2], nrm_w[2];
-#pragma unroll
-  for (int jt = 0; jt < 2; ++jt) {
-    const uint32_t r = 64 * rj + 32 * jt + col;
+  float nrm_r, nrm_w;
+  {
+    const uint32_t r = 32 * rj + col;
     const uint32_t rho = rho0 + r, t = t0 + rho / G;
-    nrm_r[jt] = t < T ? p.norm_r[(size_t)unit * T * G + (size_t)t * G + rho % G] : make_float2(0.f, 0.f);
-    nrm_w[jt] = (intra && t0 + r < T) ? p.norm_w[(size_t)unit * T + t0 + r] : make_float2(0.f, 0.f);
+    nrm_r = t < T ? p.norm_r[(size_t)unit * T * G + (size_t)t * G + rho % G].x : kNoRow;
+    nrm_w = (intra && t0 + r < T) ? p.norm_w[(size_t)unit * T + t0 + r].x : kNoRow;
   }
-  // product step: wavefront = (row block, value-column block)
-  constexpr int OMI = D / 64;                      // 32-row tiles per wavefront in the output product
-  const int orow = (D == 128) ? 64 * (wave & 1) : 32 * wave;
-  const int ocol = (D == 128) ? 64 * (wave >> 1) : 0;
-  f32x16 oacc[OMI][2], aacc[2][2];
+  // product step: wavefront = (32 output rows, half of the value columns) and, for the
+  // within-sub-chunk matrix, (32 write tokens, 64 read rows)
+  constexpr int NOC = D / 64;                      // 32-column tiles per wavefront in the output product
+  const int orow = 32 * (wave & 3), ocol = 32 * NOC * (wave >> 2);
+  const int as0 = 32 * (wave & 3), ar0 = 64 * (wave >> 2);
+  f32x16 oacc[NOC], aacc[2];
 #pragma unroll
-  for (int it = 0; it < OMI; ++it)
+  for (int jt = 0; jt < NOC; ++jt) oacc[jt] = zero16();
 #pragma unroll
-    for (int jt = 0; jt < 2; ++jt) oacc[it][jt] = zero16();
-#pragma unroll
-  for (int it = 0; it < 2; ++it)
-#pragma unroll
-    for (int jt = 0; jt < 2; ++jt) aacc[it][jt] = zero16();
+  for (int jt = 0; jt < 2; ++jt) aacc[jt] = zero16();
 
   // the query rows (and write-query rows) do not change over the loop: keep
   // their operand fragments in registers instead of re-reading LDS per tile
   __syncthreads();
-  bf16x8 xr[2][KS], xw[2][KS];
+  bf16x8 xr[KS], xw[KS];
 #pragma unroll
-  for (int jt = 0; jt < 2; ++jt)
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      xr[jt][ks] = frag(sXr, LD, 64 * rj + 32 * jt + col, ks * 16 + half * 8);
-      if (intra) xw[jt][ks] = frag(sXw, LD, 64 * rj + 32 * jt + col, ks * 16 + half * 8);
-    }
-  Tile<64, D> tk;
-  Tile<D, 64> tv;
+  for (int ks = 0; ks < KS; ++ks) {
+    xr[ks] = frag(sXr, LD, 32 * rj + col, ks * 16 + half * 8);
+    if (intra) xw[ks] = frag(sXw, LD, 32 * rj + col, ks * 16 + half * 8);
+  }
+  Tile<64, D, NT> tk;
+  Tile<D, 64, NT> tv;
   tk.fetch_block(mk, D);
   tv.fetch_block(mvt, p.M);
   for (uint32_t m0 = 0; m0 < p.M; m0 += 64) {
@@ -349,38 +357,24 @@ __global__ __launch_bounds__(256) void prefill_read_kernel(const PrefillParams p
     }
     __syncthreads();
     {
-      f32x16 sr[2], sw[2];
-#pragma unroll
-      for (int jt = 0; jt < 2; ++jt) {
-        sr[jt] = zero16();
-        sw[jt] = zero16();
-      }
+      f32x16 sr = zero16(), sw = zero16();
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        const int k = ks * 16 + half * 8;
-        const bf16x8 a = frag(sK, LD, 32 * si + col, k);
-#pragma unroll
-        for (int jt = 0; jt < 2; ++jt) {
-          sr[jt] = mfma_bf16(a, xr[jt][ks], sr[jt]);
-          if (intra) sw[jt] = mfma_bf16(a, xw[jt][ks], sw[jt]);
-        }
+        const bf16x8 a = frag(sK, LD, 32 * si + col, ks * 16 + half * 8);
+        sr = mfma_bf16(a, xr[ks], sr);
+        if (intra) sw = mfma_bf16(a, xw[ks], sw);
       }
+      const int r = 32 * rj + col;
 #pragma unroll
-      for (int jt = 0; jt < 2; ++jt) {
-        const int r = 64 * rj + 32 * jt + col;
+      for (int q4 = 0; q4 < 4; ++q4) {
+        float e[4];
 #pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-          float e[4];
+        for (int i = 0; i < 4; ++i) e[i] = fast_exp2(sr[4 * q4 + i] * p.rscale_l2e - nrm_r);
+        store4_bf16(sPr + r * LP + 32 * si + 8 * q4 + 4 * half, e[0], e[1], e[2], e[3]);
+        if (intra) {
 #pragma unroll
-          for (int i = 0; i < 4; ++i)
-            e[i] = fast_exp2(sr[jt][4 * q4 + i] * p.rscale_l2e - nrm_r[jt].x) * nrm_r[jt].y;
-          store4_bf16(sPr + r * LP + 32 * si + 8 * q4 + 4 * half, e[0], e[1], e[2], e[3]);
-          if (intra) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-              e[i] = fast_exp2(sw[jt][4 * q4 + i] * p.wscale_l2e - nrm_w[jt].x) * nrm_w[jt].y;
-            store4_bf16(sPw + r * LP + 32 * si + 8 * q4 + 4 * half, e[0], e[1], e[2], e[3]);
-          }
+          for (int i = 0; i < 4; ++i) e[i] = fast_exp2(sw[4 * q4 + i] * p.wscale_l2e - nrm_w);
+          store4_bf16(sPw + r * LP + 32 * si + 8 * q4 + 4 * half, e[0], e[1], e[2], e[3]);
         }
       }
     }
@@ -388,26 +382,14 @@ __global__ __launch_bounds__(256) void prefill_read_kernel(const PrefillParams p
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
       const int k = ks * 16 + half * 8;
-      bf16x8 bv[2];
+      const bf16x8 a = frag(sPr, LP, orow + col, k);
 #pragma unroll
-      for (int jt = 0; jt < 2; ++jt) bv[jt] = frag(sVt, LP, ocol + 32 * jt + col, k);
-#pragma unroll
-      for (int it = 0; it < OMI; ++it) {
-        const bf16x8 a = frag(sPr, LP, orow + 32 * it + col, k);
-#pragma unroll
-        for (int jt = 0; jt < 2; ++jt) oacc[it][jt] = mfma_bf16(a, bv[jt], oacc[it][jt]);
-      }
+      for (int jt = 0; jt < NOC; ++jt) oacc[jt] = mfma_bf16(a, frag(sVt, LP, ocol + 32 * jt + col, k), oacc[jt]);
       if (intra) {
         // rows of this product = write tokens s, columns = read rows
-        bf16x8 br[2];
+        const bf16x8 aw = frag(sPw, LP, as0 + col, k);
 #pragma unroll
-        for (int jt = 0; jt < 2; ++jt) br[jt] = frag(sPr, LP, 64 * (wave >> 1) + 32 * jt + col, k);
-#pragma unroll
-        for (int it = 0; it < 2; ++it) {
-          const bf16x8 a = frag(sPw, LP, 64 * (wave & 1) + 32 * it + col, k);
-#pragma unroll
-          for (int jt = 0; jt < 2; ++jt) aacc[it][jt] = mfma_bf16(a, br[jt], aacc[it][jt]);
-        }
+        for (int jt = 0; jt < 2; ++jt) aacc[jt] = mfma_bf16(aw, frag(sPr, LP, ar0 + 32 * jt + col, k), aacc[jt]);
       }
     }
   }
@@ -417,48 +399,42 @@ __global__ __launch_bounds__(256) void prefill_read_kernel(const PrefillParams p
     // A[row][s] = (s <= token of the row) ? sum_m rw[row][m] ww[s][m] : 0
 #pragma unroll
     for (int jt = 0; jt < 2; ++jt) {
-      const int r = 64 * (wave >> 1) + 32 * jt + col;
+      const int r = ar0 + 32 * jt + col;
       const int tl = (int)((rho0 + r) / G);  // the row's token within the sub-chunk
 #pragma unroll
-      for (int it = 0; it < 2; ++it)
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const int s0 = as0 + 8 * q4 + 4 * half;
+        float e[4];
 #pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-          const int s0 = 64 * (wave & 1) + 32 * it + 8 * q4 + 4 * half;
-          float e[4];
-#pragma unroll
-          for (int i = 0; i < 4; ++i) e[i] = (s0 + i <= tl) ? aacc[it][jt][4 * q4 + i] : 0.f;
-          store4_bf16(sA + r * LA + s0, e[0], e[1], e[2], e[3]);
-        }
+        for (int i = 0; i < 4; ++i) e[i] = (s0 + i <= tl) ? aacc[jt][4 * q4 + i] : 0.f;
+        store4_bf16(sA + r * LA + s0, e[0], e[1], e[2], e[3]);
+      }
     }
-    block_to_lds<D, kTC>(sWVt, LA, p.wvt + (size_t)unit * D * p.Tpad + t0, p.Tpad);
+    {
+      Tile<D, kTC, NT> t;
+      t.fetch_block(p.wvt + (size_t)unit * D * p.Tpad + t0, p.Tpad);
+      t.put(sWVt, LA);
+    }
     __syncthreads();
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
       const int k = ks * 16 + half * 8;
-      bf16x8 bv[2];
+      const bf16x8 a = frag(sA, LA, orow + col, k);
 #pragma unroll
-      for (int jt = 0; jt < 2; ++jt) bv[jt] = frag(sWVt, LA, ocol + 32 * jt + col, k);
-#pragma unroll
-      for (int it = 0; it < OMI; ++it) {
-        const bf16x8 a = frag(sA, LA, orow + 32 * it + col, k);
-#pragma unroll
-        for (int jt = 0; jt < 2; ++jt) oacc[it][jt] = mfma_bf16(a, bv[jt], oacc[it][jt]);
-      }
+      for (int jt = 0; jt < NOC; ++jt) oacc[jt] = mfma_bf16(a, frag(sWVt, LA, ocol + 32 * jt + col, k), oacc[jt]);
     }
   }
 
 #pragma unroll
-  for (int it = 0; it < OMI; ++it)
+  for (int v = 0; v < 16; ++v) {
+    const uint32_t r = orow + 8 * (v / 4) + 4 * half + (v % 4);
+    const uint32_t rho = rho0 + r, t = t0 + rho / G;
+    if (t < T) {
+      uint16_t* o = p.out + (((size_t)b * T + t) * p.Hq + h * G + rho % G) * D;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const uint32_t r = orow + 32 * it + 8 * (v / 4) + 4 * half + (v % 4);
-      const uint32_t rho = rho0 + r, t = t0 + rho / G;
-      if (t < T) {
-        uint16_t* o = p.out + (((size_t)b * T + t) * p.Hq + h * G + rho % G) * D;
-#pragma unroll
-        for (int jt = 0; jt < 2; ++jt) o[ocol + 32 * jt + col] = bf16_bits(oacc[it][jt][v]);
-      }
+      for (int jt = 0; jt < NOC; ++jt) o[ocol + 32 * jt + col] = bf16_bits(oacc[jt][v]);
     }
+  }
 }
 
 // ------------------------------------------------------------------ state
@@ -484,9 +460,14 @@ __global__ __launch_bounds__(256, 2) void prefill_state_kernel(const PrefillPara
   constexpr int TT = 64;        // tokens per tile
   constexpr int LP = TT + 8;    // row length of the WV^T tile
   constexpr int NJ = D / 32;    // 32-column tiles of the state product
-  __shared__ __attribute__((aligned(16))) uint16_t sXw[TT * LD];
-  __shared__ __attribute__((aligned(16))) uint16_t sWVt[D * LP];
-  __shared__ float2 sNorm[TT];
+  constexpr int LS = 128 + 8;   // row length of the snapshot staging tile [column][slot]
+  static_assert(TT * LD + D * LP >= D * LS && TT * LD + D * LP >= 128 * LD, "the staging tiles reuse the token tiles");
+  __shared__ __attribute__((aligned(16))) uint16_t sTok[TT * LD + D * LP];
+  __shared__ __attribute__((aligned(16))) float sNorm[TT];
+  uint16_t* const sXw = sTok;
+  uint16_t* const sWVt = sTok + TT * LD;
+  uint16_t* const sSnap = sTok;    // [column][slot] snapshot on its way out
+  uint16_t* const sStage = sTok;   // [slot][column] MV tile on its way in and out
 
   const uint32_t unit = blockIdx.y, b = unit / p.Hkv, h = unit % p.Hkv;
   const uint32_t m0 = blockIdx.x * 128, T = p.T;
@@ -505,47 +486,64 @@ __global__ __launch_bounds__(256, 2) void prefill_state_kernel(const PrefillPara
     if (live) v = *(const u32x4*)(mk + (size_t)(m0 + mslot + col) * D + ks * 16 + half * 8);
     kb[ks] = __builtin_bit_cast(bf16x8, v);
   }
-  // state product: lane column = value column, accumulator rows = slots
+  // state product: lane column = value column, accumulator rows = slots.  The MV tile comes in (and
+  // at the end leaves) through LDS in whole rows; a lane picks its 16 x NJ elements from there.
   f32x16 macc[NJ];
-#pragma unroll
-  for (int jt = 0; jt < NJ; ++jt) {
-    macc[jt] = zero16();
-    if (live) {
-#pragma unroll
-      for (int v = 0; v < 16; ++v)
-        macc[jt][v] = bf16_val(mv[(size_t)(mslot + 8 * (v / 4) + 4 * half + (v % 4)) * D + 32 * jt + col]);
-    }
+  {
+    Tile<128, D, NT> tm;
+    tm.fetch_rows(p.mk, [&](int r) -> const uint16_t* { return m0 + r < p.M ? mv + (size_t)r * D : nullptr; });
+    tm.put(sStage, LD);
   }
+  __syncthreads();
+#pragma unroll
+  for (int jt = 0; jt < NJ; ++jt)
+#pragma unroll
+    for (int v = 0; v < 16; ++v)
+      macc[jt][v] = bf16_val(sStage[(mslot + 8 * (v / 4) + 4 * half + (v % 4)) * LD + 32 * jt + col]);
 
   const uint32_t ntile = (T + TT - 1) / TT;
   Tile<TT, D, NT> tx;
   Tile<D, TT, NT> tw;
-  float2 tn = make_float2(0.f, 0.f);
+  float tn = 0.f;
+  // Tokens past the end of the chunk load the last token instead: their weights are zero (kNoRow) and
+  // their WV^T columns are zero-filled, so whatever finite scores they get changes nothing.
   auto fetch_tokens = [&](uint32_t t0) {
     tx.fetch_rows(p.mk, [&](int r) -> const uint16_t* {
-      return t0 + r < T ? p.wq + (((size_t)b * T + t0 + r) * p.Hkv + h) * D : nullptr;
+      return p.wq + (((size_t)b * T + min(t0 + r, T - 1)) * p.Hkv + h) * D;
     });
     tw.fetch_block(p.wvt + (size_t)unit * D * p.Tpad + t0, p.Tpad);
-    if (threadIdx.x < TT)
-      tn = p.norm_w[(size_t)unit * T + (t0 + threadIdx.x < T ? t0 + threadIdx.x : 0u)];
+    if (threadIdx.x < TT) tn = p.norm_w[(size_t)unit * T + min(t0 + threadIdx.x, T - 1)].x;
   };
   fetch_tokens(0);
   for (uint32_t tt = 0; tt < ntile; ++tt) {
     const uint32_t t0 = tt * TT;
-    if (p.has_read && tt > 0 && (t0 % kTC) == 0 && live) {
-      // MV at the start of sub-chunk c, transposed ([column][slot]) for the read kernel
-      uint16_t* sn = p.snap + ((size_t)(t0 / kTC) * units + unit) * p.M * D + m0 + mslot + 4 * half;
+    if (p.has_read && tt > 0 && (t0 % kTC) == 0) {
+      // MV at the start of sub-chunk c, transposed ([column][slot]) for the read kernel.  A lane holds
+      // 4 consecutive slots of one column, and columns are M elements apart in memory, so the tile
+      // goes through LDS (in place of the token tiles, which nobody reads any more) and leaves in
+      // whole 256-byte rows.
+      __syncthreads();
+      if (live) {
 #pragma unroll
-      for (int jt = 0; jt < NJ; ++jt)
+        for (int jt = 0; jt < NJ; ++jt)
 #pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4)
-          store4_bf16(sn + (size_t)(32 * jt + col) * p.M + 8 * q4, macc[jt][4 * q4 + 0], macc[jt][4 * q4 + 1],
-                      macc[jt][4 * q4 + 2], macc[jt][4 * q4 + 3]);
+          for (int q4 = 0; q4 < 4; ++q4)
+            store4_bf16(sSnap + (32 * jt + col) * LS + mslot + 8 * q4 + 4 * half, macc[jt][4 * q4 + 0],
+                        macc[jt][4 * q4 + 1], macc[jt][4 * q4 + 2], macc[jt][4 * q4 + 3]);
+      }
+      __syncthreads();
+      uint16_t* sn = p.snap + ((size_t)(t0 / kTC) * units + unit) * p.M * D + m0;
+      const int ch = threadIdx.x % 16;   // 16-byte chunk = 8 slots; M is a multiple of 64
+      if (m0 + 8 * ch < p.M) {
+#pragma unroll
+        for (int r = threadIdx.x / 16; r < D; r += NT / 16)
+          *(u32x4*)(sn + (size_t)r * p.M + 8 * ch) = *(const u32x4*)(sSnap + r * LS + 8 * ch);
+      }
     }
     __syncthreads();
     tx.put(sXw, LD);
     tw.put(sWVt, LP);
-    if (threadIdx.x < TT) sNorm[threadIdx.x] = (t0 + threadIdx.x < T) ? tn : make_float2(0.f, 0.f);
+    if (threadIdx.x < TT) sNorm[threadIdx.x] = (t0 + threadIdx.x < T) ? tn : kNoRow;
     if (tt + 1 < ntile) fetch_tokens(t0 + TT);  // next tile, in flight during this one's products
     __syncthreads();
 #pragma unroll
@@ -559,47 +557,49 @@ __global__ __launch_bounds__(256, 2) void prefill_state_kernel(const PrefillPara
       u32x4 ah[2], al[2];
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
-        const int tl = tok0 + 8 * q4 + 4 * half;
-        float w[4], lo[4];
-        uint32_t hw[2];
+        const f32x4 sh = *(const f32x4*)(sNorm + tok0 + 8 * q4 + 4 * half);   // shifts of the lane's 4 tokens
+        float w[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const float2 n = sNorm[tl + i];
-          w[i] = fast_exp2(sc[4 * q4 + i] * p.wscale_l2e - n.x) * n.y;
-        }
-        hw[0] = pack_bf16x2(w[0], w[1]);
-        hw[1] = pack_bf16x2(w[2], w[3]);
-        lo[0] = w[0] - __uint_as_float(hw[0] << 16);
-        lo[1] = w[1] - __uint_as_float(hw[0] & 0xFFFF0000u);
-        lo[2] = w[2] - __uint_as_float(hw[1] << 16);
-        lo[3] = w[3] - __uint_as_float(hw[1] & 0xFFFF0000u);
-        ah[q4 / 2][2 * (q4 % 2) + 0] = hw[0];
-        ah[q4 / 2][2 * (q4 % 2) + 1] = hw[1];
-        al[q4 / 2][2 * (q4 % 2) + 0] = pack_bf16x2(lo[0], lo[1]);
-        al[q4 / 2][2 * (q4 % 2) + 1] = pack_bf16x2(lo[2], lo[3]);
+        for (int i = 0; i < 4; ++i) w[i] = fast_exp2(sc[4 * q4 + i] * p.wscale_l2e - sh[i]);
+        const uint32_t h0 = pack_bf16x2(w[0], w[1]), h1 = pack_bf16x2(w[2], w[3]);
+        ah[q4 / 2][2 * (q4 % 2) + 0] = h0;
+        ah[q4 / 2][2 * (q4 % 2) + 1] = h1;
+        al[q4 / 2][2 * (q4 % 2) + 0] = pack_bf16x2(w[0] - __uint_as_float(h0 << 16), w[1] - __uint_as_float(h0 & 0xFFFF0000u));
+        al[q4 / 2][2 * (q4 % 2) + 1] = pack_bf16x2(w[2] - __uint_as_float(h1 << 16), w[3] - __uint_as_float(h1 & 0xFFFF0000u));
       }
       // state product over the step's 32 tokens, 16 per MFMA, in the token order the weights came in:
-      // entries 0-3 of a lane's operand are tokens 16 ks + 4 half + 0..3, entries 4-7 the same + 8
+      // entries 0-3 of a lane's operand are tokens 16 ks + 4 half + 0..3, entries 4-7 the same + 8.
+      // All hi products of a token group before its lo products: no product waits for its predecessor.
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks) {
         const bf16x8 vh = __builtin_bit_cast(bf16x8, ah[ks]), vl = __builtin_bit_cast(bf16x8, al[ks]);
+        bf16x8 bv[NJ];
 #pragma unroll
         for (int jt = 0; jt < NJ; ++jt) {
           const uint16_t* src = sWVt + (32 * jt + col) * LP + tok0 + 16 * ks + 4 * half;
           const uint2 b0 = *(const uint2*)src, b1 = *(const uint2*)(src + 8);
-          const bf16x8 bv = __builtin_bit_cast(bf16x8, (u32x4){b0.x, b0.y, b1.x, b1.y});
-          macc[jt] = mfma_bf16(vh, bv, macc[jt]);
-          macc[jt] = mfma_bf16(vl, bv, macc[jt]);
+          bv[jt] = __builtin_bit_cast(bf16x8, (u32x4){b0.x, b0.y, b1.x, b1.y});
         }
+#pragma unroll
+        for (int jt = 0; jt < NJ; ++jt) macc[jt] = mfma_bf16(vh, bv[jt], macc[jt]);
+#pragma unroll
+        for (int jt = 0; jt < NJ; ++jt) macc[jt] = mfma_bf16(vl, bv[jt], macc[jt]);
       }
     }
   }
-  if (live) {
+  __syncthreads();
 #pragma unroll
-    for (int jt = 0; jt < NJ; ++jt)
+  for (int jt = 0; jt < NJ; ++jt)
 #pragma unroll
-      for (int v = 0; v < 16; ++v)
-        mv[(size_t)(mslot + 8 * (v / 4) + 4 * half + (v % 4)) * D + 32 * jt + col] = bf16_bits(macc[jt][v]);
+    for (int v = 0; v < 16; ++v)
+      sStage[(mslot + 8 * (v / 4) + 4 * half + (v % 4)) * LD + 32 * jt + col] = bf16_bits(macc[jt][v]);
+  __syncthreads();
+  {
+    constexpr int CPR = D / 8;
+    const int ch = threadIdx.x % CPR;
+#pragma unroll
+    for (int r = threadIdx.x / CPR; r < 128; r += NT / CPR)
+      if (m0 + r < p.M) *(u32x4*)(mv + (size_t)r * D + 8 * ch) = *(const u32x4*)(sStage + r * LD + 8 * ch);
   }
 }
 
@@ -632,12 +632,13 @@ hipError_t launch_prefill_bf16(const PrefillParams& p0, hipStream_t s) {
   auto read = [&](uint32_t c_begin, uint32_t c_count) -> hipError_t {
     p.c_begin = c_begin;
     const dim3 g(c_count * p.G, units);
+    const dim3 rblock(512);
     if (p.has_write) {
-      if (d128) hipLaunchKernelGGL((prefill_read_kernel<128, true>), g, block, 0, s, p);
-      else hipLaunchKernelGGL((prefill_read_kernel<64, true>), g, block, 0, s, p);
+      if (d128) hipLaunchKernelGGL((prefill_read_kernel<128, true>), g, rblock, 0, s, p);
+      else hipLaunchKernelGGL((prefill_read_kernel<64, true>), g, rblock, 0, s, p);
     } else {
-      if (d128) hipLaunchKernelGGL((prefill_read_kernel<128, false>), g, block, 0, s, p);
-      else hipLaunchKernelGGL((prefill_read_kernel<64, false>), g, block, 0, s, p);
+      if (d128) hipLaunchKernelGGL((prefill_read_kernel<128, false>), g, rblock, 0, s, p);
+      else hipLaunchKernelGGL((prefill_read_kernel<64, false>), g, rblock, 0, s, p);
     }
     return hipGetLastError();
   };
