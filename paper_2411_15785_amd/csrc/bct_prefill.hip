@@ -165,44 +165,53 @@ __global__ __launch_bounds__(256) void prefill_transpose_kernel(const PrefillPar
 // row (token t, query head g) of a memory, the shift max + log2(sum of
 // exp2(score - max)) over all M slots, so that a weight is exp2(score - shift)
 // with no further multiplication (stored in .x of a float2; rows that do not
-// exist use kNoRow, which makes every weight zero).  One workgroup = 128 rows; it walks the keys 128 slots at
-// a time; wavefront w scores slots 32w..32w+31 of the tile against all rows.
+// exist use kNoRow, which makes every weight zero).  One workgroup = 128 rows;
+// it walks the keys 128 slots at a time; each of its eight wavefronts scores
+// 32 slots of the tile against 64 of the rows.
 template <int D>
-__global__ __launch_bounds__(256) void prefill_stats_kernel(const PrefillParams p) {
-  constexpr int LD = D + 8, KS = D / 16;
-  __shared__ __attribute__((aligned(16))) uint16_t sX[kTC * LD];
-  __shared__ __attribute__((aligned(16))) uint16_t sK[128 * LD];
+__global__ __launch_bounds__(512, 4) void prefill_stats_kernel(const PrefillParams p) {
+  constexpr int LD = D + 8, KS = D / 16, NT = 512;
+  // the query tile is only read into registers before the loop: the key tiles reuse its memory
+  __shared__ __attribute__((aligned(16))) uint16_t sTile[128 * LD];
   __shared__ float2 sRed[4][kTC];
+  uint16_t* const sX = sTile;
+  uint16_t* const sK = sTile;
 
   const uint32_t unit = blockIdx.y, b = unit / p.Hkv, h = unit % p.Hkv;
   const uint32_t nw = p.has_write ? p.T : 0u, nr = p.has_read ? p.T * p.G : 0u;
   const uint32_t row0 = blockIdx.x * kTC;
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64, col = lane % 32, half = lane / 32;
+  // wavefront = (32 slots sg of the key tile, 64 rows rh of the row tile)
+  const int sg = wave & 3, rh = wave >> 2;
 
-  rows_to_lds<D, kTC>(sX, LD, p.mk, [&](int r) -> const uint16_t* {
-    uint32_t row = row0 + r;
-    if (row < nw) return p.wq + (((size_t)b * p.T + row) * p.Hkv + h) * D;
-    row -= nw;
-    if (row < nr) return p.q + (((size_t)b * p.T + row / p.G) * p.Hq + h * p.G + row % p.G) * D;
-    return nullptr;
-  });
+  {
+    Tile<kTC, D, NT> t;
+    t.fetch_rows(p.mk, [&](int r) -> const uint16_t* {
+      uint32_t row = row0 + r;
+      if (row < nw) return p.wq + (((size_t)b * p.T + row) * p.Hkv + h) * D;
+      row -= nw;
+      if (row < nr) return p.q + (((size_t)b * p.T + row / p.G) * p.Hq + h * p.G + row % p.G) * D;
+      return nullptr;
+    });
+    t.put(sX, LD);
+  }
   const uint16_t* mk = p.mk + (size_t)(p.mk_per_seq ? unit : h) * p.M * D;
 
-  float scale[4], m[4], s[4];
+  float scale[2], m[2], s[2];
 #pragma unroll
-  for (int jt = 0; jt < 4; ++jt) {
-    scale[jt] = (row0 + 32 * jt + col < nw) ? p.wscale_l2e : p.rscale_l2e;
+  for (int jt = 0; jt < 2; ++jt) {
+    scale[jt] = (row0 + 64 * rh + 32 * jt + col < nw) ? p.wscale_l2e : p.rscale_l2e;
     m[jt] = kNegBig;
     s[jt] = 0.f;
   }
   // the query rows do not change over the loop: keep their operand fragments in registers
   __syncthreads();
-  bf16x8 xb[4][KS];
+  bf16x8 xb[2][KS];
 #pragma unroll
-  for (int jt = 0; jt < 4; ++jt)
+  for (int jt = 0; jt < 2; ++jt)
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) xb[jt][ks] = frag(sX, LD, 32 * jt + col, ks * 16 + half * 8);
-  Tile<128, D> tk;
+    for (int ks = 0; ks < KS; ++ks) xb[jt][ks] = frag(sX, LD, 64 * rh + 32 * jt + col, ks * 16 + half * 8);
+  Tile<128, D, NT> tk;
   auto fetch_keys = [&](uint32_t m0) {
     tk.fetch_rows(p.mk, [&](int r) -> const uint16_t* { return (m0 + r < p.M) ? mk + (size_t)(m0 + r) * D : nullptr; });
   };
@@ -212,18 +221,18 @@ __global__ __launch_bounds__(256) void prefill_stats_kernel(const PrefillParams 
     tk.put(sK, LD);
     if (m0 + 128 < p.M) fetch_keys(m0 + 128);  // in flight during this tile's products
     __syncthreads();
-    if (m0 + 32 * wave < p.M) {  // M is a multiple of 64: a wavefront's 32 slots are all in or all out
-      f32x16 acc[4];
+    if (m0 + 32 * sg < p.M) {  // M is a multiple of 64: a wavefront's 32 slots are all in or all out
+      f32x16 acc[2];
 #pragma unroll
-      for (int jt = 0; jt < 4; ++jt) acc[jt] = zero16();
+      for (int jt = 0; jt < 2; ++jt) acc[jt] = zero16();
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        const bf16x8 a = frag(sK, LD, 32 * wave + col, ks * 16 + half * 8);
+        const bf16x8 a = frag(sK, LD, 32 * sg + col, ks * 16 + half * 8);
 #pragma unroll
-        for (int jt = 0; jt < 4; ++jt) acc[jt] = mfma_bf16(a, xb[jt][ks], acc[jt]);
+        for (int jt = 0; jt < 2; ++jt) acc[jt] = mfma_bf16(a, xb[jt][ks], acc[jt]);
       }
 #pragma unroll
-      for (int jt = 0; jt < 4; ++jt) {
+      for (int jt = 0; jt < 2; ++jt) {
         float tmax = kNegBig;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
@@ -240,9 +249,9 @@ __global__ __launch_bounds__(256) void prefill_stats_kernel(const PrefillParams 
     }
   }
 #pragma unroll
-  for (int jt = 0; jt < 4; ++jt) {
+  for (int jt = 0; jt < 2; ++jt) {
     merge_stat(m[jt], s[jt], __shfl_xor(m[jt], 32, 64), __shfl_xor(s[jt], 32, 64));
-    if (half == 0) sRed[wave][32 * jt + col] = make_float2(m[jt], s[jt]);
+    if (half == 0) sRed[sg][64 * rh + 32 * jt + col] = make_float2(m[jt], s[jt]);
   }
   __syncthreads();
   if (threadIdx.x < kTC) {
@@ -625,8 +634,8 @@ hipError_t launch_prefill_bf16(const PrefillParams& p0, hipStream_t s) {
   if (p.has_read && (e = transpose(1)) != hipSuccess) return e;
 
   const dim3 gs((rows + kTC - 1) / kTC, units);
-  if (d128) hipLaunchKernelGGL(prefill_stats_kernel<128>, gs, block, 0, s, p);
-  else hipLaunchKernelGGL(prefill_stats_kernel<64>, gs, block, 0, s, p);
+  if (d128) hipLaunchKernelGGL(prefill_stats_kernel<128>, gs, dim3(512), 0, s, p);
+  else hipLaunchKernelGGL(prefill_stats_kernel<64>, gs, dim3(512), 0, s, p);
   if ((e = hipGetLastError()) != hipSuccess) return e;
 
   auto read = [&](uint32_t c_begin, uint32_t c_count) -> hipError_t {
