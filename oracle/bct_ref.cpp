@@ -174,7 +174,7 @@ inline size_t key_offset(const RefCache& c, uint32_t b, uint32_t h) {
 // offsets so that the same routine serves [B][H][d] and [B][T][H][d] inputs.
 void unit_decode_step(RefCache& c, uint32_t b, uint32_t h, const void* q, size_t q_off, size_t q_head_stride,
                       const void* wq, size_t wq_off, const void* wv, size_t wv_off, void* out, size_t out_off,
-                      size_t out_head_stride, double* w) {
+                      size_t out_head_stride, double* w, double eta = 1.0) {
   const uint32_t M = c.ds.M, d = c.ds.d, G = c.ds.Hq / c.ds.Hkv;
   const int dt = c.ds.dtype;
   const size_t koff = key_offset(c, b, h);
@@ -184,7 +184,7 @@ void unit_decode_step(RefCache& c, uint32_t b, uint32_t h, const void* q, size_t
   if (wq) {
     softmax_weights(c, wq, wq_off, koff, (double)c.ds.write_scale, w);
     for (uint32_t m = 0; m < M; ++m) {
-      const float wwm = (float)w[m];
+      const float wwm = (float)(eta * w[m]);   // the token's step size scales its write weights
       for (uint32_t j = 0; j < d; ++j) {
         const size_t i = voff + (size_t)m * d + j;
         const float upd = std::fmaf(wwm, load_elem_f(wv, wv_off + j, dt), load_elem_f(mv, i, dt));
@@ -206,8 +206,8 @@ void unit_decode_step(RefCache& c, uint32_t b, uint32_t h, const void* q, size_t
 
 // A chunk of T tokens for one (b, h) memory: the same recurrence, with MV held
 // in float for the whole chunk and rounded to the storage dtype once at the end.
-void unit_prefill(RefCache& c, uint32_t b, uint32_t h, const void* q, const void* wq, const void* wv, uint32_t T,
-                  void* out, double* w, float* shadow) {
+void unit_prefill(RefCache& c, uint32_t b, uint32_t h, const void* q, const void* wq, const void* wv,
+                  const float* gate, uint32_t T, void* out, double* w, float* shadow) {
   const uint32_t M = c.ds.M, d = c.ds.d, Hq = c.ds.Hq, Hkv = c.ds.Hkv, G = Hq / Hkv;
   const int dt = c.ds.dtype;
   const size_t koff = key_offset(c, b, h);
@@ -219,8 +219,9 @@ void unit_prefill(RefCache& c, uint32_t b, uint32_t h, const void* q, const void
     if (wq) {
       const size_t woff = (((size_t)b * T + t) * Hkv + h) * d;
       softmax_weights(c, wq, woff, koff, (double)c.ds.write_scale, w);
+      const double eta = gate ? (double)gate[((size_t)b * T + t) * Hkv + h] : 1.0;
       for (uint32_t m = 0; m < M; ++m) {
-        const float wwm = (float)w[m];
+        const float wwm = (float)(eta * w[m]);
         for (uint32_t j = 0; j < d; ++j)
           shadow[(size_t)m * d + j] = std::fmaf(wwm, load_elem_f(wv, woff + j, dt), shadow[(size_t)m * d + j]);
       }
@@ -318,8 +319,12 @@ int bct_ref_cache_steps(const bct_ref_cache* c, uint64_t* steps) {
 // q, out: [B][Hq][d]; wq (k_new), wv (v_new): [B][Hkv][d]; storage dtype.
 // wq == wv == NULL: read-only step.  q == out == NULL: write-only step
 // (Algorithm 1 alone).  Any other NULL mix is an error.  5 = keys not set.
-int bct_ref_decode_step(bct_ref_cache* c, const void* q, const void* wq, const void* wv, void* out) {
+// gate: NULL, or one step size per memory, float [B][Hkv] (the "learning rate adaptation" item of
+// section 3.5 read as a per-token scalar on the write: MV <- MV + eta * ww^T wv).  Needs a write.
+int bct_ref_decode_step_gated(bct_ref_cache* c, const void* q, const void* wq, const void* wv, const float* gate,
+                              void* out) {
   if (!c) return 1;
+  if (gate && !wq) return 1;
   if ((wq == nullptr) != (wv == nullptr)) return 1;
   if ((q == nullptr) != (out == nullptr)) return 1;
   if (!q && !wq) return 1;
@@ -334,16 +339,24 @@ int bct_ref_decode_step(bct_ref_cache* c, const void* q, const void* wq, const v
       const uint32_t b = (uint32_t)(u / Hkv), h = (uint32_t)(u % Hkv);
       const size_t kv_off = ((size_t)b * Hkv + h) * d;
       const size_t q_off = ((size_t)b * Hq + (size_t)h * G) * d;
-      unit_decode_step(*c, b, h, q, q_off, d, wq, kv_off, wv, kv_off, out, q_off, d, w.data());
+      unit_decode_step(*c, b, h, q, q_off, d, wq, kv_off, wv, kv_off, out, q_off, d, w.data(),
+                       gate ? (double)gate[(size_t)b * Hkv + h] : 1.0);
     }
   }
   c->steps += 1;
   return 0;
 }
 
+int bct_ref_decode_step(bct_ref_cache* c, const void* q, const void* wq, const void* wv, void* out) {
+  return bct_ref_decode_step_gated(c, q, wq, wv, nullptr, out);
+}
+
 // q, out: [B][T][Hq][d]; wq, wv: [B][T][Hkv][d].  Same NULL conventions.
-int bct_ref_prefill(bct_ref_cache* c, const void* q, const void* wq, const void* wv, uint32_t T, void* out) {
+// gate: NULL, or float [B][T][Hkv].
+int bct_ref_prefill_gated(bct_ref_cache* c, const void* q, const void* wq, const void* wv, const float* gate,
+                          uint32_t T, void* out) {
   if (!c || T == 0) return 1;
+  if (gate && !wq) return 1;
   if ((wq == nullptr) != (wv == nullptr)) return 1;
   if ((q == nullptr) != (out == nullptr)) return 1;
   if (!q && !wq) return 1;
@@ -357,11 +370,15 @@ int bct_ref_prefill(bct_ref_cache* c, const void* q, const void* wq, const void*
 #pragma omp for schedule(static)
     for (long u = 0; u < units; ++u) {
       const uint32_t b = (uint32_t)(u / Hkv), h = (uint32_t)(u % Hkv);
-      unit_prefill(*c, b, h, q, wq, wv, T, out, w.data(), shadow.data());
+      unit_prefill(*c, b, h, q, wq, wv, gate, T, out, w.data(), shadow.data());
     }
   }
   c->steps += T;
   return 0;
+}
+
+int bct_ref_prefill(bct_ref_cache* c, const void* q, const void* wq, const void* wv, uint32_t T, void* out) {
+  return bct_ref_prefill_gated(c, q, wq, wv, nullptr, T, out);
 }
 
 // Test probes: the softmax weights of one vector (d storage-dtype elements)

@@ -53,6 +53,8 @@ def lib():
         L.bct_ref_cache_steps.argtypes = [vp, ctypes.POINTER(ctypes.c_uint64)]
         L.bct_ref_decode_step.argtypes = [vp, vp, vp, vp, vp]
         L.bct_ref_prefill.argtypes = [vp, vp, vp, vp, ctypes.c_uint32, vp]
+        L.bct_ref_decode_step_gated.argtypes = [vp, vp, vp, vp, vp, vp]
+        L.bct_ref_prefill_gated.argtypes = [vp, vp, vp, vp, vp, ctypes.c_uint32, vp]
         L.bct_ref_probe_weights.argtypes = [vp, ctypes.c_uint32, ctypes.c_uint32, vp, ctypes.c_double, vp]
         L.bct_ref_round_bf16_from_float.argtypes = [ctypes.c_float]
         L.bct_ref_round_bf16_from_float.restype = ctypes.c_uint16
@@ -142,8 +144,15 @@ class RefCache:
         assert lib().bct_ref_cache_steps(self._h, ctypes.byref(st)) == 0
         return st.value
 
-    def decode_step(self, q, wq, wv):
-        """Returns out [B][Hq][d] (or None for a write-only step)."""
+    def _gate(self, gate, shape):
+        if gate is None:
+            return None
+        gate = np.ascontiguousarray(gate)
+        assert gate.dtype == np.float32 and gate.shape == tuple(shape), (gate.dtype, gate.shape, shape)
+        return gate
+
+    def decode_step(self, q, wq, wv, gate=None):
+        """Returns out [B][Hq][d] (or None for a write-only step).  gate: float32 [B][Hkv] step sizes."""
         out = None
         if q is not None:
             q = self._chk(q, (self.B, self.Hq, self.d))
@@ -152,7 +161,8 @@ class RefCache:
             wq = self._chk(wq, (self.B, self.Hkv, self.d))
         if wv is not None:
             wv = self._chk(wv, (self.B, self.Hkv, self.d))
-        rc = lib().bct_ref_decode_step(self._h, _ptr(q), _ptr(wq), _ptr(wv), _ptr(out))
+        gate = self._gate(gate, (self.B, self.Hkv))
+        rc = lib().bct_ref_decode_step_gated(self._h, _ptr(q), _ptr(wq), _ptr(wv), _ptr(gate), _ptr(out))
         if rc != 0:
             raise RuntimeError(f"bct_ref_decode_step failed ({rc})")
         return out
@@ -160,7 +170,7 @@ class RefCache:
     def decode_step_rc(self, q, wq, wv, out):
         return lib().bct_ref_decode_step(self._h, _ptr(q), _ptr(wq), _ptr(wv), _ptr(out))
 
-    def prefill(self, q, wq, wv, T):
+    def prefill(self, q, wq, wv, T, gate=None):
         out = None
         if q is not None:
             q = self._chk(q, (self.B, T, self.Hq, self.d))
@@ -169,7 +179,8 @@ class RefCache:
             wq = self._chk(wq, (self.B, T, self.Hkv, self.d))
         if wv is not None:
             wv = self._chk(wv, (self.B, T, self.Hkv, self.d))
-        rc = lib().bct_ref_prefill(self._h, _ptr(q), _ptr(wq), _ptr(wv), T, _ptr(out))
+        gate = self._gate(gate, (self.B, T, self.Hkv))
+        rc = lib().bct_ref_prefill_gated(self._h, _ptr(q), _ptr(wq), _ptr(wv), _ptr(gate), T, _ptr(out))
         if rc != 0:
             raise RuntimeError(f"bct_ref_prefill failed ({rc})")
         return out

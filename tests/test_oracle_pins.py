@@ -460,3 +460,58 @@ def test_bf16_rounding_against_grid_rounding_and_library_cast():
     assert bct_ref.round_bf16_from_double(tie) == 0x3F80                 # ties to even
     assert bct_ref.round_bf16_from_double(tie + 2.0 ** -40) == 0x3F81    # just above the tie
     assert bct_ref.round_bf16_from_double(tie - 2.0 ** -40) == 0x3F80
+
+
+# ------------------------------------------------------------------ P13 per-token step size (gate)
+# Section 3.5 names a step size "for each token" without an equation; the reading is
+# MV <- MV + eta_t * ww^T wv with one scalar per memory and token.  What fixes it: eta = 1 is
+# the ungated step, eta = 0 writes nothing, and a power-of-two eta is exactly a scaled wv.
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_p13_gate_one_is_the_plain_step_and_zero_writes_nothing(dtype):
+    M, B, Hq, Hkv, d = 16, 2, 4, 2, 8
+    c1, _, _ = make_cache(M, B, Hq, Hkv, d, dtype, mv0=True)
+    c2, _, _ = make_cache(M, B, Hq, Hkv, d, dtype, mv0=True)
+    c3, _, _ = make_cache(M, B, Hq, Hkv, d, dtype, mv0=True)
+    before = c3.values().copy()
+    for t in range(4):
+        q, wq, wv = step_inputs(c1, 6, t)
+        o1 = c1.decode_step(q, wq, wv)
+        o2 = c2.decode_step(q, wq, wv, gate=np.ones((B, Hkv), np.float32))
+        assert np.array_equal(o1, o2)
+        o3 = c3.decode_step(q, wq, wv, gate=np.zeros((B, Hkv), np.float32))
+        assert np.array_equal(c3.values(), before)                    # eta = 0: the state does not move
+        c4, _, _ = make_cache(M, B, Hq, Hkv, d, dtype, mv0=True)
+        assert np.array_equal(o3, c4.decode_step(q, None, None))      # and the read is a read-only step
+    assert np.array_equal(c1.values(), c2.values())
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_p13b_power_of_two_gate_is_a_scaled_write_value(dtype):
+    M, B, Hq, Hkv, d = 16, 2, 4, 2, 8
+    c1, _, _ = make_cache(M, B, Hq, Hkv, d, dtype, mv0=True)
+    c2, _, _ = make_cache(M, B, Hq, Hkv, d, dtype, mv0=True)
+    gate = np.array([[0.5, 2.0], [0.25, 1.0]], np.float32)             # one step size per (sequence, KV head)
+    for t in range(6):
+        q, wq, wv = step_inputs(c1, 6, t)
+        wv_scaled = syn.pack(f64(wv, dtype) * gate[:, :, None], dtype)   # exact: powers of two
+        o1 = c1.decode_step(q, wq, wv, gate=gate)
+        o2 = c2.decode_step(q, wq, wv_scaled)
+        assert np.array_equal(o1, o2)
+        assert np.array_equal(c1.values(), c2.values())
+
+
+def test_p13c_gated_prefill_equals_gated_steps_in_fp32():
+    M, B, Hq, Hkv, d, T = 16, 2, 4, 2, 8, 5
+    c1, _, _ = make_cache(M, B, Hq, Hkv, d, "f32", mv0=True)
+    c2, _, _ = make_cache(M, B, Hq, Hkv, d, "f32", mv0=True)
+    gate = (0.25 + np.abs(syn.normal(3, 9, 0, (B, T, Hkv)))).astype(np.float32)
+    steps = [step_inputs(c1, 6, t) for t in range(T)]
+    q, wq, wv = (np.ascontiguousarray(np.stack([s[i] for s in steps], axis=1)) for i in range(3))
+    out = c1.prefill(q, wq, wv, T, gate=gate)
+    for t in range(T):
+        o = c2.decode_step(steps[t][0], steps[t][1], steps[t][2], gate=np.ascontiguousarray(gate[:, t]))
+        assert np.array_equal(o, out[:, t])
+    assert np.array_equal(c1.values(), c2.values())
+    with pytest.raises(RuntimeError):
+        c1.decode_step(steps[0][0], None, None, gate=np.ones((B, Hkv), np.float32))   # a gate needs a write
