@@ -108,6 +108,17 @@ bct_status bct_decode_step(bct_cache* c, const void* q, const void* k_new, const
 bct_status bct_prefill(bct_cache* c, const void* q, const void* k_new, const void* v_new,
                        uint32_t T, void* out, void* hip_stream);
 
+/* The same two calls with a step size per token (section 3.5 lists a "learning rate adaptation" that
+ * sets the step size of each token, without an equation; taken here as one scalar eta_t per memory on
+ * the write: MV <- MV + eta_t * ww^T wv).  gate: DEVICE, float32, [B][n_kv_heads] for a decode step,
+ * [B][T][n_kv_heads] for a chunk; NULL = 1 everywhere = the plain call.  eta must be >= 0 (0 writes
+ * nothing); a negative or NaN eta gives NaN in that memory.  A gate without a write is
+ * BCT_ERR_INVALID_ARG.  The read is unchanged. */
+bct_status bct_decode_step_gated(bct_cache* c, const void* q, const void* k_new, const void* v_new,
+                                 const float* gate, void* out, void* hip_stream);
+bct_status bct_prefill_gated(bct_cache* c, const void* q, const void* k_new, const void* v_new,
+                             const float* gate, uint32_t T, void* out, void* hip_stream);
+
 /* Checkpoint: copies MK and/or MV out of / into the cache (device pointers,
  * either may be NULL) together with the step counter (host). */
 bct_status bct_cache_export(const bct_cache* c, void* mk_dst, void* mv_dst, uint64_t* steps,

@@ -27,7 +27,7 @@ BCT_MK_PER_SEQUENCE = 1
 
 EXPORTS = [
     "bct_cache_query", "bct_cache_init", "bct_cache_set_keys", "bct_cache_set_values",
-    "bct_decode_step", "bct_prefill", "bct_cache_export", "bct_cache_import", "bct_cache_steps",
+    "bct_decode_step", "bct_prefill", "bct_decode_step_gated", "bct_prefill_gated", "bct_cache_export", "bct_cache_import", "bct_cache_steps",
     "bct_cache_regions", "bct_cache_destroy", "bct_strerror", "bct_last_error", "bct_stream_copy",
     "bct_profile_enable", "bct_profile_read",
 ]
@@ -73,6 +73,8 @@ def lib() -> ctypes.CDLL:
     L.bct_cache_set_values.argtypes = [vp, vp, vp]
     L.bct_decode_step.argtypes = [vp, vp, vp, vp, vp, vp]
     L.bct_prefill.argtypes = [vp, vp, vp, vp, u32, vp, vp]
+    L.bct_decode_step_gated.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+    L.bct_prefill_gated.argtypes = [vp, vp, vp, vp, vp, u32, vp, vp]
     L.bct_cache_export.argtypes = [vp, vp, vp, ctypes.POINTER(u64), vp]
     L.bct_cache_import.argtypes = [vp, vp, vp, u64, vp]
     L.bct_cache_steps.argtypes = [vp, ctypes.POINTER(u64)]
@@ -219,21 +221,33 @@ class BctCache:
         self._check(mv0, self.values_shape, "mv0")
         self._call("bct_cache_set_values", _dptr(mv0))
 
-    def decode_step(self, q, k_new, v_new, out=None):
-        """One token per sequence; returns out [B][Hq][d] (None for a write-only step)."""
+    def _check_gate(self, gate, shape):
         torch = _torch()
+        if gate is not None and (gate.dtype != torch.float32 or tuple(gate.shape) != tuple(shape)
+                                 or not gate.is_contiguous() or gate.device != self.device):
+            raise ValueError(f"gate: expected contiguous float32 {tuple(shape)} on {self.device}")
+
+    def decode_step(self, q, k_new, v_new, out=None, gate=None):
+        """One token per sequence; returns out [B][Hq][d] (None for a write-only step).
+        gate: float32 [B][Hkv] step sizes of the write, or None."""
+        torch = _torch()
+        self._check_gate(gate, (self.B, self.Hkv))
         self._check(q, (self.B, self.Hq, self.d), "q")
         self._check(k_new, (self.B, self.Hkv, self.d), "k_new")
         self._check(v_new, (self.B, self.Hkv, self.d), "v_new")
         if q is not None and out is None:
             out = torch.empty_like(q)
         self._check(out, (self.B, self.Hq, self.d), "out")
-        self._call("bct_decode_step", _dptr(q), _dptr(k_new), _dptr(v_new), _dptr(out))
+        if gate is None:
+            self._call("bct_decode_step", _dptr(q), _dptr(k_new), _dptr(v_new), _dptr(out))
+        else:
+            self._call("bct_decode_step_gated", _dptr(q), _dptr(k_new), _dptr(v_new), _dptr(gate), _dptr(out))
         return out
 
-    def prefill(self, q, k_new, v_new, T, out=None):
-        """A chunk of T tokens per sequence; tensors are [B][T][H][d]."""
+    def prefill(self, q, k_new, v_new, T, out=None, gate=None):
+        """A chunk of T tokens per sequence; tensors are [B][T][H][d]; gate float32 [B][T][Hkv] or None."""
         torch = _torch()
+        self._check_gate(gate, (self.B, T, self.Hkv))
         self._check(q, (self.B, T, self.Hq, self.d), "q")
         self._check(k_new, (self.B, T, self.Hkv, self.d), "k_new")
         self._check(v_new, (self.B, T, self.Hkv, self.d), "v_new")
@@ -242,7 +256,11 @@ class BctCache:
         self._check(out, (self.B, T, self.Hq, self.d), "out")
         torch = _torch()
         with torch.cuda.device(self.device):
-            st = lib().bct_prefill(self._h, _dptr(q), _dptr(k_new), _dptr(v_new), T, _dptr(out), _stream_ptr())
+            if gate is None:
+                st = lib().bct_prefill(self._h, _dptr(q), _dptr(k_new), _dptr(v_new), T, _dptr(out), _stream_ptr())
+            else:
+                st = lib().bct_prefill_gated(self._h, _dptr(q), _dptr(k_new), _dptr(v_new), _dptr(gate), T,
+                                             _dptr(out), _stream_ptr())
         if st != BCT_OK:
             raise BctError(st, "bct_prefill")
         return out

@@ -151,7 +151,8 @@ bct_status check_io(const bct_cache* c, const void* q, const void* k_new, const 
 // The three launches of one decode step; q/kv batch strides allow a token of
 // a [B][T][H][d] chunk to be stepped in place.
 bct_status run_decode(bct_cache* c, const void* q, const void* k_new, const void* v_new, void* out,
-                      uint64_t q_bstride, uint64_t kv_bstride, hipStream_t s) {
+                      uint64_t q_bstride, uint64_t kv_bstride, const float* gate, uint64_t gate_bstride,
+                      hipStream_t s) {
   bct::DecodeParams p = c->plan;
   p.mk = c->mk;
   p.mv = c->mv;
@@ -168,6 +169,8 @@ bct_status run_decode(bct_cache* c, const void* q, const void* k_new, const void
   p.R = p.has_write + (p.has_read ? p.G : 0u);
   p.q_bstride = q_bstride;
   p.kv_bstride = kv_bstride;
+  p.gate = gate;
+  p.gate_bstride = gate_bstride;
   hipError_t e;
   hipEvent_t* ev = (c->prof_n < c->prof_cap) ? &c->prof_ev[(size_t)c->prof_n * 4] : nullptr;
   if (ev && (e = hipEventRecord(ev[0], s)) != hipSuccess) return hip_fail(e, "event record");
@@ -260,23 +263,32 @@ bct_status bct_cache_set_values(bct_cache* c, const void* mv0_dev, void* hip_str
   return BCT_OK;
 }
 
-bct_status bct_decode_step(bct_cache* c, const void* q, const void* k_new, const void* v_new, void* out,
-                           void* hip_stream) {
+bct_status bct_decode_step_gated(bct_cache* c, const void* q, const void* k_new, const void* v_new,
+                                 const float* gate, void* out, void* hip_stream) {
   bct_status st = check_io(c, q, k_new, v_new, out);
   if (st != BCT_OK) return st;
+  if (gate && !k_new) return fail(BCT_ERR_INVALID_ARG, "a gate needs a write (k_new, v_new)");
+  if (((uintptr_t)gate & 3u) != 0) return fail(BCT_ERR_MISALIGNED, "gate must be 4-byte aligned");
   st = run_decode(c, q, k_new, v_new, out, (uint64_t)c->desc.n_q_heads * c->desc.head_dim,
-                  (uint64_t)c->desc.n_kv_heads * c->desc.head_dim, (hipStream_t)hip_stream);
+                  (uint64_t)c->desc.n_kv_heads * c->desc.head_dim, gate, c->desc.n_kv_heads, (hipStream_t)hip_stream);
   if (st != BCT_OK) return st;
   c->steps += 1;
   return BCT_OK;
 }
 
-bct_status bct_prefill(bct_cache* c, const void* q, const void* k_new, const void* v_new, uint32_t T, void* out,
-                       void* hip_stream) {
+bct_status bct_decode_step(bct_cache* c, const void* q, const void* k_new, const void* v_new, void* out,
+                           void* hip_stream) {
+  return bct_decode_step_gated(c, q, k_new, v_new, nullptr, out, hip_stream);
+}
+
+bct_status bct_prefill_gated(bct_cache* c, const void* q, const void* k_new, const void* v_new, const float* gate,
+                             uint32_t T, void* out, void* hip_stream) {
   bct_status st = check_io(c, q, k_new, v_new, out);
   if (st != BCT_OK) return st;
   if (T == 0) return fail(BCT_ERR_INVALID_ARG, "T must be positive");
   if (T > c->max_T) return fail(BCT_ERR_BUFFER_TOO_SMALL, "T %u exceeds max_prefill_T %u given at init", T, c->max_T);
+  if (gate && !k_new) return fail(BCT_ERR_INVALID_ARG, "a gate needs a write (k_new, v_new)");
+  if (((uintptr_t)gate & 3u) != 0) return fail(BCT_ERR_MISALIGNED, "gate must be 4-byte aligned");
   const size_t sz = esize(c->desc.dtype);
   const uint64_t qs = (uint64_t)c->desc.n_q_heads * c->desc.head_dim;
   const uint64_t ks = (uint64_t)c->desc.n_kv_heads * c->desc.head_dim;
@@ -286,7 +298,8 @@ bct_status bct_prefill(bct_cache* c, const void* q, const void* k_new, const voi
     for (uint32_t t = 0; t < T; ++t) {
       st = run_decode(c, q ? (const char*)q + t * qs * sz : nullptr, k_new ? (const char*)k_new + t * ks * sz : nullptr,
                       v_new ? (const char*)v_new + t * ks * sz : nullptr, out ? (char*)out + t * qs * sz : nullptr,
-                      (uint64_t)T * qs, (uint64_t)T * ks, (hipStream_t)hip_stream);
+                      (uint64_t)T * qs, (uint64_t)T * ks, gate ? gate + (size_t)t * c->desc.n_kv_heads : nullptr,
+                      (uint64_t)T * c->desc.n_kv_heads, (hipStream_t)hip_stream);
       if (st != BCT_OK) return st;
     }
     c->steps += T;
@@ -300,6 +313,7 @@ bct_status bct_prefill(bct_cache* c, const void* q, const void* k_new, const voi
   pp.wq = (const uint16_t*)k_new;
   pp.wv = (const uint16_t*)v_new;
   pp.out = (uint16_t*)out;
+  pp.gate = gate;
   pp.norm_w = (float2*)(c->ws + c->off_pf_norm_w);
   pp.norm_r = (float2*)(c->ws + c->off_pf_norm_r);
   pp.snap = (uint16_t*)(c->ws + c->off_pf_snap);
@@ -320,6 +334,11 @@ bct_status bct_prefill(bct_cache* c, const void* q, const void* k_new, const voi
   if (e != hipSuccess) return hip_fail(e, "prefill launch");
   c->steps += T;
   return BCT_OK;
+}
+
+bct_status bct_prefill(bct_cache* c, const void* q, const void* k_new, const void* v_new, uint32_t T, void* out,
+                       void* hip_stream) {
+  return bct_prefill_gated(c, q, k_new, v_new, nullptr, T, out, hip_stream);
 }
 
 bct_status bct_cache_export(const bct_cache* c, void* mk_dst, void* mv_dst, uint64_t* steps, void* hip_stream) {

@@ -166,7 +166,9 @@ __global__ __launch_bounds__(64) void scores_mfma_bf16_kernel(const DecodeParams
 }
 
 // Softmax normalisers: one wavefront per (memory, row) merges the per-tile
-// (max, sum) pairs into the row's (max, 1 / sum of exp2(score - max)).
+// (max, sum) pairs into the row's (max, 1 / sum of exp2(score - max)).  A step
+// size, if given, multiplies the write row's 1 / sum: the MV pass then applies
+// eta * ww at no cost of its own.
 __global__ __launch_bounds__(256) void normalise_kernel(const DecodeParams p) {
   const uint32_t row = blockIdx.x * 4 + threadIdx.x / 64, lane = threadIdx.x % 64;
   if (row >= p.B * p.Hkv * p.R) return;
@@ -177,7 +179,14 @@ __global__ __launch_bounds__(256) void normalise_kernel(const DecodeParams p) {
   float sm = 0.f;
   for (uint32_t i = lane; i < p.n_tiles; i += 64) sm += st[i].y * fast_exp2(st[i].x - mx);
   sm = xor_sum<1, 32>(sm);
-  if (lane == 0) p.norm[row] = make_float2(mx, 1.0f / sm);
+  if (lane == 0) {
+    float inv = 1.0f / sm;
+    if (p.gate && p.has_write && row % p.R == 0) {  // row 0 of a memory is its write row
+      const uint32_t unit = row / p.R;
+      inv *= p.gate[(size_t)(unit / p.Hkv) * p.gate_bstride + unit % p.Hkv];
+    }
+    p.norm[row] = make_float2(mx, inv);
+  }
 }
 
 // out[b][hq][:] = round(sum over the S split-M partial outputs).  A workgroup

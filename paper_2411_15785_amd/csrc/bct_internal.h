@@ -38,6 +38,10 @@ struct DecodeParams {
   // strides (in elements) between consecutive batch entries of q/out and wq/wv;
   // [B][H][d] inputs use H*d, a token t of a [B][T][H][d] chunk uses T*H*d.
   uint64_t q_bstride, kv_bstride;
+  // optional step size per memory (section 3.5, learning-rate adaptation): eta of memory (b, h) at
+  // gate[b * gate_bstride + h]; null = 1.  Scales the write weights.
+  const float* gate;
+  uint64_t gate_bstride;
 };
 
 // One prefill chunk of a bf16 cache: everything its launches need.
@@ -57,6 +61,7 @@ struct PrefillParams {
   uint32_t has_write, has_read, mk_per_seq;
   float rscale_l2e, wscale_l2e;
   uint32_t c_begin;    // first sub-chunk of a read launch
+  const float* gate;   // [B][T][Hkv] step sizes (>= 0) or null
 };
 constexpr uint32_t kPrefillSubChunk = 128;
 hipError_t launch_prefill_bf16(const PrefillParams& p, hipStream_t s);

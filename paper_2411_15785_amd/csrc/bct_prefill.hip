@@ -260,7 +260,10 @@ __global__ __launch_bounds__(512, 4) void prefill_stats_kernel(const PrefillPara
     for (int w = 1; w < 4; ++w) merge_stat(mm, ss, sRed[w][threadIdx.x].x, sRed[w][threadIdx.x].y);
     uint32_t row = row0 + threadIdx.x;
     if (row < nw) {
-      p.norm_w[(size_t)unit * p.T + row] = make_float2(mm + __log2f(ss), 0.f);
+      // a step size eta >= 0 scales the token's write weights: exp2(score - shift) * eta
+      // = exp2(score - (shift - log2 eta)); eta = 0 gives shift = +inf and weights 0
+      const float le = p.gate ? __log2f(p.gate[((size_t)b * p.T + row) * p.Hkv + h]) : 0.f;
+      p.norm_w[(size_t)unit * p.T + row] = make_float2(mm + __log2f(ss) - le, 0.f);
     } else if (row - nw < nr) {
       p.norm_r[(size_t)unit * p.T * p.G + (row - nw)] = make_float2(mm + __log2f(ss), 0.f);
     }
