@@ -93,6 +93,12 @@ bct_status bct_cache_set_keys(bct_cache* c, const void* mk_dev, void* hip_stream
  * random values").  Does not touch steps. */
 bct_status bct_cache_set_values(bct_cache* c, const void* mv0_dev, void* hip_stream);
 
+/* MV := amplitude * u with u uniform on [-1, 1) (section 3.1 allows random initial contents and names
+ * no distribution).  Reproducible anywhere: element i of the flat [B][Hkv][M][d] array takes the
+ * (i + 1)-th output z of the splitmix64 generator started at seed, u = ((z >> 40) - 2^23) / 2^23,
+ * one fp32 multiplication by amplitude, one rounding to the storage dtype.  Does not touch steps. */
+bct_status bct_cache_randomize_values(bct_cache* c, uint64_t seed, float amplitude, void* hip_stream);
+
 /* One token per sequence (section 3.2 steps 2-5 for the write, then the read).
  *   k_new == v_new == NULL : read-only step, MV untouched.
  *   q == out == NULL       : write-only step = one iteration of Algorithm 1.
@@ -118,6 +124,16 @@ bct_status bct_decode_step_gated(bct_cache* c, const void* q, const void* k_new,
                                  const float* gate, void* out, void* hip_stream);
 bct_status bct_prefill_gated(bct_cache* c, const void* q, const void* k_new, const void* v_new,
                              const float* gate, uint32_t T, void* out, void* hip_stream);
+
+/* Session swap: copies sequence b's slice of the state, MV[b] = n_kv_heads * M * head_dim contiguous
+ * elements (device pointers), out of / into the cache; the memory of a sequence has a fixed size
+ * whatever its length (section 4.3), so parking a session is one constant-size copy.  mk_* must be
+ * NULL unless the keys are per sequence (then MK[b], same size).  The step counter is the cache's
+ * and is not touched. */
+bct_status bct_cache_export_sequence(const bct_cache* c, uint32_t b, void* mk_dst, void* mv_dst,
+                                     void* hip_stream);
+bct_status bct_cache_import_sequence(bct_cache* c, uint32_t b, const void* mk_src, const void* mv_src,
+                                     void* hip_stream);
 
 /* Checkpoint: copies MK and/or MV out of / into the cache (device pointers,
  * either may be NULL) together with the step counter (host). */

@@ -291,6 +291,56 @@ int bct_ref_cache_set_values(bct_ref_cache* c, const void* mv0) {
   return 0;
 }
 
+// MV := random values (section 3.1 allows "zero or random" initial contents; the distribution is not
+// given).  Element i (flat index of [B][Hkv][M][d]) is amplitude * u_i, u_i uniform on the 2^24-point
+// grid of [-1, 1): u_i = ((z_i >> 40) - 2^23) / 2^23 with z_i the (i + 1)-th output of the splitmix64
+// generator (Steele, Lea, Flood 2014) started at `seed`; the product is one fp32 multiplication,
+// then one rounding to the storage dtype.  Every step is exact or a single IEEE rounding, so another
+// implementation can reproduce the bits.
+uint64_t splitmix64_at(uint64_t seed, uint64_t n) {  // n-th output, n >= 1
+  uint64_t z = seed + n * 0x9E3779B97F4A7C15ull;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+
+int bct_ref_cache_randomize_values(bct_ref_cache* c, uint64_t seed, float amplitude) {
+  if (!c || !std::isfinite(amplitude)) return 1;
+  const size_t n = (size_t)c->ds.B * c->ds.Hkv * c->ds.M * c->ds.d;
+  for (size_t i = 0; i < n; ++i) {
+    const int32_t k = (int32_t)(splitmix64_at(seed, (uint64_t)i + 1) >> 40) - (1 << 23);
+    const float u = (float)k * (1.0f / 8388608.0f);
+    store_from_float(c->mv.data(), i, c->ds.dtype, u * amplitude);
+  }
+  return 0;
+}
+
+uint64_t bct_ref_splitmix64_at(uint64_t seed, uint64_t n) { return splitmix64_at(seed, n); }
+
+// One sequence's state, for swapping a session in and out: MV[b] is Hkv * M * d contiguous elements
+// (and MK[b] likewise when the keys are per sequence; mk may be NULL).
+int bct_ref_cache_export_sequence(const bct_ref_cache* c, uint32_t b, void* mk_dst, void* mv_dst) {
+  if (!c || b >= c->ds.B) return 1;
+  const size_t per = (size_t)c->ds.Hkv * c->ds.M * c->ds.d * esize(c->ds.dtype);
+  if (mv_dst) std::memcpy(mv_dst, c->mv.data() + (size_t)b * per, per);
+  if (mk_dst) {
+    if (!(c->ds.flags & REF_FLAG_MK_PER_SEQUENCE)) return 1;
+    std::memcpy(mk_dst, c->mk.data() + (size_t)b * per, per);
+  }
+  return 0;
+}
+
+int bct_ref_cache_import_sequence(bct_ref_cache* c, uint32_t b, const void* mk_src, const void* mv_src) {
+  if (!c || b >= c->ds.B) return 1;
+  const size_t per = (size_t)c->ds.Hkv * c->ds.M * c->ds.d * esize(c->ds.dtype);
+  if (mv_src) std::memcpy(c->mv.data() + (size_t)b * per, mv_src, per);
+  if (mk_src) {
+    if (!(c->ds.flags & REF_FLAG_MK_PER_SEQUENCE)) return 1;
+    std::memcpy(c->mk.data() + (size_t)b * per, mk_src, per);
+  }
+  return 0;
+}
+
 int bct_ref_cache_export(const bct_ref_cache* c, void* mk_dst, void* mv_dst, uint64_t* steps) {
   if (!c) return 1;
   if (mk_dst) std::memcpy(mk_dst, c->mk.data(), c->mk.size());

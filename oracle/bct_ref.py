@@ -53,6 +53,11 @@ def lib():
         L.bct_ref_cache_steps.argtypes = [vp, ctypes.POINTER(ctypes.c_uint64)]
         L.bct_ref_decode_step.argtypes = [vp, vp, vp, vp, vp]
         L.bct_ref_prefill.argtypes = [vp, vp, vp, vp, ctypes.c_uint32, vp]
+        L.bct_ref_cache_randomize_values.argtypes = [vp, ctypes.c_uint64, ctypes.c_float]
+        L.bct_ref_splitmix64_at.argtypes = [ctypes.c_uint64, ctypes.c_uint64]
+        L.bct_ref_splitmix64_at.restype = ctypes.c_uint64
+        L.bct_ref_cache_export_sequence.argtypes = [vp, ctypes.c_uint32, vp, vp]
+        L.bct_ref_cache_import_sequence.argtypes = [vp, ctypes.c_uint32, vp, vp]
         L.bct_ref_decode_step_gated.argtypes = [vp, vp, vp, vp, vp, vp]
         L.bct_ref_prefill_gated.argtypes = [vp, vp, vp, vp, vp, ctypes.c_uint32, vp]
         L.bct_ref_probe_weights.argtypes = [vp, ctypes.c_uint32, ctypes.c_uint32, vp, ctypes.c_double, vp]
@@ -120,6 +125,19 @@ class RefCache:
         if mv0 is not None:
             mv0 = self._chk(mv0, self.values_shape)
         assert lib().bct_ref_cache_set_values(self._h, _ptr(mv0)) == 0
+
+    def randomize_values(self, seed, amplitude):
+        assert lib().bct_ref_cache_randomize_values(self._h, seed, amplitude) == 0
+
+    def export_sequence(self, b):
+        """-> MV[b] as [Hkv][M][d]."""
+        mv = np.empty(self.values_shape[1:], dtype=self._np)
+        assert lib().bct_ref_cache_export_sequence(self._h, b, None, _ptr(mv)) == 0
+        return mv
+
+    def import_sequence(self, b, mv):
+        mv = self._chk(mv, self.values_shape[1:])
+        assert lib().bct_ref_cache_import_sequence(self._h, b, None, _ptr(mv)) == 0
 
     def export(self):
         mk = np.empty(self.keys_shape, dtype=self._np)
@@ -191,6 +209,10 @@ class RefCache:
         w = np.empty(self.M, dtype=np.float64)
         assert lib().bct_ref_probe_weights(self._h, b, h, _ptr(vec), scale, _ptr(w)) == 0
         return w
+
+
+def splitmix64_at(seed: int, n: int) -> int:
+    return lib().bct_ref_splitmix64_at(seed, n)
 
 
 def num_threads() -> int:

@@ -27,7 +27,8 @@ BCT_MK_PER_SEQUENCE = 1
 
 EXPORTS = [
     "bct_cache_query", "bct_cache_init", "bct_cache_set_keys", "bct_cache_set_values",
-    "bct_decode_step", "bct_prefill", "bct_decode_step_gated", "bct_prefill_gated", "bct_cache_export", "bct_cache_import", "bct_cache_steps",
+    "bct_decode_step", "bct_prefill", "bct_decode_step_gated", "bct_prefill_gated", "bct_cache_export",
+    "bct_cache_randomize_values", "bct_cache_export_sequence", "bct_cache_import_sequence", "bct_cache_import", "bct_cache_steps",
     "bct_cache_regions", "bct_cache_destroy", "bct_strerror", "bct_last_error", "bct_stream_copy",
     "bct_profile_enable", "bct_profile_read",
 ]
@@ -73,6 +74,9 @@ def lib() -> ctypes.CDLL:
     L.bct_cache_set_values.argtypes = [vp, vp, vp]
     L.bct_decode_step.argtypes = [vp, vp, vp, vp, vp, vp]
     L.bct_prefill.argtypes = [vp, vp, vp, vp, u32, vp, vp]
+    L.bct_cache_randomize_values.argtypes = [vp, u64, ctypes.c_float, vp]
+    L.bct_cache_export_sequence.argtypes = [vp, u32, vp, vp, vp]
+    L.bct_cache_import_sequence.argtypes = [vp, u32, vp, vp, vp]
     L.bct_decode_step_gated.argtypes = [vp, vp, vp, vp, vp, vp, vp]
     L.bct_prefill_gated.argtypes = [vp, vp, vp, vp, vp, u32, vp, vp]
     L.bct_cache_export.argtypes = [vp, vp, vp, ctypes.POINTER(u64), vp]
@@ -220,6 +224,22 @@ class BctCache:
     def set_values(self, mv0=None):
         self._check(mv0, self.values_shape, "mv0")
         self._call("bct_cache_set_values", _dptr(mv0))
+
+    def randomize_values(self, seed, amplitude):
+        self._call("bct_cache_randomize_values", ctypes.c_uint64(seed), ctypes.c_float(amplitude))
+
+    def export_sequence(self, b, with_keys=False):
+        """-> MV[b] [Hkv][M][d] (and MK[b] first if with_keys) as fresh tensors."""
+        torch = _torch()
+        mv = torch.empty(self.values_shape[1:], dtype=self.torch_dtype, device=self.device)
+        mk = torch.empty(self.values_shape[1:], dtype=self.torch_dtype, device=self.device) if with_keys else None
+        self._call("bct_cache_export_sequence", ctypes.c_uint32(b), _dptr(mk), _dptr(mv))
+        return (mk, mv) if with_keys else mv
+
+    def import_sequence(self, b, mv, mk=None):
+        self._check(mv, self.values_shape[1:], "mv")
+        self._check(mk, self.values_shape[1:], "mk")
+        self._call("bct_cache_import_sequence", ctypes.c_uint32(b), _dptr(mk), _dptr(mv))
 
     def _check_gate(self, gate, shape):
         torch = _torch()

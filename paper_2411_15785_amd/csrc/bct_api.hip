@@ -263,6 +263,47 @@ bct_status bct_cache_set_values(bct_cache* c, const void* mv0_dev, void* hip_str
   return BCT_OK;
 }
 
+bct_status bct_cache_randomize_values(bct_cache* c, uint64_t seed, float amplitude, void* hip_stream) {
+  if (!c) return fail(BCT_ERR_INVALID_ARG, "cache handle is NULL");
+  if (!(amplitude == amplitude) || amplitude - amplitude != 0.0f)
+    return fail(BCT_ERR_INVALID_ARG, "amplitude must be finite");
+  const hipError_t e = bct::launch_randomize(c->mv, c->mv_bytes, c->desc.dtype, seed, amplitude, (hipStream_t)hip_stream);
+  if (e != hipSuccess) return hip_fail(e, "randomising MV");
+  return BCT_OK;
+}
+
+// One sequence's slice of MV (and of MK when the keys are per sequence) is contiguous.
+static bct_status sequence_copy(bct_cache* c, uint32_t b, void* mk_ext, void* mv_ext, bool out, hipStream_t s) {
+  if (!c) return fail(BCT_ERR_INVALID_ARG, "cache handle is NULL");
+  if (b >= c->desc.batch) return fail(BCT_ERR_INVALID_ARG, "sequence %u of a batch of %u", b, c->desc.batch);
+  if (!mk_ext && !mv_ext) return fail(BCT_ERR_INVALID_ARG, "nothing to copy");
+  if (mk_ext && !(c->desc.flags & BCT_MK_PER_SEQUENCE))
+    return fail(BCT_ERR_INVALID_ARG, "the keys are shared by the batch: there is no per-sequence MK");
+  if (!aligned16(mk_ext) || !aligned16(mv_ext)) return fail(BCT_ERR_MISALIGNED, "buffers must be 16-byte aligned");
+  const size_t per = c->mv_bytes / c->desc.batch;
+  hipError_t e;
+  if (mv_ext) {
+    char* in = (char*)c->mv + (size_t)b * per;
+    if ((e = out ? bct::launch_copy(mv_ext, in, per, s) : bct::launch_copy(in, mv_ext, per, s)) != hipSuccess)
+      return hip_fail(e, "copying a sequence's MV");
+  }
+  if (mk_ext) {
+    char* in = (char*)c->mk + (size_t)b * per;
+    if ((e = out ? bct::launch_copy(mk_ext, in, per, s) : bct::launch_copy(in, mk_ext, per, s)) != hipSuccess)
+      return hip_fail(e, "copying a sequence's MK");
+  }
+  return BCT_OK;
+}
+
+bct_status bct_cache_export_sequence(const bct_cache* c, uint32_t b, void* mk_dst, void* mv_dst, void* hip_stream) {
+  return sequence_copy(const_cast<bct_cache*>(c), b, mk_dst, mv_dst, true, (hipStream_t)hip_stream);
+}
+
+bct_status bct_cache_import_sequence(bct_cache* c, uint32_t b, const void* mk_src, const void* mv_src,
+                                     void* hip_stream) {
+  return sequence_copy(c, b, const_cast<void*>(mk_src), const_cast<void*>(mv_src), false, (hipStream_t)hip_stream);
+}
+
 bct_status bct_decode_step_gated(bct_cache* c, const void* q, const void* k_new, const void* v_new,
                                  const float* gate, void* out, void* hip_stream) {
   bct_status st = check_io(c, q, k_new, v_new, out);

@@ -235,6 +235,28 @@ __global__ __launch_bounds__(256) void copy_kernel(u32x4* dst, const u32x4* src,
     __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 
+// MV := amplitude * u, u uniform on the 2^24-point grid of [-1, 1): element i of the flat array takes
+// the (i + 1)-th output of the splitmix64 generator started at `seed` (counter-based, so any thread
+// can produce any element), its top 24 bits as a signed grid index.  Integer steps are exact, the
+// two floating-point steps are single IEEE roundings: the values do not depend on the machine.
+template <typename DT>
+__global__ __launch_bounds__(256) void randomize_kernel(u32x4* dst, size_t n_vec, uint64_t seed, float amplitude) {
+  constexpr int E = DT::kElemsPerVec;
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n_vec; i += stride) {
+    float f[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+      uint64_t z = seed + (uint64_t)(i * E + e + 1) * 0x9E3779B97F4A7C15ull;
+      z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+      z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+      z ^= z >> 31;
+      f[e] = (float)((int32_t)(z >> 40) - (1 << 23)) * (1.0f / 8388608.0f) * amplitude;
+    }
+    dst[i] = pack16_round<DT>(f);
+  }
+}
+
 // ------------------------------------------------------------------ host side
 
 static bool use_mfma_scores(const DecodeParams& p, int dtype) { return dtype == 1 && !p.mk_per_seq; }
@@ -317,6 +339,18 @@ hipError_t launch_fill_zero(void* dst, size_t n_bytes, hipStream_t s) {
   const size_t n_vec = n_bytes / 16;
   if (n_vec == 0) return hipSuccess;
   hipLaunchKernelGGL(fill_zero_kernel, dim3(grid_for(n_vec)), dim3(256), 0, s, (u32x4*)dst, n_vec);
+  return hipGetLastError();
+}
+
+hipError_t launch_randomize(void* dst, size_t n_bytes, int dtype, uint64_t seed, float amplitude, hipStream_t s) {
+  const size_t n_vec = n_bytes / 16;
+  if (n_vec == 0) return hipSuccess;
+  if (dtype == 0)
+    hipLaunchKernelGGL((randomize_kernel<F32>), dim3(grid_for(n_vec)), dim3(256), 0, s, (u32x4*)dst, n_vec, seed,
+                       amplitude);
+  else
+    hipLaunchKernelGGL((randomize_kernel<BF16>), dim3(grid_for(n_vec)), dim3(256), 0, s, (u32x4*)dst, n_vec, seed,
+                       amplitude);
   return hipGetLastError();
 }
 

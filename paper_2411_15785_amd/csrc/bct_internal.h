@@ -73,6 +73,7 @@ hipError_t launch_stream(const DecodeParams& p, int dtype, hipStream_t s);
 hipError_t launch_merge(const DecodeParams& p, int dtype, hipStream_t s);
 hipError_t launch_fill_zero(void* dst, size_t n_bytes, hipStream_t s);
 hipError_t launch_copy(void* dst, const void* src, size_t n_bytes, hipStream_t s);
+hipError_t launch_randomize(void* dst, size_t n_bytes, int dtype, uint64_t seed, float amplitude, hipStream_t s);
 
 // Chooses stat_tile / n_tiles (scores pass) and the MV pass shape (mv_bs, mv_u, S).
 void plan_decode(DecodeParams& p, int dtype);

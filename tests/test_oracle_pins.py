@@ -515,3 +515,53 @@ def test_p13c_gated_prefill_equals_gated_steps_in_fp32():
     assert np.array_equal(c1.values(), c2.values())
     with pytest.raises(RuntimeError):
         c1.decode_step(steps[0][0], None, None, gate=np.ones((B, Hkv), np.float32))   # a gate needs a write
+
+
+# ------------------------------------------------------------------ P14 random initial MV, session swap
+
+def test_p14_generator_matches_the_published_splitmix64_vectors():
+    # first outputs of splitmix64 started at 0, as printed with the reference implementation
+    want = [0xE220A8397B1DCDAF, 0x6E789E6AA1B965F4, 0x06C45D188009454F, 0xF88BB8A8724C81EC]
+    assert [bct_ref.splitmix64_at(0, n) for n in (1, 2, 3, 4)] == want
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_p14b_random_values_are_the_documented_grid_points(dtype):
+    c, _, _ = make_cache(8, 2, 2, 2, 4, dtype)
+    amp = 0.75
+    c.randomize_values(12345, amp)
+    got = f64(c.values(), dtype).reshape(-1)
+    # element i from the (i + 1)-th generator output, written out with Python integers
+    def out(n):
+        z = (12345 + n * 0x9E3779B97F4A7C15) & (2 ** 64 - 1)
+        z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & (2 ** 64 - 1)
+        z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & (2 ** 64 - 1)
+        return z ^ (z >> 31)
+    u = np.array([((out(i + 1) >> 40) - 2 ** 23) / 2.0 ** 23 for i in range(got.size)])
+    want = f64(syn.pack((u.astype(np.float32) * np.float32(amp)).astype(np.float64), dtype), dtype)
+    assert np.array_equal(got, want)
+    assert np.all(np.abs(got) <= amp) and abs(got.mean()) < 0.15 and got.std() > 0.3 * amp
+    c.randomize_values(12346, amp)
+    assert not np.array_equal(f64(c.values(), dtype).reshape(-1), got)      # the seed matters
+
+
+def test_p14c_sequence_export_import_moves_exactly_one_sequence():
+    c, _, mv0 = make_cache(8, 3, 2, 2, 4, "bf16", mv0=True)
+    one = c.export_sequence(1)
+    assert np.array_equal(one, mv0[1])
+    new = rng_normal(5, syn.TID_MV0, 1, one.shape, "bf16")
+    c.import_sequence(1, new)
+    after = c.values()
+    assert np.array_equal(after[1], new) and np.array_equal(after[0], mv0[0]) and np.array_equal(after[2], mv0[2])
+    # a swapped-out session continues exactly where it stopped: run two steps, swap sequence 0 out and in
+    a, _, _ = make_cache(8, 3, 2, 2, 4, "bf16", mv0=True)
+    b, _, _ = make_cache(8, 3, 2, 2, 4, "bf16", mv0=True)
+    for t in range(2):
+        q, wq, wv = step_inputs(a, 6, t)
+        a.decode_step(q, wq, wv), b.decode_step(q, wq, wv)
+    saved = b.export_sequence(0)
+    b.import_sequence(0, rng_normal(7, syn.TID_MV0, 2, saved.shape, "bf16"))   # another session uses the slot
+    b.import_sequence(0, saved)
+    q, wq, wv = step_inputs(a, 6, 2)
+    assert np.array_equal(a.decode_step(q, wq, wv), b.decode_step(q, wq, wv))
+    assert np.array_equal(a.values(), b.values())
