@@ -52,7 +52,12 @@ typedef enum {
 
 typedef enum { BCT_F32 = 0, BCT_BF16 = 1 } bct_dtype;
 
-enum { BCT_MK_PER_SEQUENCE = 1u }; /* desc.flags: one key table per batch element */
+enum {
+  BCT_MK_PER_SEQUENCE = 1u, /* desc.flags: one key table per batch element */
+  BCT_STEP_STREAMING = 2u   /* desc.flags: always take the four-launch decode step, also for a cache small
+                             * enough for the one-launch step (same results to the stated tolerances;
+                             * for comparing the two) */
+};
 
 typedef struct {
   uint32_t capacity_M;  /* M > 0, multiple of 64, at most 65536                        */
@@ -63,7 +68,7 @@ typedef struct {
   int32_t  dtype;       /* bct_dtype: storage and I/O type of MK, MV, q, k_new, v_new, out */
   float    read_scale;  /* multiplies q . MK^T, e.g. 1/sqrt(d)                         */
   float    write_scale; /* multiplies wq . MK^T; 1.0 = Algorithm 1 as printed          */
-  uint32_t flags;       /* 0 or BCT_MK_PER_SEQUENCE                                    */
+  uint32_t flags;       /* 0 or an OR of the flags above                               */
 } bct_cache_desc;
 
 typedef struct bct_cache bct_cache; /* opaque, host memory */

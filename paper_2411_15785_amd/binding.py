@@ -24,6 +24,7 @@ BCT_ERR_HIP = 6
 BCT_F32 = 0
 BCT_BF16 = 1
 BCT_MK_PER_SEQUENCE = 1
+BCT_STEP_STREAMING = 2
 
 EXPORTS = [
     "bct_cache_query", "bct_cache_init", "bct_cache_set_keys", "bct_cache_set_values",

@@ -67,7 +67,7 @@ bct_status check_desc(const bct_cache_desc* d) {
   if (d->n_q_heads / d->n_kv_heads > bct::kMaxG)
     return fail(BCT_ERR_UNSUPPORTED, "n_q_heads / n_kv_heads = %u (at most %u)", d->n_q_heads / d->n_kv_heads,
                 bct::kMaxG);
-  if (d->flags & ~(uint32_t)BCT_MK_PER_SEQUENCE) return fail(BCT_ERR_UNSUPPORTED, "unknown flags 0x%x", d->flags);
+  if (d->flags & ~(uint32_t)(BCT_MK_PER_SEQUENCE | BCT_STEP_STREAMING)) return fail(BCT_ERR_UNSUPPORTED, "unknown flags 0x%x", d->flags);
   if ((uint64_t)d->batch * d->n_kv_heads > 65535u)
     return fail(BCT_ERR_UNSUPPORTED, "batch * n_kv_heads = %llu (at most 65535)",
                 (unsigned long long)d->batch * d->n_kv_heads);
@@ -96,6 +96,7 @@ void fill_plan(const bct_cache_desc* d, bct::DecodeParams& p) {
   p.R = 1 + p.G;
   p.has_write = p.has_read = 1;
   bct::plan_decode(p, d->dtype);
+  if (d->flags & BCT_STEP_STREAMING) p.fused = 0u;
 }
 
 Sizes compute_sizes(const bct_cache_desc* d, uint32_t max_T) {
@@ -174,12 +175,19 @@ bct_status run_decode(bct_cache* c, const void* q, const void* k_new, const void
   hipError_t e;
   hipEvent_t* ev = (c->prof_n < c->prof_cap) ? &c->prof_ev[(size_t)c->prof_n * 4] : nullptr;
   if (ev && (e = hipEventRecord(ev[0], s)) != hipSuccess) return hip_fail(e, "event record");
-  if ((e = bct::launch_scores(p, c->desc.dtype, s)) != hipSuccess) return hip_fail(e, "scores launch");
-  if ((e = bct::launch_normalise(p, s)) != hipSuccess) return hip_fail(e, "normaliser launch");
-  if (ev && (e = hipEventRecord(ev[1], s)) != hipSuccess) return hip_fail(e, "event record");
-  if ((e = bct::launch_stream(p, c->desc.dtype, s)) != hipSuccess) return hip_fail(e, "MV pass launch");
-  if (ev && (e = hipEventRecord(ev[2], s)) != hipSuccess) return hip_fail(e, "event record");
-  if ((e = bct::launch_merge(p, c->desc.dtype, s)) != hipSuccess) return hip_fail(e, "merge launch");
+  if (p.fused) {
+    // a small cache: the whole step in one launch (timed as the MV pass)
+    if (ev && (e = hipEventRecord(ev[1], s)) != hipSuccess) return hip_fail(e, "event record");
+    if ((e = bct::launch_fused(p, c->desc.dtype, s)) != hipSuccess) return hip_fail(e, "fused step launch");
+    if (ev && (e = hipEventRecord(ev[2], s)) != hipSuccess) return hip_fail(e, "event record");
+  } else {
+    if ((e = bct::launch_scores(p, c->desc.dtype, s)) != hipSuccess) return hip_fail(e, "scores launch");
+    if ((e = bct::launch_normalise(p, s)) != hipSuccess) return hip_fail(e, "normaliser launch");
+    if (ev && (e = hipEventRecord(ev[1], s)) != hipSuccess) return hip_fail(e, "event record");
+    if ((e = bct::launch_stream(p, c->desc.dtype, s)) != hipSuccess) return hip_fail(e, "MV pass launch");
+    if (ev && (e = hipEventRecord(ev[2], s)) != hipSuccess) return hip_fail(e, "event record");
+    if ((e = bct::launch_merge(p, c->desc.dtype, s)) != hipSuccess) return hip_fail(e, "merge launch");
+  }
   if (ev) {
     if ((e = hipEventRecord(ev[3], s)) != hipSuccess) return hip_fail(e, "event record");
     c->prof_n += 1;

@@ -275,6 +275,7 @@ void plan_decode(DecodeParams& p, int dtype) {
   }
   p.n_tiles = p.M / p.stat_tile;
   plan_mv_pass(p, dtype);
+  p.fused = (p.M <= kFusedMaxM && (uint64_t)p.B * p.Hkv <= kFusedMaxUnits) ? 1u : 0u;
 }
 
 template <int D, int NT>

@@ -12,6 +12,14 @@ namespace bct {
 constexpr uint32_t kMaxG = 8;          // query heads per KV head
 constexpr uint32_t kMaxRows = 1 + kMaxG;  // score rows per memory: write + G reads
 constexpr uint32_t kMinStatTile = 32;  // smallest slot tile with its own (max, sum) partial
+// A cache this small is stepped by one launch, one workgroup per memory: up to this many
+// slots and this many memories (one resident round of workgroups).  Measured inside a HIP graph
+// (bf16 d = 128 / fp32 d = 64, 4 to 512 memories): M = 64: 6.5-7.9 us against 7.0-10.9 us for
+// the four launches, M = 128: equal or better, M = 256: 15-21 us against 9-23 us (a single
+// workgroup has too few loads in flight to stream a larger memory), so the limit is 128.
+// Launched eagerly the one launch also saves three launch overheads (config 1: 11 us against 25).
+constexpr uint32_t kFusedMaxM = 128;
+constexpr uint32_t kFusedMaxUnits = 512;
 
 // One decode step of one layer: everything its launches need.
 struct DecodeParams {
@@ -34,6 +42,7 @@ struct DecodeParams {
   uint32_t S;          // split-M factor of the MV pass: workgroups per memory
   uint32_t mv_bs;      // threads per workgroup of the MV pass
   uint32_t mv_u;       // 16-byte loads per lane of the MV pass
+  uint32_t fused;      // 1: the whole step is one launch of decode_fused_kernel
   float rscale_l2e, wscale_l2e;  // scale * log2(e)
   // strides (in elements) between consecutive batch entries of q/out and wq/wv;
   // [B][H][d] inputs use H*d, a token t of a [B][T][H][d] chunk uses T*H*d.
@@ -71,6 +80,7 @@ hipError_t launch_scores(const DecodeParams& p, int dtype, hipStream_t s);
 hipError_t launch_normalise(const DecodeParams& p, hipStream_t s);
 hipError_t launch_stream(const DecodeParams& p, int dtype, hipStream_t s);
 hipError_t launch_merge(const DecodeParams& p, int dtype, hipStream_t s);
+hipError_t launch_fused(const DecodeParams& p, int dtype, hipStream_t s);
 hipError_t launch_fill_zero(void* dst, size_t n_bytes, hipStream_t s);
 hipError_t launch_copy(void* dst, const void* src, size_t n_bytes, hipStream_t s);
 hipError_t launch_randomize(void* dst, size_t n_bytes, int dtype, uint64_t seed, float amplitude, hipStream_t s);

@@ -64,7 +64,7 @@ def make_pair(w, ref_cls, gpu_cls, *, flags=0, read_scale=None, write_scale=None
     if mv0:
         g.set_values(to_dev(mv, w.dtype))
     bs = list(range(w.B)) if batch_subset is None else list(batch_subset)
-    r = ref_cls(w.M, len(bs), w.Hq, w.Hkv, w.d, w.dtype, rs, ws, flags)
+    r = ref_cls(w.M, len(bs), w.Hq, w.Hkv, w.d, w.dtype, rs, ws, flags & 1)   # bit 1 is a GPU-side choice of path
     r.set_keys(np.ascontiguousarray(mk[bs]) if per_seq else mk)
     if mv0:
         r.set_values(np.ascontiguousarray(mv[bs]))

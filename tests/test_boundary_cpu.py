@@ -111,6 +111,7 @@ def test_query_sizes_are_exact_and_constant(L):
     (dict(head_dim=96), P.BCT_ERR_UNSUPPORTED),
     (dict(dtype=7), P.BCT_ERR_UNSUPPORTED),
     (dict(flags=8), P.BCT_ERR_UNSUPPORTED),
+    (dict(flags=4), P.BCT_ERR_UNSUPPORTED),
     (dict(n_q_heads=32, n_kv_heads=2), P.BCT_ERR_UNSUPPORTED),   # 16 query heads per KV head
 ])
 def test_bad_descriptors_are_rejected(L, kw, status):

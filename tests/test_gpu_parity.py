@@ -110,13 +110,24 @@ SMALL = [
     ("bf16_m65536", 1, 1, 1, 128, 65536, "bf16"),       # the largest capacity the library accepts
     ("f32_d128_m65536", 1, 1, 1, 128, 65536, "f32"),
     ("bf16_gqa8_m4160", 1, 8, 1, 128, 4160, "bf16"),    # 8 query heads per KV head, 65 chunks of 64
+    # Caches of at most 128 slots and 512 memories take the one-launch step, all others the four-launch
+    # step (flags = 2 forces the latter): these are cases on both sides of the two limits
+    ("f32_d64_units640", 40, 16, 16, 64, 128, "f32"),
+    ("bf16_d128_gqa2_units576", 36, 32, 16, 128, 192, "bf16"),
+    ("bf16_d64_units1024", 64, 16, 16, 64, 64, "bf16"),
+    ("f32_d128_gqa4_units520", 130, 16, 4, 128, 64, "f32"),
+    ("bf16_m128_units512", 16, 32, 32, 128, 128, "bf16"),     # the largest cache of the one-launch step
+    ("f32_gqa8_m128", 1, 8, 1, 128, 128, "f32"),
+    ("bf16_gqa4_m128_d64", 3, 8, 2, 64, 128, "bf16"),
 ]
 
 
 @pytest.mark.parametrize("name,B,Hq,Hkv,d,M,dtype", SMALL)
 @pytest.mark.parametrize("mode", ["rw", "write_only", "read_only"])
-@pytest.mark.parametrize("flags", [0, 1])
+@pytest.mark.parametrize("flags", [0, 1, 2])
 def test_one_step_from_common_state(P, R, name, B, Hq, Hkv, d, M, dtype, mode, flags):
+    if flags == 2 and M > 128:
+        pytest.skip("flag 2 (always the four-launch step) changes nothing for a cache this large")
     w = syn.Workload(name, 1, B, Hq, Hkv, d, M, dtype, 4)
     ref, gpu, mk, mv0, bs = make_pair(w, R.RefCache, P.BctCache, flags=flags, mv0=True)
     for t in range(3):
@@ -126,7 +137,8 @@ def test_one_step_from_common_state(P, R, name, B, Hq, Hkv, d, M, dtype, mode, f
         if mode == "read_only":
             wq = wv = None
         # resynchronise: both sides start the step from the oracle's state
-        gpu.set_values(to_dev(ref.values(), dtype))
+        before = ref.values()
+        gpu.set_values(to_dev(before, dtype))
         o_ref = ref.decode_step(q, wq, wv)
         o_gpu = gpu.decode_step(to_dev(q, dtype), to_dev(wq, dtype), to_dev(wv, dtype))
         if mode != "write_only":
@@ -138,7 +150,7 @@ def test_one_step_from_common_state(P, R, name, B, Hq, Hkv, d, M, dtype, mode, f
         if mode == "read_only":
             assert np.array_equal(to_np(mv_g, dtype), ref.values())   # untouched, bit for bit
         else:
-            check_state_one_step(to_np(mv_g, dtype), ref.values(), dtype, f"{name}/{mode} step {t}")
+            check_state_one_step(to_np(mv_g, dtype), ref.values(), dtype, f"{name}/{mode} step {t}", before=before)
         assert st == t + 1
 
 
