@@ -122,12 +122,14 @@ SMALL = [
 ]
 
 
-@pytest.mark.parametrize("name,B,Hq,Hkv,d,M,dtype", SMALL)
+# flags: 0 shared keys, 1 per-sequence keys, 2 always the four-launch step (a different path only for
+# caches small enough for the one-launch step)
+SMALL_FLAGS = [c + (f,) for c in SMALL for f in (0, 1, 2) if f < 2 or (c[5] <= 128 and c[1] * c[3] <= 512)]
+
+
+@pytest.mark.parametrize("name,B,Hq,Hkv,d,M,dtype,flags", SMALL_FLAGS)
 @pytest.mark.parametrize("mode", ["rw", "write_only", "read_only"])
-@pytest.mark.parametrize("flags", [0, 1, 2])
 def test_one_step_from_common_state(P, R, name, B, Hq, Hkv, d, M, dtype, mode, flags):
-    if flags == 2 and M > 128:
-        pytest.skip("flag 2 (always the four-launch step) changes nothing for a cache this large")
     w = syn.Workload(name, 1, B, Hq, Hkv, d, M, dtype, 4)
     ref, gpu, mk, mv0, bs = make_pair(w, R.RefCache, P.BctCache, flags=flags, mv0=True)
     for t in range(3):
