@@ -7,8 +7,9 @@
 //               slot tile.  (section 3.2 step 2 / Algorithm 1 "score"; the same
 //               pass serves the read.)
 //   2. normalise : merges the (max, sum) pairs into each row's softmax
-//               normaliser (a few microseconds; it keeps that dependent chain
-//               out of every workgroup of the next launch).
+//               normaliser.  Only for memories with more than 64 slot tiles:
+//               up to 64 pairs are one per lane, and every workgroup of the MV
+//               pass merges them itself while its loads are in flight.
 //   3. MV pass : ONE pass over MV: load, ww[m] * wv + MV (one fp32 FMA),
 //               round to storage, store, and accumulate the read output from
 //               the value just stored.  (section 3.2 steps 2, 4, 5; section 3.4
@@ -314,6 +315,7 @@ hipError_t launch_scores(const DecodeParams& p, int dtype, hipStream_t s) {
 }
 
 hipError_t launch_normalise(const DecodeParams& p, hipStream_t s) {
+  if (p.fuse_norm) return hipSuccess;  // the MV pass does it
   const uint32_t rows = p.B * p.Hkv * p.R;
   hipLaunchKernelGGL(normalise_kernel, dim3((rows + 3) / 4), dim3(256), 0, s, p);
   return hipGetLastError();

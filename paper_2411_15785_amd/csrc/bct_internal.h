@@ -43,6 +43,7 @@ struct DecodeParams {
   uint32_t mv_bs;      // threads per workgroup of the MV pass
   uint32_t mv_u;       // 16-byte loads per lane of the MV pass
   uint32_t fused;      // 1: the whole step is one launch of decode_fused_kernel
+  uint32_t fuse_norm;  // 1: the MV pass merges the per-tile statistics itself, no normaliser launch
   float rscale_l2e, wscale_l2e;  // scale * log2(e)
   // strides (in elements) between consecutive batch entries of q/out and wq/wv;
   // [B][H][d] inputs use H*d, a token t of a [B][T][H][d] chunk uses T*H*d.

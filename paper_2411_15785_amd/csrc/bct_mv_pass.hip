@@ -43,7 +43,10 @@ __device__ __forceinline__ void load_run(const float* p, float* w) {
   }
 }
 
-template <typename DT, int D, int GT, bool WRITE, bool READ, int BS, int U>
+// NORM: the workgroup merges the per-tile (max, sum) pairs of its memory's rows itself (at most 64
+// tiles: one per lane, the same arithmetic as the normaliser kernel, so the same bits) while its MV
+// loads are in flight, and the normaliser launch is dropped.
+template <typename DT, int D, int GT, bool WRITE, bool READ, int BS, int U, bool NORM>
 __global__ __launch_bounds__(BS) void mv_pass_kernel(const DecodeParams p) {
   typedef typename DT::elem elem;
   constexpr int E = DT::kElemsPerVec;
@@ -78,9 +81,30 @@ __global__ __launch_bounds__(BS) void mv_pass_kernel(const DecodeParams p) {
 #pragma unroll
     for (int e = 0; e < E; ++e) acc[g][e] = 0.f;
 
+  // (max, 1/sum) of row r of this memory
+  constexpr int NR = (WRITE ? 1 : 0) + (READ ? GT : 0);
+  float2 nrm[NR];
+  if (NORM) {
+#pragma unroll
+    for (int r = 0; r < NR; ++r) {
+      if ((uint32_t)r < R) {
+        float2 st = make_float2(-INFINITY, 0.f);
+        if ((uint32_t)lane < p.n_tiles) st = p.stats[((size_t)unit * R + r) * p.n_tiles + lane];
+        const float mx = xor_max<1, 32>(st.x);
+        const float sm = xor_sum<1, 32>(st.y * fast_exp2(st.x - mx));
+        float inv = 1.0f / sm;
+        if (WRITE && r == 0 && p.gate) inv *= p.gate[(size_t)b * p.gate_bstride + h];
+        nrm[r] = make_float2(mx, inv);
+      }
+    }
+  } else {
+#pragma unroll
+    for (int r = 0; r < NR; ++r)
+      if ((uint32_t)r < R) nrm[r] = p.norm[(size_t)unit * R + r];
+  }
+
   if (active) {
     const float* sc = p.scores + (size_t)unit * R * M + slot0;  // row r at sc + r*M
-    const float2* nrm = p.norm + (size_t)unit * R;              // (max, 1/sum) of row r
     float ww[U];
     if (WRITE) {
       load_run<U>(sc, ww);
@@ -183,17 +207,25 @@ void plan_mv_pass(DecodeParams& p, int dtype) {
   const uint32_t row_bytes = p.d * (dtype == 0 ? 4u : 2u);
   const uint32_t spb = s.bs * s.u * 16u / row_bytes;  // slots per workgroup
   p.S = (p.M + spb - 1) / spb;
+  // with at most one (max, sum) pair per lane the MV pass merges them itself
+  p.fuse_norm = p.n_tiles <= 64 ? 1u : 0u;
+}
+
+template <typename DT, int D, int GT, int BS, int U, bool NORM>
+static void launch_mode_n(const DecodeParams& p, hipStream_t s) {
+  const dim3 grid(p.S, p.B * p.Hkv), block(BS);
+  if (p.has_write && p.has_read)
+    hipLaunchKernelGGL((mv_pass_kernel<DT, D, GT, true, true, BS, U, NORM>), grid, block, 0, s, p);
+  else if (p.has_read)
+    hipLaunchKernelGGL((mv_pass_kernel<DT, D, GT, false, true, BS, U, NORM>), grid, block, 0, s, p);
+  else
+    hipLaunchKernelGGL((mv_pass_kernel<DT, D, 1, true, false, BS, U, NORM>), grid, block, 0, s, p);
 }
 
 template <typename DT, int D, int GT, int BS, int U>
 static void launch_mode(const DecodeParams& p, hipStream_t s) {
-  const dim3 grid(p.S, p.B * p.Hkv), block(BS);
-  if (p.has_write && p.has_read)
-    hipLaunchKernelGGL((mv_pass_kernel<DT, D, GT, true, true, BS, U>), grid, block, 0, s, p);
-  else if (p.has_read)
-    hipLaunchKernelGGL((mv_pass_kernel<DT, D, GT, false, true, BS, U>), grid, block, 0, s, p);
-  else
-    hipLaunchKernelGGL((mv_pass_kernel<DT, D, 1, true, false, BS, U>), grid, block, 0, s, p);
+  if (p.fuse_norm) launch_mode_n<DT, D, GT, BS, U, true>(p, s);
+  else launch_mode_n<DT, D, GT, BS, U, false>(p, s);
 }
 
 template <typename DT, int D>
