@@ -204,13 +204,22 @@ __global__ __launch_bounds__(512, 4) void prefill_stats_kernel(const PrefillPara
     m[jt] = kNegBig;
     s[jt] = 0.f;
   }
-  // the query rows do not change over the loop: keep their operand fragments in registers
+  // the query rows do not change over the loop: keep their operand fragments in registers.
+  // A negative scale is moved into the row itself (negating bf16 is exact), so that below the
+  // largest raw score is also the largest scaled one and the scaling can ride in the exponent's fma.
   __syncthreads();
   bf16x8 xb[2][KS];
 #pragma unroll
-  for (int jt = 0; jt < 2; ++jt)
+  for (int jt = 0; jt < 2; ++jt) {
+    const uint32_t flip = scale[jt] < 0.f ? 0x80008000u : 0u;
+    scale[jt] = fabsf(scale[jt]);
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) xb[jt][ks] = frag(sX, LD, 64 * rh + 32 * jt + col, ks * 16 + half * 8);
+    for (int ks = 0; ks < KS; ++ks) {
+      u32x4 v = __builtin_bit_cast(u32x4, frag(sX, LD, 64 * rh + 32 * jt + col, ks * 16 + half * 8));
+      v ^= (u32x4){flip, flip, flip, flip};
+      xb[jt][ks] = __builtin_bit_cast(bf16x8, v);
+    }
+  }
   Tile<128, D, NT> tk;
   auto fetch_keys = [&](uint32_t m0) {
     tk.fetch_rows(p.mk, [&](int r) -> const uint16_t* { return (m0 + r < p.M) ? mk + (size_t)(m0 + r) * D : nullptr; });
@@ -233,16 +242,13 @@ __global__ __launch_bounds__(512, 4) void prefill_stats_kernel(const PrefillPara
       }
 #pragma unroll
       for (int jt = 0; jt < 2; ++jt) {
-        float tmax = kNegBig;
+        float tmax = acc[jt][0];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          acc[jt][v] *= scale[jt];
-          tmax = fmaxf(tmax, acc[jt][v]);
-        }
-        const float mn = fmaxf(m[jt], tmax);
+        for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, acc[jt][v]);
+        const float mn = fmaxf(m[jt], tmax * scale[jt]);
         float add = 0.f;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) add += fast_exp2(acc[jt][v] - mn);
+        for (int v = 0; v < 16; ++v) add += fast_exp2(__builtin_fmaf(acc[jt][v], scale[jt], -mn));
         s[jt] = s[jt] * fast_exp2(m[jt] - mn) + add;
         m[jt] = mn;
       }

@@ -136,6 +136,27 @@ def test_prefill_per_sequence_keys_and_scales(P, R):
     check_prefill_state(R, ref, mk, wq, wv, to_np(gpu.export()[1], "bf16"), T, "per-seq")
 
 
+@pytest.mark.parametrize("rs,ws", [(-0.08, 0.09), (0.09, -0.12), (0.0, 0.09), (-0.05, -0.05)])
+def test_prefill_and_decode_with_negative_or_zero_scales(P, R, rs, ws):
+    """A scale is any finite number: a negative one attends to the least similar keys, zero gives
+    uniform weights.  Both entry points against the oracle."""
+    w = syn.Workload("pf_neg", 1, 2, 4, 2, 128, 256, "bf16", 0)
+    T = 140
+    ref, gpu, mk, _, _ = make_pair(w, R.RefCache, P.BctCache, mv0=True, max_prefill_T=T, read_scale=rs, write_scale=ws)
+    q, wq, wv = syn.make_step(w, 0, T=T)
+    o_ref = ref.prefill(q, wq, wv, T)
+    o_gpu = gpu.prefill(to_dev(q, "bf16"), to_dev(wq, "bf16"), to_dev(wv, "bf16"), T)
+    check_prefill_out(to_np(o_gpu, "bf16"), o_ref, "bf16", f"scales {rs} {ws}")
+    check_prefill_state(R, ref, mk, wq, wv, to_np(gpu.export()[1], "bf16"), T, f"scales {rs} {ws}")
+    before = ref.values()
+    gpu.set_values(to_dev(before, "bf16"))
+    q, wq, wv = syn.make_step(w, T)
+    o_ref = ref.decode_step(q, wq, wv)
+    o_gpu = gpu.decode_step(to_dev(q, "bf16"), to_dev(wq, "bf16"), to_dev(wv, "bf16"))
+    assert np.max(np.abs(f64(to_np(o_gpu, "bf16"), "bf16") - f64(o_ref, "bf16"))) <= 2e-2
+    check_state_one_step(to_np(gpu.export()[1], "bf16"), ref.values(), "bf16", "decode", before=before)
+
+
 def test_prefill_then_decode_continues(P, R):
     """A prompt through bct_prefill, then decode steps: the two entry points share one state."""
     w = syn.Workload("pf_dec", 1, 2, 4, 4, 128, 256, "bf16", 0)
