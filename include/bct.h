@@ -149,6 +149,20 @@ bct_status bct_cache_import(bct_cache* c, const void* mk_src, const void* mv_src
 
 bct_status bct_cache_steps(const bct_cache* c, uint64_t* steps);
 
+/* The launch plan the library would use for a decode step of this descriptor (no GPU needed):
+ * how many launches, and the shape of the pass over MV.  For inspection and tests. */
+typedef struct bct_plan_info {
+  uint32_t launches;          /* kernels per decode step with both a write and a read: 1, 3 or 4       */
+  uint32_t one_launch;        /* 1: the small-cache single-workgroup step                               */
+  uint32_t scores_mfma;       /* 1: scores by MFMA (bf16, keys shared by the batch), else dot products  */
+  uint32_t slots_per_stat;    /* slots per (max, sum) partial of the scores pass                        */
+  uint32_t normaliser_launch; /* 1: the partials are merged by a launch of their own                    */
+  uint32_t mv_workgroup;      /* threads per workgroup of the MV pass                                   */
+  uint32_t mv_loads_per_lane; /* 16-byte loads each lane of the MV pass has in flight                   */
+  uint32_t mv_splits;         /* workgroups per memory in the MV pass (> 1: a merge launch follows)     */
+} bct_plan_info;
+bct_status bct_plan_query(const bct_cache_desc* desc, bct_plan_info* info);
+
 /* Device addresses of the two regions inside cache_mem (for zero-copy views). */
 bct_status bct_cache_regions(const bct_cache* c, void** mk_dev, size_t* mk_bytes,
                              void** mv_dev, size_t* mv_bytes);

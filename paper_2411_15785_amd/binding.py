@@ -29,7 +29,7 @@ BCT_STEP_STREAMING = 2
 EXPORTS = [
     "bct_cache_query", "bct_cache_init", "bct_cache_set_keys", "bct_cache_set_values",
     "bct_decode_step", "bct_prefill", "bct_decode_step_gated", "bct_prefill_gated", "bct_cache_export",
-    "bct_cache_randomize_values", "bct_cache_export_sequence", "bct_cache_import_sequence", "bct_cache_import", "bct_cache_steps",
+    "bct_cache_randomize_values", "bct_cache_export_sequence", "bct_cache_import_sequence", "bct_plan_query", "bct_cache_import", "bct_cache_steps",
     "bct_cache_regions", "bct_cache_destroy", "bct_strerror", "bct_last_error", "bct_stream_copy",
     "bct_profile_enable", "bct_profile_read",
 ]
@@ -41,6 +41,12 @@ class bct_cache_desc(ctypes.Structure):
                 ("head_dim", ctypes.c_uint32), ("dtype", ctypes.c_int32),
                 ("read_scale", ctypes.c_float), ("write_scale", ctypes.c_float),
                 ("flags", ctypes.c_uint32)]
+
+
+class bct_plan_info(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_uint32) for n in ("launches", "one_launch", "scores_mfma", "slots_per_stat",
+                                               "normaliser_launch", "mv_workgroup", "mv_loads_per_lane",
+                                               "mv_splits")]
 
 
 class BctError(RuntimeError):
@@ -75,6 +81,7 @@ def lib() -> ctypes.CDLL:
     L.bct_cache_set_values.argtypes = [vp, vp, vp]
     L.bct_decode_step.argtypes = [vp, vp, vp, vp, vp, vp]
     L.bct_prefill.argtypes = [vp, vp, vp, vp, u32, vp, vp]
+    L.bct_plan_query.argtypes = [dp, ctypes.POINTER(bct_plan_info)]
     L.bct_cache_randomize_values.argtypes = [vp, u64, ctypes.c_float, vp]
     L.bct_cache_export_sequence.argtypes = [vp, u32, vp, vp, vp]
     L.bct_cache_import_sequence.argtypes = [vp, u32, vp, vp, vp]
@@ -122,6 +129,13 @@ def bct_cache_init(desc, max_prefill_T, cache_ptr, cache_bytes, ws_ptr, ws_bytes
     st = lib().bct_cache_init(ctypes.byref(desc) if desc is not None else None, max_prefill_T, cache_ptr,
                               cache_bytes, ws_ptr, ws_bytes, stream, ctypes.byref(h))
     return st, h
+
+
+def bct_plan_query(desc):
+    """-> (status, {field: value}) : the launch plan of a decode step for this descriptor."""
+    info = bct_plan_info()
+    st = lib().bct_plan_query(ctypes.byref(desc) if desc is not None else None, ctypes.byref(info))
+    return st, {n: getattr(info, n) for n, _ in bct_plan_info._fields_}
 
 
 def bct_last_error() -> str:

@@ -423,6 +423,23 @@ bct_status bct_cache_steps(const bct_cache* c, uint64_t* steps) {
   return BCT_OK;
 }
 
+bct_status bct_plan_query(const bct_cache_desc* desc, bct_plan_info* info) {
+  const bct_status st = check_desc(desc);
+  if (st != BCT_OK) return st;
+  if (!info) return fail(BCT_ERR_INVALID_ARG, "info is NULL");
+  bct::DecodeParams p;
+  fill_plan(desc, p);
+  info->one_launch = p.fused;
+  info->scores_mfma = (desc->dtype == BCT_BF16 && !p.mk_per_seq) ? 1u : 0u;
+  info->slots_per_stat = p.stat_tile;
+  info->normaliser_launch = (!p.fused && !p.fuse_norm) ? 1u : 0u;
+  info->mv_workgroup = p.mv_bs;
+  info->mv_loads_per_lane = p.mv_u;
+  info->mv_splits = p.S;
+  info->launches = p.fused ? 1u : 2u + info->normaliser_launch + (p.S > 1 ? 1u : 0u);
+  return BCT_OK;
+}
+
 bct_status bct_cache_regions(const bct_cache* c, void** mk_dev, size_t* mk_bytes, void** mv_dev, size_t* mv_bytes) {
   if (!c) return fail(BCT_ERR_INVALID_ARG, "cache handle is NULL");
   if (mk_dev) *mk_dev = c->mk;

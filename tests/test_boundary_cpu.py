@@ -154,3 +154,35 @@ def test_bench_refuses_more_than_one_gpu():
     import sys
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode != 0 and "one GPU" in r.stderr
+
+
+def test_launch_plans_of_the_five_workloads(L):
+    """Host logic: which path a decode step takes, decided from the descriptor alone."""
+    import bct_synth as syn
+
+    def plan(name, flags=0):
+        w = syn.WORKLOADS[name]
+        dt = P.BCT_F32 if w.dtype == "f32" else P.BCT_BF16
+        st, info = P.bct_plan_query(P.make_desc(w.M, w.B, w.Hq, w.Hkv, w.d, dt, w.scale, w.scale, flags))
+        assert st == P.BCT_OK
+        return info
+
+    c1 = plan("cfg1")            # 4 memories of 64 slots: one launch
+    assert c1["one_launch"] == 1 and c1["launches"] == 1
+    c1s = plan("cfg1", P.BCT_STEP_STREAMING)
+    assert c1s["one_launch"] == 0 and c1s["scores_mfma"] == 0 and c1s["launches"] == 2     # one split: no merge
+    c2 = plan("cfg2")            # M = 1024: too large for the one-launch step
+    assert c2["one_launch"] == 0 and c2["scores_mfma"] == 1
+    c3 = plan("cfg3")            # the headline shape: scores, MV pass (merging the 32 partials per row itself), merge
+    assert c3 == dict(launches=3, one_launch=0, scores_mfma=1, slots_per_stat=128, normaliser_launch=0,
+                      mv_workgroup=256, mv_loads_per_lane=4, mv_splits=64)
+    assert c3["mv_workgroup"] * c3["mv_loads_per_lane"] * 16 * c3["mv_splits"] == 4096 * 128 * 2   # one memory, one-shot
+    c4 = plan("cfg4")            # 4 query heads per KV head: the wide workgroup; 128 partials per row: own launch
+    assert c4["mv_workgroup"] == 512 and c4["mv_loads_per_lane"] == 8 and c4["normaliser_launch"] == 1
+    assert c4["launches"] == 4
+    c5 = plan("cfg5")
+    assert c5["mv_splits"] * c5["mv_workgroup"] * c5["mv_loads_per_lane"] * 16 == 16384 * 128 * 2
+    assert plan("cfg3", P.BCT_MK_PER_SEQUENCE)["scores_mfma"] == 0      # per-sequence keys: no shared contraction
+    st, _ = P.bct_plan_query(desc(capacity_M=100))
+    assert st == P.BCT_ERR_UNSUPPORTED
+    assert L.bct_plan_query(ctypes.byref(desc()), None) == P.BCT_ERR_INVALID_ARG
