@@ -80,6 +80,7 @@ hipError_t launch_prefill_bf16(const PrefillParams& p, hipStream_t s);
 hipError_t launch_scores(const DecodeParams& p, int dtype, hipStream_t s);
 hipError_t launch_normalise(const DecodeParams& p, hipStream_t s);
 hipError_t launch_stream(const DecodeParams& p, int dtype, hipStream_t s);
+hipError_t launch_stream_gqa(const DecodeParams& p, hipStream_t s);   // bf16, d = 128, G > 2, with a read
 hipError_t launch_merge(const DecodeParams& p, int dtype, hipStream_t s);
 hipError_t launch_fused(const DecodeParams& p, int dtype, hipStream_t s);
 hipError_t launch_fill_zero(void* dst, size_t n_bytes, hipStream_t s);

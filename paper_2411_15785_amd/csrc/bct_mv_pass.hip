@@ -200,8 +200,14 @@ struct MvShape {
 static constexpr MvShape kSmall = {256, 4};  // 16 KB per workgroup
 static constexpr MvShape kWide = {512, 8};   // 64 KB per workgroup
 
+// bf16, d = 128, G > 2: the MFMA read (bct_mv_pass_gqa.hip), again 16 KB one-shot workgroups.  Measured at
+// B = 64, Hkv = 8, G = 4, M = 8192 (MV pass alone): 128 threads 351 us, 256 threads 386 us, 512 threads 415 us,
+// against 429 us for the vector-ALU read in its best shape (512 x 8); the smaller workgroups leave more
+// partial outputs to sum (merge 21 us against 7 us).
+static constexpr MvShape kGqa = {128, 8};
+
 void plan_mv_pass(DecodeParams& p, int dtype) {
-  const MvShape s = (p.G <= 2) ? kSmall : kWide;
+  const MvShape s = (p.G <= 2) ? kSmall : (dtype == 1 && p.d == 128) ? kGqa : kWide;
   p.mv_bs = s.bs;
   p.mv_u = s.u;
   const uint32_t row_bytes = p.d * (dtype == 0 ? 4u : 2u);
@@ -237,14 +243,22 @@ static bool launch_shape(const DecodeParams& p, hipStream_t s) {
     return true;
   }
   if (p.mv_bs == kWide.bs && p.mv_u == kWide.u && G > 2) {
-    if (G <= 4) launch_mode<DT, D, 4, 512, 8>(p, s);
+    if (!p.has_read) launch_mode<DT, D, 1, 512, 8>(p, s);
+    else if (G <= 4) launch_mode<DT, D, 4, 512, 8>(p, s);
     else launch_mode<DT, D, 8, 512, 8>(p, s);
+    return true;
+  }
+  if (p.mv_u == 8 && G > 2 && !p.has_read) {   // write-only step of a cache whose reads take the MFMA pass
+    if (p.mv_bs == 256) launch_mode<DT, D, 1, 256, 8>(p, s);
+    else if (p.mv_bs == 128) launch_mode<DT, D, 1, 128, 8>(p, s);
+    else return false;
     return true;
   }
   return false;
 }
 
 hipError_t launch_stream(const DecodeParams& p, int dtype, hipStream_t s) {
+  if (dtype == 1 && p.d == 128 && p.G > 2 && p.has_read) return launch_stream_gqa(p, s);
   bool ok;
   if (dtype == 0) ok = (p.d == 128) ? launch_shape<F32, 128>(p, s) : launch_shape<F32, 64>(p, s);
   else ok = (p.d == 128) ? launch_shape<BF16, 128>(p, s) : launch_shape<BF16, 64>(p, s);

@@ -177,8 +177,11 @@ def test_launch_plans_of_the_five_workloads(L):
     assert c3 == dict(launches=3, one_launch=0, scores_mfma=1, slots_per_stat=128, normaliser_launch=0,
                       mv_workgroup=256, mv_loads_per_lane=4, mv_splits=64)
     assert c3["mv_workgroup"] * c3["mv_loads_per_lane"] * 16 * c3["mv_splits"] == 4096 * 128 * 2   # one memory, one-shot
-    c4 = plan("cfg4")            # 4 query heads per KV head: the wide workgroup; 128 partials per row: own launch
-    assert c4["mv_workgroup"] == 512 and c4["mv_loads_per_lane"] == 8 and c4["normaliser_launch"] == 1
+    c4 = plan("cfg4")            # 4 query heads per KV head: the MFMA read, 16 KB workgroups; 128 partials per row: own launch
+    assert c4["mv_workgroup"] == 128 and c4["mv_loads_per_lane"] == 8 and c4["normaliser_launch"] == 1
+    w4 = syn.WORKLOADS["cfg4"]
+    st, f4 = P.bct_plan_query(P.make_desc(w4.M, w4.B, w4.Hq, w4.Hkv, w4.d, P.BCT_F32, w4.scale, w4.scale))
+    assert st == P.BCT_OK and f4["mv_workgroup"] == 512          # fp32 storage keeps the vector-ALU read
     assert c4["launches"] == 4
     c5 = plan("cfg5")
     assert c5["mv_splits"] * c5["mv_workgroup"] * c5["mv_loads_per_lane"] * 16 == 16384 * 128 * 2
