@@ -116,6 +116,8 @@ SMALL = [
     ("bf16_d128_gqa2_units576", 36, 32, 16, 128, 192, "bf16"),
     ("bf16_d64_units1024", 64, 16, 16, 64, 64, "bf16"),
     ("f32_d128_gqa4_units520", 130, 16, 4, 128, 64, "f32"),
+    ("bf16_units4096", 512, 8, 8, 64, 64, "bf16"),            # many small memories
+    ("bf16_gqa4_units2048", 256, 32, 8, 128, 64, "bf16"),     # the MFMA read with a single 64-slot tile per memory
     ("bf16_m128_units512", 16, 32, 32, 128, 128, "bf16"),     # the largest cache of the one-launch step
     ("f32_gqa8_m128", 1, 8, 1, 128, 128, "f32"),
     ("bf16_gqa4_m128_d64", 3, 8, 2, 64, 128, "bf16"),
