@@ -22,11 +22,8 @@ namespace bct {
 
 namespace {
 
-// Workgroup shapes of the projections: wavefronts that split K, and weight tiles a wavefront has in flight.
-// A plain projection uses 16 wavefronts so that K = 4096 is a single round of loads per wavefront; the
-// SwiGLU pair, with two weight streams per wavefront, uses 8 (and so may use 256 registers per lane).
-constexpr int kLinWaves = 16, kLinUnroll = 8;
-constexpr int kGluWaves = 8, kGluUnroll = 8;
+// Workgroup shapes of the projections (wavefronts that split K, weight tiles a wavefront has in flight,
+// feature tiles per workgroup) are template parameters chosen where the kernels are launched.
 
 __device__ __forceinline__ float bf16f(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
 __device__ __forceinline__ uint16_t f2bf16(float x) { return __builtin_bit_cast(uint16_t, (__bf16)x); }
@@ -67,19 +64,27 @@ struct LinearOut {
   uint32_t start[4];
 };
 
-template <bool SWIGLU, bool XT, int WAVES, int U>
+// FT: feature tiles (of 16) per workgroup.  Every wavefront streams FT (x 2 for SwiGLU) weight tiles against
+// each activation fragment it loads: the activations come from L2, where all workgroups ask for the same
+// lines at the same time, and with one weight tile per fragment that traffic (2 KB per KB of weights)
+// bounds the kernel at about 4 TB/s of weights; two tiles per fragment reach about 5.
+template <bool SWIGLU, bool XT, int WAVES, int U, int FT>
 __global__ __launch_bounds__(64 * WAVES) void linear_kernel(const uint16_t* __restrict__ x,
                                                             const u32x4* __restrict__ w,
                                                             const u32x4* __restrict__ w2, const uint16_t* residual,
                                                             LinearOut dst, uint32_t rows, uint32_t K,
                                                             uint32_t out_tiled) {
+  constexpr int NW2 = SWIGLU ? 2 : 1;   // weight matrices
+  constexpr int NS = FT * NW2;          // weight streams of a wavefront: stream s = feature tile s / NW2 of matrix s % NW2
+  constexpr int NTHR = 64 * WAVES;
   __shared__ float sC[WAVES][32][17];
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64, jl = lane % 16, kg = lane / 16;
-  const uint32_t nt = blockIdx.x, r0 = blockIdx.y * 32, KT = K / 32;
+  const uint32_t nt0 = blockIdx.x * FT, r0 = blockIdx.y * 32, KT = K / 32;
   // this wavefront's share of the K tiles
   const uint32_t kt0 = (uint32_t)((uint64_t)wave * KT / WAVES), kt1 = (uint32_t)((uint64_t)(wave + 1) * KT / WAVES);
-  const u32x4* wt = w + ((size_t)nt * KT + kt0) * 64 + lane;
-  const u32x4* wt2 = SWIGLU ? w2 + ((size_t)nt * KT + kt0) * 64 + lane : nullptr;
+  const u32x4* wt[NS];
+#pragma unroll
+  for (int s = 0; s < NS; ++s) wt[s] = ((s % NW2) ? w2 : w) + ((size_t)(nt0 + s / NW2) * KT + kt0) * 64 + lane;
   // A operand: lane holds token row jl (+16 for the second row tile), inputs 8 * kg .. + 8 of the K tile.
   // Rows past the end load a valid row instead; their results are never stored.
   // Tiled activations: the two operands of K tile kt are the consecutive 1 KB tiles 2 * kt, 2 * kt + 1
@@ -90,23 +95,23 @@ __global__ __launch_bounds__(64 * WAVES) void linear_kernel(const uint16_t* __re
                           : x + (size_t)ra * K + (size_t)kt0 * 32 + kg * 8;
   const uint16_t* xb = XT ? xa + 64 * 8 : x + (size_t)rb * K + (size_t)kt0 * 32 + kg * 8;
   constexpr size_t xstep = XT ? 128 * 8 : 32;
-  f32x4 acc[2][2];
+  f32x4 acc[NS][2];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int s = 0; s < NS; ++s)
 #pragma unroll
-    for (int j = 0; j < 2; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < 2; ++j) acc[s][j] = f32x4{0.f, 0.f, 0.f, 0.f};
   const uint32_t n_t = kt1 - kt0;
   // Rounds of U tiles: all loads of a round are issued before its first MFMA, so a round costs one memory
   // latency.  The last, partial round loads its missing tiles from the share's last tile (in bounds) and
   // zeroes their weights, which removes them from the sum.
   for (uint32_t t = 0; t < n_t; t += U) {
     const bool whole = t + U <= n_t;
-    u32x4 b[U], b2[U], a0[U], a1[U];
+    u32x4 b[U][NS], a0[U], a1[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const size_t i = whole ? t + u : min(t + u, n_t - 1);
-      b[u] = __builtin_nontemporal_load(wt + i * 64);
-      if (SWIGLU) b2[u] = __builtin_nontemporal_load(wt2 + i * 64);
+#pragma unroll
+      for (int s = 0; s < NS; ++s) b[u][s] = __builtin_nontemporal_load(wt[s] + i * 64);
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -118,50 +123,61 @@ __global__ __launch_bounds__(64 * WAVES) void linear_kernel(const uint16_t* __re
 #pragma unroll
       for (int u = 0; u < U; ++u)
         if (t + u >= n_t) {
-          b[u] = u32x4{0u, 0u, 0u, 0u};
-          if (SWIGLU) b2[u] = u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+          for (int s = 0; s < NS; ++s) b[u][s] = u32x4{0u, 0u, 0u, 0u};
         }
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const bf16x8 va = __builtin_bit_cast(bf16x8, a0[u]), vb = __builtin_bit_cast(bf16x8, a1[u]);
-      acc[0][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, __builtin_bit_cast(bf16x8, b[u]), acc[0][0], 0, 0, 0);
-      acc[0][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vb, __builtin_bit_cast(bf16x8, b[u]), acc[0][1], 0, 0, 0);
-      if (SWIGLU) {
-        acc[1][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, __builtin_bit_cast(bf16x8, b2[u]), acc[1][0], 0, 0, 0);
-        acc[1][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vb, __builtin_bit_cast(bf16x8, b2[u]), acc[1][1], 0, 0, 0);
+#pragma unroll
+      for (int s = 0; s < NS; ++s) {
+        const bf16x8 vw = __builtin_bit_cast(bf16x8, b[u][s]);
+        acc[s][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, vw, acc[s][0], 0, 0, 0);
+        acc[s][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vb, vw, acc[s][1], 0, 0, 0);
       }
     }
   }
-  // accumulator element v of a lane: token row 4 * kg + v of the row tile, feature jl.
-  // The first 512 threads then own one of the 32 x 16 outputs each and add the partials in wave order;
-  // the SwiGLU variant sends its second accumulator pair through the same buffer afterwards.
-  const uint32_t oi = (threadIdx.x / 16) % 32, oj = threadIdx.x % 16;
-  float sum[2];
+  // accumulator element v of a lane: token row 4 * kg + v of the row tile, feature jl.  Per feature tile
+  // the partials of all wavefronts go through LDS (one matrix at a time through the same buffer) and
+  // every thread adds them in wave order for the outputs it owns (32 x 16 per tile).
+  constexpr int OPT = (512 + NTHR - 1) / NTHR;   // outputs per thread and tile
 #pragma unroll
-  for (int pass = 0; pass < (SWIGLU ? 2 : 1); ++pass) {
-    if (pass) __syncthreads();
+  for (int f = 0; f < FT; ++f) {
+    float sum[NW2][OPT];
 #pragma unroll
-    for (int rt = 0; rt < 2; ++rt)
+    for (int pass = 0; pass < NW2; ++pass) {
+      if (f || pass) __syncthreads();
 #pragma unroll
-      for (int v = 0; v < 4; ++v) sC[wave][16 * rt + 4 * kg + v][jl] = acc[pass][rt][v];
-    __syncthreads();
-    float a = 0.f;
+      for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
-    for (int k = 0; k < WAVES; ++k) a += sC[k][oi][oj];
-    sum[pass] = a;
-  }
-  if (threadIdx.x < 512 && r0 + oi < rows) {
-    const uint32_t n = nt * 16 + oj;
-    const int which = n >= dst.start[2] ? 2 : n >= dst.start[1] ? 1 : 0;
-    const uint32_t width = dst.start[which + 1] - dst.start[which], col = n - dst.start[which];
-    const size_t o = (size_t)(r0 + oi) * width + col;
-    const float g = sum[0];
-    float y;
-    if (SWIGLU) y = g / (1.0f + __expf(-g)) * sum[1];
-    else y = residual ? g + bf16f(residual[o]) : g;
-    // a tiled output is the input of a projection whose K is this output's width
-    dst.ptr[which][out_tiled ? tiled_chunk(r0 + oi, col, width) * 8 + col % 8 : o] = f2bf16(y);
+        for (int v = 0; v < 4; ++v) sC[wave][16 * rt + 4 * kg + v][jl] = acc[f * NW2 + pass][rt][v];
+      __syncthreads();
+#pragma unroll
+      for (int q = 0; q < OPT; ++q) {
+        const uint32_t o = (threadIdx.x + q * NTHR) % 512, oi = o / 16, oj = o % 16;
+        float a = 0.f;
+#pragma unroll
+        for (int k = 0; k < WAVES; ++k) a += sC[k][oi][oj];
+        sum[pass][q] = a;
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < OPT; ++q) {
+      const uint32_t o = threadIdx.x + q * NTHR, oi = (o % 512) / 16, oj = o % 16;
+      if (o < 512 && r0 + oi < rows) {
+        const uint32_t n = (nt0 + f) * 16 + oj;
+        const int which = n >= dst.start[2] ? 2 : n >= dst.start[1] ? 1 : 0;
+        const uint32_t width = dst.start[which + 1] - dst.start[which], col = n - dst.start[which];
+        const size_t oo = (size_t)(r0 + oi) * width + col;
+        const float g = sum[0][q];
+        float y;
+        if (SWIGLU) y = g / (1.0f + __expf(-g)) * sum[NW2 - 1][q];
+        else y = residual ? g + bf16f(residual[oo]) : g;
+        // a tiled output is the input of a projection whose K is this output's width
+        dst.ptr[which][out_tiled ? tiled_chunk(r0 + oi, col, width) * 8 + col % 8 : oo] = f2bf16(y);
+      }
+    }
   }
 }
 
@@ -275,6 +291,33 @@ bct_status check_linear(const void* x, const void* w, const void* out, uint32_t 
 
 using namespace bct;
 
+template <int WV, int UN, int FT>
+static void launch_linear_w(const void* x, const void* w, const void* residual, const LinearOut& dst, uint32_t rows,
+                            uint32_t K, uint32_t N, uint32_t flags, void* hip_stream) {
+  const dim3 grid(N / (16 * FT), (rows + 31) / 32), block(64 * WV);
+  if (flags & BCTM_X_TILED)
+    hipLaunchKernelGGL((linear_kernel<false, true, WV, UN, FT>), grid, block, 0, (hipStream_t)hip_stream,
+                       (const uint16_t*)x, (const u32x4*)w, (const u32x4*)nullptr, (const uint16_t*)residual, dst, rows,
+                       K, 0u);
+  else
+    hipLaunchKernelGGL((linear_kernel<false, false, WV, UN, FT>), grid, block, 0, (hipStream_t)hip_stream,
+                       (const uint16_t*)x, (const u32x4*)w, (const u32x4*)nullptr, (const uint16_t*)residual, dst, rows,
+                       K, 0u);
+}
+
+template <int WV, int UN, int FT>
+static void launch_swiglu_w(const void* x, const void* wg, const void* wu, const LinearOut& dst, uint32_t rows,
+                            uint32_t K, uint32_t N, uint32_t flags, void* hip_stream) {
+  const dim3 grid(N / (16 * FT), (rows + 31) / 32), block(64 * WV);
+  const uint32_t ot = flags & BCTM_OUT_TILED ? 1u : 0u;
+  if (flags & BCTM_X_TILED)
+    hipLaunchKernelGGL((linear_kernel<true, true, WV, UN, FT>), grid, block, 0, (hipStream_t)hip_stream,
+                       (const uint16_t*)x, (const u32x4*)wg, (const u32x4*)wu, (const uint16_t*)nullptr, dst, rows, K, ot);
+  else
+    hipLaunchKernelGGL((linear_kernel<true, false, WV, UN, FT>), grid, block, 0, (hipStream_t)hip_stream,
+                       (const uint16_t*)x, (const u32x4*)wg, (const u32x4*)wu, (const uint16_t*)nullptr, dst, rows, K, ot);
+}
+
 extern "C" {
 
 bct_status bctm_embed(const int32_t* ids, const void* table, void* out, uint32_t rows, uint32_t vocab, uint32_t dim,
@@ -329,15 +372,10 @@ bct_status bctm_pack_weight(const void* w, void* packed, uint32_t N, uint32_t K,
 
 static bct_status launch_linear(const void* x, const void* w, const void* residual, const LinearOut& dst,
                                 uint32_t rows, uint32_t K, uint32_t N, uint32_t flags, void* hip_stream) {
-  const dim3 grid(N / 16, (rows + 31) / 32), block(64 * kLinWaves);
-  if (flags & BCTM_X_TILED)
-    hipLaunchKernelGGL((linear_kernel<false, true, kLinWaves, kLinUnroll>), grid, block, 0, (hipStream_t)hip_stream,
-                       (const uint16_t*)x, (const u32x4*)w, (const u32x4*)nullptr, (const uint16_t*)residual, dst, rows,
-                       K, 0u);
-  else
-    hipLaunchKernelGGL((linear_kernel<false, false, kLinWaves, kLinUnroll>), grid, block, 0, (hipStream_t)hip_stream,
-                       (const uint16_t*)x, (const u32x4*)w, (const u32x4*)nullptr, (const uint16_t*)residual, dst, rows,
-                       K, 0u);
+  // Measured at 32 rows (weights in TB/s): K = 4096, N = 4096 / 12288: 16 wavefronts, one feature tile
+  // 3.6 / 4.0 against 2.8 / 3.8 for two tiles (too few workgroups); N = 32000: two tiles 5.0 against 4.3.
+  if (N >= 16384 && N % 32 == 0) launch_linear_w<8, 4, 2>(x, w, residual, dst, rows, K, N, flags, hip_stream);
+  else launch_linear_w<16, 8, 1>(x, w, residual, dst, rows, K, N, flags, hip_stream);
   return launched("linear");
 }
 
@@ -379,17 +417,8 @@ bct_status bctm_swiglu(const void* x, const void* w_gate, const void* w_up, void
   if ((flags & BCTM_OUT_TILED) && N % 32 != 0)
     return mfail(BCT_ERR_UNSUPPORTED, "tiled activations need a multiple of 32 columns");
   if (!al16(w_up)) return mfail(BCT_ERR_MISALIGNED, "pointers must be 16-byte aligned");
-  const dim3 grid(N / 16, (rows + 31) / 32), block(64 * kGluWaves);
-  const uint32_t ot = flags & BCTM_OUT_TILED ? 1u : 0u;
   const LinearOut dst = {{(uint16_t*)out, nullptr, nullptr}, {0u, N, N, N}};
-  if (flags & BCTM_X_TILED)
-    hipLaunchKernelGGL((linear_kernel<true, true, kGluWaves, kGluUnroll>), grid, block, 0, (hipStream_t)hip_stream,
-                       (const uint16_t*)x, (const u32x4*)w_gate, (const u32x4*)w_up, (const uint16_t*)nullptr, dst, rows,
-                       K, ot);
-  else
-    hipLaunchKernelGGL((linear_kernel<true, false, kGluWaves, kGluUnroll>), grid, block, 0, (hipStream_t)hip_stream,
-                       (const uint16_t*)x, (const u32x4*)w_gate, (const u32x4*)w_up, (const uint16_t*)nullptr, dst, rows,
-                       K, ot);
+  launch_swiglu_w<4, 8, 1>(x, w_gate, w_up, dst, rows, K, N, flags, hip_stream);   // 36 us at 4096 -> 11008 (8 wavefronts: 38)
   return launched("swiglu");
 }
 

@@ -46,7 +46,8 @@ def check_close(got_bits, ref_bits, slack, what):
 
 LIN_SHAPES = [  # rows, K, N
     (1, 32, 16), (5, 64, 96), (32, 192, 48), (33, 320, 32), (70, 1024, 160), (32, 4096, 256), (3, 11008, 64),
-    (17, 2336, 16),    # 73 K tiles: uneven shares for the eight wavefronts, unrolled part plus remainder
+    (17, 2336, 16),    # 73 K tiles: uneven shares for the wavefronts, whole rounds plus a masked one
+    (33, 96, 16416),   # wide output (an output head): two feature tiles per workgroup
 ]
 
 
@@ -79,7 +80,8 @@ def test_pack_rows_layout(M, rows, K):
     assert np.array_equal(untile(t, rows, K), x)
 
 
-@pytest.mark.parametrize("rows,K,N", [(1, 32, 16), (32, 4096, 256), (45, 320, 64), (3, 11008, 64), (17, 2336, 16)])
+@pytest.mark.parametrize("rows,K,N", [(1, 32, 16), (32, 4096, 256), (45, 320, 64), (3, 11008, 64), (17, 2336, 16),
+                                      (5, 160, 16416)])
 def test_linear_tiled_input_is_bitwise_the_row_major_result(M, rows, K, N):
     x, w, res = draw(1, (rows, K)), M.bctm_pack_weight(dev(draw(2, (N, K), K ** -0.5))), dev(draw(3, (rows, N)))
     a = M.bctm_linear(dev(x), w, res)
