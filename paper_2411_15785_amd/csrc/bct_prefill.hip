@@ -177,7 +177,9 @@ __global__ __launch_bounds__(512, 4) void prefill_stats_kernel(const PrefillPara
   uint16_t* const sX = sTile;
   uint16_t* const sK = sTile;
 
-  const uint32_t unit = blockIdx.y, b = unit / p.Hkv, h = unit % p.Hkv;
+  // launch order: all sequences of one KV head, then the next head, so that the workgroups in flight
+  // share one head's keys (1 MB at M = 4096) in each XCD's L2 instead of cycling through all heads
+  const uint32_t h = blockIdx.y / p.B, b = blockIdx.y % p.B, unit = b * p.Hkv + h;
   const uint32_t nw = p.has_write ? p.T : 0u, nr = p.has_read ? p.T * p.G : 0u;
   const uint32_t row0 = blockIdx.x * kTC;
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64, col = lane % 32, half = lane / 32;
@@ -305,7 +307,9 @@ __global__ __launch_bounds__(512) void prefill_read_kernel(const PrefillParams p
   uint16_t* const sA = sBuf;
   uint16_t* const sWVt = sA + kTC * LA;
 
-  const uint32_t unit = blockIdx.y, b = unit / p.Hkv, h = unit % p.Hkv;
+  // launch order: all sequences of one KV head, then the next head, so that the workgroups in flight
+  // share one head's keys (1 MB at M = 4096) in each XCD's L2 instead of cycling through all heads
+  const uint32_t h = blockIdx.y / p.B, b = blockIdx.y % p.B, unit = b * p.Hkv + h;
   const uint32_t G = p.G, T = p.T;
   const uint32_t c = p.c_begin + blockIdx.x / G, gp = blockIdx.x % G;
   const uint32_t t0 = c * kTC, rho0 = gp * kTC;
