@@ -13,8 +13,8 @@
 //     out_c = RW_c . MV_c + tril(RW_c . WW_c^T) . WV_c,   MV_c = MV at the start of the sub-chunk,
 // where the state kernel, which walks the sub-chunks in order with its MV tile
 // in fp32 registers, leaves MV_c (rounded to bf16, as an MFMA operand has to be)
-// in the workspace.  Launches: transposes -> stats -> read(c = 0) -> state ->
-// read(c >= 1).
+// in the workspace.  Launches: transposes -> stats -> state -> read (all
+// sub-chunks; sub-chunk 0 reads the transposed copy of the initial MV).
 //
 // All matrix products use v_mfma_f32_32x32x16_bf16 with both operands read from
 // LDS tiles whose rows run along the contraction index (C[i][j] += sum_k
@@ -664,18 +664,16 @@ hipError_t launch_prefill_bf16(const PrefillParams& p0, hipStream_t s) {
     }
     return hipGetLastError();
   };
-  if (p.has_read) {
-    // without a write every sub-chunk reads MV as it is; with one, sub-chunk 0
-    // must read MV before the state kernel overwrites it
-    if ((e = read(0, p.has_write ? 1u : nb)) != hipSuccess) return e;
-  }
   if (p.has_write) {
     const dim3 g((p.M + 127) / 128, units);
     if (d128) hipLaunchKernelGGL(prefill_state_kernel<128>, g, dim3(256), 0, s, p);
     else hipLaunchKernelGGL(prefill_state_kernel<64>, g, dim3(256), 0, s, p);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    if (p.has_read && nb > 1 && (e = read(1, nb - 1)) != hipSuccess) return e;
   }
+  // every sub-chunk reads its starting state from the transposed copies in the workspace (sub-chunk 0:
+  // the copy made before the state kernel ran; without a write: all of them that copy), so one launch
+  // serves all sub-chunks
+  if (p.has_read && (e = read(0, nb)) != hipSuccess) return e;
   return hipSuccess;
 }
 
