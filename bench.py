@@ -244,6 +244,9 @@ def main():
         with open(tpath) as f:
             traffic = json.load(f).get("mv_pass_hbm_bytes_per_launch")
 
+    _, plan = pkg.bct_plan_query(desc)
+    kernel = ("decode_fused_kernel" if plan["one_launch"] else
+              "mv_pass_gqa_kernel" if (w.dtype == "bf16" and w.d == 128 and w.G > 2) else "mv_pass_kernel")
     rec = {
         "metric": "decode tokens/sec and achieved HBM GB/s (% of peak) at fixed cache capacity M",
         "value": tok_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -252,7 +255,7 @@ def main():
         "config": {"workload": f"{w.name}: {L} layers x (B={w.B}, Hq={w.Hq}, Hkv={w.Hkv}, d={w.d}, M={w.M}, "
                                f"{w.dtype}), one decode step per layer per token, attention + cache update only",
                    "layers": L, "batch": w.B, "capacity_M": w.M},
-        "roofline": {"bound": "hbm", "kernel": "mv_pass_kernel",
+        "roofline": {"bound": "hbm", "kernel": kernel,
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": (achieved / HBM_PEAK_GBS) if achieved else None, "traffic": traffic,
                      "bytes_per_launch": mv_pass_bytes, "ms_per_launch": ms_mv, "launches_timed": n_rec},
