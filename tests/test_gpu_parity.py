@@ -253,3 +253,66 @@ def test_capacity_is_constant_and_errors_are_reported(P, R):
     assert torch.cuda.memory_allocated() == free0           # no growth, no allocation in the step
     assert gpu.steps == 3 * w.M
     assert torch.isfinite(out).all()
+
+
+# ------------------------------------------------------------------ extreme inputs
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("kind", ["zero_keys", "huge_queries", "tiny_queries", "zero_write_value"])
+def test_extreme_inputs(P, R, dtype, kind):
+    """Degenerate softmaxes: all-zero keys (uniform weights), queries scaled until the softmax is one-hot
+    (scores of several thousand), queries scaled towards zero, and a write of zeros (state unchanged)."""
+    w = syn.Workload(f"extreme_{kind}", 1, 2, 4, 2, 128, 256, dtype, 0)
+    ref, gpu, mk, mv0, _ = make_pair(w, R.RefCache, P.BctCache, mv0=True, max_prefill_T=40)
+    if kind == "zero_keys":
+        z = np.zeros_like(mk)
+        ref.set_keys(z)
+        gpu.set_keys(to_dev(z, dtype))
+    for t in range(2):
+        q, wq, wv = step_np(w, t)
+        if kind == "huge_queries":
+            q, wq = (syn.pack(f64(a, dtype) * 256.0, dtype) for a in (q, wq))
+        if kind == "tiny_queries":
+            q, wq = (syn.pack(f64(a, dtype) * 2.0 ** -20, dtype) for a in (q, wq))
+        if kind == "zero_write_value":
+            wv = np.zeros_like(wv)
+        before = ref.values()
+        gpu.set_values(to_dev(before, dtype))
+        o_ref = ref.decode_step(q, wq, wv)
+        o_gpu = gpu.decode_step(to_dev(q, dtype), to_dev(wq, dtype), to_dev(wv, dtype))
+        if kind == "huge_queries":
+            # A score s carries a rounding error of about |s| * 2^-24 from its fp32 dot product, and the
+            # softmax weight inherits it as a RELATIVE error: at |s| of a few thousand that is 1e-4, not
+            # the 1e-6 of unit-scale scores, so the output bound is widened by that factor here.
+            g, r = f64(to_np(o_gpu, dtype), dtype), f64(o_ref, dtype)
+            assert np.all(np.isfinite(g))
+            assert rel_normwise(g, r) <= (4e-4 if dtype == "f32" else 2.0 ** -7), f"{kind} step {t}"
+        else:
+            check_out(to_np(o_gpu, dtype), o_ref, dtype, f"{kind} step {t}")
+        got = to_np(gpu.export()[1], dtype)
+        if kind == "zero_write_value":
+            assert np.array_equal(got, before)
+        elif kind == "huge_queries" and dtype == "f32":
+            r = ref.values().astype(np.float64)
+            assert np.max(np.abs(got - r)) <= 4e-4 * np.max(np.abs(r)), f"{kind} step {t}"
+        else:
+            check_state_one_step(got, ref.values(), dtype, f"{kind} step {t}", before=before,
+                                 rel=4e-4 if kind == "huge_queries" else 4e-6)
+    # the same through a chunk
+    T = 40
+    q, wq, wv = syn.make_step(w, 2, T=T)
+    if kind == "huge_queries":
+        q, wq = (syn.pack(f64(a, dtype) * 256.0, dtype) for a in (q, wq))
+    if kind == "tiny_queries":
+        q, wq = (syn.pack(f64(a, dtype) * 2.0 ** -20, dtype) for a in (q, wq))
+    if kind == "zero_write_value":
+        wv = np.zeros_like(wv)
+    gpu.set_values(to_dev(ref.values(), dtype))
+    o_ref = ref.prefill(q, wq, wv, T)
+    o_gpu = gpu.prefill(to_dev(q, dtype), to_dev(wq, dtype), to_dev(wv, dtype), T)
+    g, r = f64(to_np(o_gpu, dtype), dtype), f64(o_ref, dtype)
+    assert np.all(np.isfinite(g))
+    tol = 1e-5 if dtype == "f32" else 2.0 ** -6
+    if kind == "huge_queries":
+        tol = 4e-4 if dtype == "f32" else 2.0 ** -5
+    assert np.max(np.max(np.abs(g - r), axis=-1) / np.maximum(np.max(np.abs(r), axis=-1), 1e-30)) <= tol, kind
