@@ -244,6 +244,28 @@ def main():
         with open(tpath) as f:
             traffic = json.load(f).get("mv_pass_hbm_bytes_per_launch")
 
+    # The practical ceiling for a 1:1 read/write stream: the library's plain copy kernel, in place,
+    # on a buffer of MV's size, timed in this same run.
+    copy = None
+    if mv_bytes >= (64 << 20):
+        import ctypes
+        buf = torch.empty(mv_bytes, dtype=torch.uint8, device=dev)
+        bp, sp = ctypes.c_void_p(buf.data_ptr()), ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+        for _ in range(3):
+            assert pkg.lib().bct_stream_copy(bp, bp, mv_bytes, sp) == pkg.BCT_OK
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(20):
+            pkg.lib().bct_stream_copy(bp, bp, mv_bytes, sp)
+        e1.record()
+        torch.cuda.synchronize()
+        cms = e0.elapsed_time(e1) / 20
+        cgbs = 2 * mv_bytes / (cms * 1e-3) / 1e9
+        copy = {"what": f"bct_stream_copy in place over {mv_bytes} bytes (read + write counted)",
+                "ms": cms, "GB/s": cgbs, "frac_of_peak": cgbs / HBM_PEAK_GBS,
+                "mv_pass_vs_copy": (achieved / cgbs) if achieved else None}
+        del buf
+
     _, plan = pkg.bct_plan_query(desc)
     kernel = ("decode_fused_kernel" if plan["one_launch"] else
               "mv_pass_gqa_kernel" if (w.dtype == "bf16" and w.d == 128 and w.G > 2) else "mv_pass_kernel")
@@ -264,6 +286,8 @@ def main():
                        "frac_of_peak": layer_step_bytes / (layer_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                        "ms_scores": ms_scores, "ms_mv_pass": ms_mv, "ms_merge": ms_merge},
     }
+    if copy:
+        rec["copy_ceiling"] = copy
     if prefill:
         rec["prefill"] = prefill
     if w.name == "cfg3" and not args.no_full_stack:

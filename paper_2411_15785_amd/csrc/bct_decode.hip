@@ -230,10 +230,19 @@ __global__ __launch_bounds__(256) void fill_zero_kernel(u32x4* dst, size_t n_vec
     dst[i] = (u32x4){0u, 0u, 0u, 0u};
 }
 
+// A visit of a workgroup covers 16 KB: four 16-byte vectors per lane, all four loads issued before the
+// first store, consecutive lanes on consecutive vectors (the access shape of the MV pass).
 __global__ __launch_bounds__(256) void copy_kernel(u32x4* dst, const u32x4* src, size_t n_vec) {
-  const size_t stride = (size_t)gridDim.x * 256;
-  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n_vec; i += stride)
-    __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+  const size_t stride = (size_t)gridDim.x * 1024;
+  for (size_t base = (size_t)blockIdx.x * 1024 + threadIdx.x; base < n_vec; base += stride) {
+    u32x4 v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (base + u * 256 < n_vec) v[u] = __builtin_nontemporal_load(src + base + u * 256);
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (base + u * 256 < n_vec) __builtin_nontemporal_store(v[u], dst + base + u * 256);
+  }
 }
 
 // MV := amplitude * u, u uniform on the 2^24-point grid of [-1, 1): element i of the flat array takes
@@ -360,7 +369,9 @@ hipError_t launch_randomize(void* dst, size_t n_bytes, int dtype, uint64_t seed,
 hipError_t launch_copy(void* dst, const void* src, size_t n_bytes, hipStream_t s) {
   const size_t n_vec = n_bytes / 16;
   if (n_vec == 0) return hipSuccess;
-  hipLaunchKernelGGL(copy_kernel, dim3(grid_for(n_vec)), dim3(256), 0, s, (u32x4*)dst, (const u32x4*)src, n_vec);
+  size_t blocks = (n_vec + 1023) / 1024;
+  if (blocks > 8192) blocks = 8192;
+  hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (u32x4*)dst, (const u32x4*)src, n_vec);
   return hipGetLastError();
 }
 

@@ -97,3 +97,21 @@ def test_session_call_errors(P, R):
         gpu.export_sequence(0, with_keys=True)              # shared keys: no per-sequence MK
     with pytest.raises(P.BctError):
         gpu.randomize_values(1, float("inf"))
+
+
+@pytest.mark.parametrize("n_vec", [1, 255, 1024, 1025, 3 * 1024 + 77, 8192 * 1024 + 513])
+def test_stream_copy_copies_exactly_its_range(P, n_vec):
+    """bct_stream_copy: every byte of the range arrives, the bytes after it stay as they were (sizes that
+    end inside a lane group, inside a workgroup's visit, and beyond one visit of the whole grid)."""
+    import ctypes
+
+    import torch
+    g = torch.Generator(device="cpu").manual_seed(n_vec)
+    src = torch.randint(0, 256, (n_vec * 16,), dtype=torch.uint8, generator=g).to("cuda:0")
+    dst = torch.full((n_vec * 16 + 4096,), 0xA5, dtype=torch.uint8, device="cuda:0")
+    st = P.lib().bct_stream_copy(ctypes.c_void_p(dst.data_ptr()), ctypes.c_void_p(src.data_ptr()), n_vec * 16,
+                                 ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+    assert st == P.BCT_OK
+    torch.cuda.synchronize()
+    assert torch.equal(dst[:n_vec * 16], src)
+    assert bool((dst[n_vec * 16:] == 0xA5).all())
