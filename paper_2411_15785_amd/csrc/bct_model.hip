@@ -181,6 +181,166 @@ __global__ __launch_bounds__(64 * WAVES) void linear_kernel(const uint16_t* __re
   }
 }
 
+// The same projections for MANY token rows (a prefill chunk: batch x T rows), where the product is a
+// dense contraction bound by the matrix cores and no longer by streaming the weights.  A workgroup of four
+// wavefronts owns 128 token rows x 128 output features (SwiGLU: 64 features of both matrices), each
+// wavefront 64 x 64 of it as 4 x 4 accumulators of v_mfma_f32_16x16x32_bf16.  Both operands are already
+// stored in MFMA operand order (packed weights, tiled activations), so a K step of 32 inputs is 16 one-KB
+// tiles that the workgroup copies to LDS unchanged (linear 16-byte accesses on both sides) and every
+// wavefront reads back its four row tiles and four feature tiles; the loads of the next K step are in
+// flight in registers while the current one is multiplied (two LDS stages, one barrier per K step).
+// Workgroups are numbered so that the 64 of them resident on one XCD at a time (every eighth workgroup id)
+// form 8 row tiles x 8 feature tiles: each operand panel is fetched into that XCD's L2 once for eight uses.
+// Output: the accumulators go through LDS (fp32) and leave as 16-byte row-contiguous chunks, with the
+// residual added / the SwiGLU applied in fp32 before the one rounding to bf16.
+template <bool SWIGLU, bool XT>
+__global__ __launch_bounds__(256, 2) void linear_rows_kernel(const uint16_t* __restrict__ x,
+                                                             const u32x4* __restrict__ w,
+                                                             const u32x4* __restrict__ w2, const uint16_t* residual,
+                                                             LinearOut dst, uint32_t rows, uint32_t K, uint32_t NT,
+                                                             uint32_t out_tiled) {
+  constexpr uint32_t HB = 8;                       // row tiles of a band
+  constexpr uint32_t BNF = SWIGLU ? 64 : 128;      // output features of a workgroup
+  constexpr int ES = 68;                           // floats per row of the output staging (64 + pad)
+  __shared__ __attribute__((aligned(16))) unsigned char smem[4 * 32 * ES * 4 > 32768 ? 4 * 32 * ES * 4 : 32768];
+  u32x4(*sA)[8][64] = (u32x4(*)[8][64])smem;               // [stage][tile][lane]
+  u32x4(*sB)[8][64] = (u32x4(*)[8][64])(smem + 16384);
+  float(*sE)[32][ES] = (float(*)[32][ES])smem;             // [wavefront][row][column], after the K loop
+
+  const uint32_t RT = (rows + 127) / 128, total = RT * NT, per = (total + 7) / 8;
+  const uint32_t vid = (blockIdx.x % 8) * per + blockIdx.x / 8;
+  if (vid >= total) return;
+  const uint32_t nfull = RT / HB;
+  uint32_t rt, nt;
+  if (vid < nfull * HB * NT) {
+    const uint32_t band = vid / (HB * NT), rem = vid % (HB * NT);
+    nt = rem / HB;
+    rt = band * HB + rem % HB;
+  } else {
+    const uint32_t rem = vid - nfull * HB * NT, cnt = RT - nfull * HB;
+    nt = rem / cnt;
+    rt = nfull * HB + rem % cnt;
+  }
+  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64, jl = lane % 16, kg = lane / 16;
+  const int wr = wave / 2, wc = wave % 2;
+  const uint32_t r0 = rt * 128, KT = K / 32;
+
+  // this thread's two chunks of the A tiles and of the B tiles of a K step: tiles wave and wave + 4
+  const uint16_t* pa[2];
+  const u32x4* pb[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const uint32_t tile = wave + 4 * j;
+    if (XT) {
+      const uint32_t g = min(r0 / 32 + tile / 2, (rows + 31) / 32 - 1);   // row groups past the end: a valid one
+      pa[j] = x + (((size_t)g * KT * 2 + tile % 2) * 64 + lane) * 8;
+    } else {
+      const uint32_t r = min(r0 + tile * 16 + jl, rows - 1);
+      pa[j] = x + (size_t)r * K + kg * 8;
+    }
+    if (SWIGLU) pb[j] = ((tile % 2) ? w2 : w) + (size_t)(nt * 4 + tile / 2) * KT * 64 + lane;
+    else pb[j] = w + (size_t)(nt * 8 + tile) * KT * 64 + lane;
+  }
+  constexpr size_t astep = XT ? 128 * 8 : 32;
+
+  f32x4 acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  u32x4 ga[2], gb[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    ga[j] = *(const u32x4*)pa[j];
+    gb[j] = *pb[j];
+  }
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    sA[0][wave + 4 * j][lane] = ga[j];
+    sB[0][wave + 4 * j][lane] = gb[j];
+  }
+  __syncthreads();
+  for (uint32_t kt = 0; kt < KT; ++kt) {
+    const int st = kt & 1;
+    const bool more = kt + 1 < KT;
+    if (more) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        ga[j] = *(const u32x4*)(pa[j] + (size_t)(kt + 1) * astep);
+        gb[j] = pb[j][(size_t)(kt + 1) * 64];
+      }
+    }
+    bf16x8 a[4], b[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      a[i] = __builtin_bit_cast(bf16x8, sA[st][4 * wr + i][lane]);
+      b[i] = __builtin_bit_cast(bf16x8, sB[st][4 * wc + i][lane]);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    if (more) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        sA[st ^ 1][wave + 4 * j][lane] = ga[j];
+        sB[st ^ 1][wave + 4 * j][lane] = gb[j];
+      }
+    }
+    __syncthreads();
+  }
+
+  // Output, 32 rows of every wavefront at a time.  Accumulator element v of a lane: token row 4 * kg + v of
+  // row tile i, column jl of B tile j.  Staging columns: plain, B tile j at 16 * j; SwiGLU, B tile
+  // j = 2 * f + matrix at 32 * matrix + 16 * f (gate columns 0..31, up columns 32..63).
+#pragma unroll
+  for (int hf = 0; hf < 2; ++hf) {
+    if (hf) __syncthreads();
+#pragma unroll
+    for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int col = SWIGLU ? 32 * (j % 2) + 16 * (j / 2) + jl : 16 * j + jl;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) sE[wave][16 * ii + 4 * kg + v][col] = acc[2 * hf + ii][j][v];
+      }
+    __syncthreads();
+    const int cc = lane % 8;
+    if (!SWIGLU || cc < 4) {
+#pragma unroll
+      for (int ps = 0; ps < 4; ++ps) {
+        const int rr = ps * 8 + lane / 8;
+        const uint32_t row = r0 + wr * 64 + hf * 32 + rr;
+        if (row < rows) {
+          float y[8];
+          *(f32x4*)&y[0] = *(const f32x4*)&sE[wave][rr][8 * cc];
+          *(f32x4*)&y[4] = *(const f32x4*)&sE[wave][rr][8 * cc + 4];
+          const uint32_t n = nt * BNF + (SWIGLU ? wc * 32 : wc * 64) + 8 * cc;
+          const int which = n >= dst.start[2] ? 2 : n >= dst.start[1] ? 1 : 0;
+          const uint32_t width = dst.start[which + 1] - dst.start[which], col = n - dst.start[which];
+          const size_t oo = (size_t)row * width + col;
+          if (SWIGLU) {
+            float u[8];
+            *(f32x4*)&u[0] = *(const f32x4*)&sE[wave][rr][32 + 8 * cc];
+            *(f32x4*)&u[4] = *(const f32x4*)&sE[wave][rr][32 + 8 * cc + 4];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) y[e] = y[e] / (1.0f + __expf(-y[e])) * u[e];
+          } else if (residual) {
+            float rv[8];
+            unpack16<BF16>(*(const u32x4*)(residual + oo), rv);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) y[e] += rv[e];
+          }
+          const u32x4 o = pack16_round<BF16>(y);
+          if (out_tiled) ((u32x4*)dst.ptr[which])[tiled_chunk(row, col, width)] = o;
+          else *(u32x4*)(dst.ptr[which] + oo) = o;
+        }
+      }
+    }
+  }
+}
+
 // One workgroup per row; a thread keeps its (up to eight) 16-byte chunks of the row in registers between
 // the sum of squares and the scaling, so the row is read once.
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const uint16_t* x, const uint16_t* gain, uint16_t* out,
@@ -305,6 +465,26 @@ static void launch_linear_w(const void* x, const void* w, const void* residual, 
                        K, 0u);
 }
 
+// Many rows: the matrix-core kernel, for shapes its 128-feature (SwiGLU: 64) workgroup tiles cover exactly.
+static bool rows_kernel_fits(uint32_t rows, uint32_t N, bool swiglu) {
+  return rows >= 128 && N % (swiglu ? 64u : 128u) == 0;
+}
+
+template <bool SWIGLU>
+static void launch_rows(const void* x, const void* w, const void* w2, const void* residual, const LinearOut& dst,
+                        uint32_t rows, uint32_t K, uint32_t N, uint32_t flags, void* hip_stream) {
+  const uint32_t NT = N / (SWIGLU ? 64u : 128u), RT = (rows + 127) / 128;
+  const dim3 grid(8 * ((RT * NT + 7) / 8)), block(256);
+  const uint32_t ot = flags & BCTM_OUT_TILED ? 1u : 0u;
+  if (flags & BCTM_X_TILED)
+    hipLaunchKernelGGL((linear_rows_kernel<SWIGLU, true>), grid, block, 0, (hipStream_t)hip_stream, (const uint16_t*)x,
+                       (const u32x4*)w, (const u32x4*)w2, (const uint16_t*)residual, dst, rows, K, NT, ot);
+  else
+    hipLaunchKernelGGL((linear_rows_kernel<SWIGLU, false>), grid, block, 0, (hipStream_t)hip_stream,
+                       (const uint16_t*)x, (const u32x4*)w, (const u32x4*)w2, (const uint16_t*)residual, dst, rows, K,
+                       NT, ot);
+}
+
 template <int WV, int UN, int FT>
 static void launch_swiglu_w(const void* x, const void* wg, const void* wu, const LinearOut& dst, uint32_t rows,
                             uint32_t K, uint32_t N, uint32_t flags, void* hip_stream) {
@@ -374,7 +554,8 @@ static bct_status launch_linear(const void* x, const void* w, const void* residu
                                 uint32_t rows, uint32_t K, uint32_t N, uint32_t flags, void* hip_stream) {
   // Measured at 32 rows (weights in TB/s): K = 4096, N = 4096 / 12288: 16 wavefronts, one feature tile
   // 3.6 / 4.0 against 2.8 / 3.8 for two tiles (too few workgroups); N = 32000: two tiles 5.0 against 4.3.
-  if (N >= 16384 && N % 32 == 0) launch_linear_w<8, 4, 2>(x, w, residual, dst, rows, K, N, flags, hip_stream);
+  if (rows_kernel_fits(rows, N, false)) launch_rows<false>(x, w, nullptr, residual, dst, rows, K, N, flags, hip_stream);
+  else if (N >= 16384 && N % 32 == 0) launch_linear_w<8, 4, 2>(x, w, residual, dst, rows, K, N, flags, hip_stream);
   else launch_linear_w<16, 8, 1>(x, w, residual, dst, rows, K, N, flags, hip_stream);
   return launched("linear");
 }
@@ -418,7 +599,8 @@ bct_status bctm_swiglu(const void* x, const void* w_gate, const void* w_up, void
     return mfail(BCT_ERR_UNSUPPORTED, "tiled activations need a multiple of 32 columns");
   if (!al16(w_up)) return mfail(BCT_ERR_MISALIGNED, "pointers must be 16-byte aligned");
   const LinearOut dst = {{(uint16_t*)out, nullptr, nullptr}, {0u, N, N, N}};
-  launch_swiglu_w<4, 8, 1>(x, w_gate, w_up, dst, rows, K, N, flags, hip_stream);   // 36 us at 4096 -> 11008 (8 wavefronts: 38)
+  if (rows_kernel_fits(rows, N, true)) launch_rows<true>(x, w_gate, w_up, nullptr, dst, rows, K, N, flags, hip_stream);
+  else launch_swiglu_w<4, 8, 1>(x, w_gate, w_up, dst, rows, K, N, flags, hip_stream);   // 36 us at 4096 -> 11008 (8 wavefronts: 38)
   return launched("swiglu");
 }
 

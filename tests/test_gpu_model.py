@@ -61,6 +61,70 @@ def test_linear(M, rows, K, N, with_res):
     check_close(host(out), R.linear(x, w, res), 2.0 ** -20 * mass, f"linear {rows}x{K}x{N}")
 
 
+# Many rows (a prefill chunk): the 128 x 128 matrix-core kernel.  Ragged row counts, several row bands,
+# one K step and many, feature counts that make the last XCD round partial.
+ROWS_SHAPES = [(128, 32, 128), (130, 320, 256), (257, 4096, 384), (300, 96, 128), (1100, 64, 640), (129, 2336, 1152)]
+
+
+@pytest.mark.parametrize("rows,K,N", ROWS_SHAPES)
+@pytest.mark.parametrize("with_res", [False, True])
+@pytest.mark.parametrize("tiled", [False, True])
+def test_linear_many_rows(M, rows, K, N, with_res, tiled):
+    x, w = draw(1, (rows, K)), draw(2, (N, K), K ** -0.5)
+    res = draw(3, (rows, N)) if with_res else None
+    xin = M.bctm_pack_rows(dev(x)) if tiled else dev(x)
+    out = M.bctm_linear(xin, M.bctm_pack_weight(dev(w)), dev(res) if with_res else None)
+    mass = np.abs(R.bf16_to_f64(x)) @ np.abs(R.bf16_to_f64(w)).T
+    check_close(host(out), R.linear(x, w, res), 2.0 ** -20 * mass, f"linear {rows}x{K}x{N}")
+
+
+def test_linear_many_rows_selects_the_right_operands(M):
+    # one-hot weight rows pick input features, distinct per output feature and row: exact
+    rows, K, N = 200, 256, 256
+    x = draw(4, (rows, K))
+    sel = (np.arange(N) * 37 + 5) % K
+    w = np.zeros((N, K), dtype=np.float32)
+    w[np.arange(N), sel] = 1.0
+    wb = (w.view(np.uint32) >> 16).astype(np.uint16)
+    for xin in (dev(x), M.bctm_pack_rows(dev(x))):
+        out = host(M.bctm_linear(xin, M.bctm_pack_weight(dev(wb))))
+        assert np.array_equal(out, x[:, sel])
+
+
+def test_linear_many_rows_in_place_residual_and_split(M):
+    import torch
+    rows, K = 150, 192
+    x, res = draw(1, (rows, K)), draw(3, (rows, 256))
+    w = draw(2, (256, K), K ** -0.5)
+    buf = dev(res)
+    M.bctm_linear(dev(x), M.bctm_pack_weight(dev(w)), buf, buf)
+    mass = np.abs(R.bf16_to_f64(x)) @ np.abs(R.bf16_to_f64(w)).T
+    check_close(host(buf), R.linear(x, w, res), 2.0 ** -20 * mass, "in place, many rows")
+    # three outputs whose borders fall inside a workgroup's 128 features
+    widths = (144, 48, 64)
+    ws = [draw(20 + i, (n, K), K ** -0.5) for i, n in enumerate(widths)]
+    outs = [torch.zeros((rows, n), dtype=torch.bfloat16, device="cuda") for n in widths]
+    M.bctm_linear_split(M.bctm_pack_rows(dev(x)), M.bctm_pack_weight(*[dev(a) for a in ws]), outs)
+    for o, wi in zip(outs, ws):
+        m = np.abs(R.bf16_to_f64(x)) @ np.abs(R.bf16_to_f64(wi)).T
+        check_close(host(o), R.linear(x, wi, None), 2.0 ** -20 * m, "split, many rows")
+
+
+@pytest.mark.parametrize("rows,K,N", [(128, 64, 64), (200, 544, 192), (260, 4096, 320)])
+def test_swiglu_many_rows(M, rows, K, N):
+    x, wg, wu = draw(5, (rows, K)), draw(6, (N, K), 2.0 * K ** -0.5), draw(7, (N, K), K ** -0.5)
+    pg, pu = M.bctm_pack_weight(dev(wg)), M.bctm_pack_weight(dev(wu))
+    out = M.bctm_swiglu(dev(x), pg, pu)
+    xa = np.abs(R.bf16_to_f64(x))
+    g, u = R.linear_f64(x, wg), R.linear_f64(x, wu)
+    mg, mu = xa @ np.abs(R.bf16_to_f64(wg)).T, xa @ np.abs(R.bf16_to_f64(wu)).T
+    slack = 2.0 ** -20 * (1.1 * mg * np.abs(u) + (np.abs(g) + 1.0) * mu + np.abs(g * u))
+    check_close(host(out), R.swiglu(x, wg, wu), slack, f"swiglu {rows}x{K}x{N}")
+    if N % 32 == 0:
+        t = M.bctm_swiglu(M.bctm_pack_rows(dev(x)), pg, pu, tiled=True)
+        assert np.array_equal(untile(t, rows, N), host(out))
+
+
 def tiled_offsets(rows, K):
     """bf16 offset of element (r, k) in the tiled activation layout, written out from its definition."""
     r, k = np.meshgrid(np.arange(rows), np.arange(K), indexing="ij")
