@@ -84,12 +84,39 @@ def full_stack(w, L, steps, warmup, attention_ms_per_step):
                "layers": [{n: (mat(shp) if len(shp) == 2 else mat(shp, 0.0, 1.0)) for n, shp in s.weight_shapes().items()}
                           for _ in range(L)],
                "keys": [mat((s.n_kv_heads, s.capacity_M, s.head_dim), 1.0) for _ in range(L)]}
-    stack = M.BctStack(s, weights, device=dev)
+    T = w.prefill_chunk if w.prompt else 0
+    stack = M.BctStack(s, weights, max_prefill_T=T, device=dev)
     del weights
     torch.cuda.synchronize()
     torch.cuda.empty_cache()
     log(f"full stack: {s.weight_bytes() / 2**30:.1f} GiB of weights packed in {time.perf_counter() - t0:.1f} s")
     ids = torch.randint(0, s.vocab, (s.batch,), generator=g, device=dev, dtype=torch.int32)
+    prompt = None
+    if T:
+        # the prompt through the whole model, chunk by chunk (projections in the matrix-core kernel, attention
+        # in bct_prefill), the head on each sequence's last token only; one warm-up chunk, then MV back to 0
+        n_chunks = w.prompt // T
+        pids = torch.randint(0, s.vocab, (n_chunks, s.batch * T), generator=g, device=dev, dtype=torch.int32)
+        stack.forward(pids[0], T=T, next_ids=ids, head="last")
+        for c in stack.caches:
+            c.set_values(None)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(n_chunks):
+            stack.forward(pids[k], T=T, next_ids=ids, head="last")
+        torch.cuda.synchronize()
+        pms = (time.perf_counter() - t0) * 1e3
+        rows = s.batch * w.prompt
+        per_layer = sum(a * b for (a, b) in (shp for shp in s.weight_shapes().values() if len(shp) == 2))
+        proj_flops = 2.0 * rows * per_layer * L
+        units = s.batch * s.n_kv_heads
+        G = s.n_q_heads // s.n_kv_heads
+        attn_flops = units * 2.0 * T * s.capacity_M * s.head_dim * ((1 + G) + 1 + G + G * 128.0 / s.head_dim) * n_chunks * L
+        prompt = {"ms": pms, "tokens_per_s": rows / (pms * 1e-3), "chunk_T": T, "chunks": n_chunks,
+                  "projection_flops": proj_flops, "attention_flops": attn_flops,
+                  "TFLOP/s": (proj_flops + attn_flops) / (pms * 1e-3) / 1e12,
+                  "frac_of_mfma_peak": (proj_flops + attn_flops) / (pms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TF}
+        log(f"full stack: prompt of {w.prompt} tokens x {s.batch} sequences in {pms:.1f} ms")
     for _ in range(warmup):
         stack.forward(ids, next_ids=ids)
     torch.cuda.synchronize()
@@ -119,7 +146,7 @@ def full_stack(w, L, steps, warmup, attention_ms_per_step):
                      f"bf16 weights N(0, 0.02), greedy decoding from random ids",
             "glue_ms_per_step": glue_ms, "weight_bytes_per_step": wbytes,
             "glue_GB/s": wbytes / (glue_ms * 1e-3) / 1e9 if glue_ms > 0 else None,
-            "attention_share": attention_ms_per_step / ms}
+            "attention_share": attention_ms_per_step / ms, "prompt": prompt}
 
 
 def main():

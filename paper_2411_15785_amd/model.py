@@ -351,20 +351,28 @@ class BctStack:
             self._bufs[k] = TiledRows(rows, cols, self.device)
         return self._bufs[k]
 
-    def forward(self, ids, T=1, next_ids=None):
-        """ids int32 [B*T] (sequence-major: row b*T + t) -> (next ids int32 [B*T], logits [B*T][vocab]).
+    def forward(self, ids, T=1, next_ids=None, head="all"):
+        """ids int32 [B*T] (sequence-major: row b*T + t) -> (next ids, logits).
         T = 1 is a decode step; T > 1 pushes a chunk of T tokens per sequence through bct_prefill.
+        head = "all": logits [B*T][vocab] and greedy ids [B*T] for every row; head = "last": only for the last
+        token of every sequence ([B][vocab], [B]) - what a prompt needs, without a [B*T][vocab] product.
         next_ids: where to write the greedy tokens (may be ids itself: it is read first, written last).
-        After the first call of a given (B, T) no memory is allocated, so a call can be captured in a HIP graph."""
+        After the first call of a given (B, T, head) no memory is allocated, so a call can be captured in a
+        HIP graph."""
         s = self.shape
         rows = s.batch * T
         if ids.numel() != rows:
             raise ValueError(f"ids: expected {rows} entries")
+        if head not in ("all", "last"):
+            raise ValueError('head: "all" or "last"')
         x = bctm_embed(ids, self.embed, self._buf("x", rows, s.dim))
         # every input of a projection is kept tiled, so that the projections read it in whole kilobytes
         h, f = self._tiled("h", rows, s.dim), self._tiled("f", rows, s.ffn)
         q, wq, wv = self._buf("q", rows, s.q_width), self._buf("wq", rows, s.kv_width), self._buf("wv", rows, s.kv_width)
         a = self._buf("a", rows, s.q_width)
+        # a chunk's attention output is re-tiled for W_o (the matrix-core kernel reads whole tiles); for the
+        # few rows of a decode step re-tiling would cost more than it saves
+        at = self._tiled("a", rows, s.q_width) if rows >= 128 else None
         for l, lw in enumerate(self.layers):
             bctm_rmsnorm(x, lw["attn_norm"], s.eps, h, tiled=True)
             bctm_linear_split(h, lw["w_qkv"], (q, wq, wv))
@@ -377,10 +385,19 @@ class BctStack:
                 c.prefill(q.view(s.batch, T, s.n_q_heads, s.head_dim), wq.view(s.batch, T, s.n_kv_heads, s.head_dim),
                           wv.view(s.batch, T, s.n_kv_heads, s.head_dim), T,
                           a.view(s.batch, T, s.n_q_heads, s.head_dim))
-            bctm_linear(a, lw["w_o"], x, x)     # row-major: re-tiling a would cost more than it saves
+            bctm_linear(bctm_pack_rows(a, at) if at is not None else a, lw["w_o"], x, x)
             bctm_rmsnorm(x, lw["mlp_norm"], s.eps, h, tiled=True)
             bctm_swiglu(h, lw["w_gate"], lw["w_up"], f, tiled=True)
             bctm_linear(f, lw["w_down"], x, x)
+        if head == "last" and T > 1:
+            # rows b*T + T-1, gathered with the embedding kernel (a row lookup) from x as the table
+            torch = _torch()
+            k = ("last_rows", s.batch, T)
+            if k not in self._bufs:
+                self._bufs[k] = (torch.arange(s.batch, dtype=torch.int32, device=self.device) * T + (T - 1)).contiguous()
+            x = bctm_embed(self._bufs[k], x, self._buf("x_last", s.batch, s.dim))
+            rows = s.batch
+            h = self._tiled("h_last", rows, s.dim)
         bctm_rmsnorm(x, self.final_norm, s.eps, h, tiled=True)
         logits = bctm_linear(h, self.head, None, self._buf("logits", rows, s.vocab))
         nxt = bctm_argmax(logits, next_ids)

@@ -328,3 +328,29 @@ def test_stack_prefill_then_decode(M):
         r_ids, r_lg = ref.forward(ids)
         g_ids, g_lg = gpu.forward(torch.from_numpy(ids).cuda())
         check_logits(host(g_lg), r_lg, g_ids.cpu().numpy(), r_ids, 2e-2, f"decode {t}")
+
+
+def test_stack_long_chunk_through_the_many_rows_kernels(M):
+    """A chunk of 3 x 70 = 210 rows: every projection runs in the matrix-core kernel (row-major W_o input
+    re-tiled first), the attention in bct_prefill; logits of all rows, then of the last token only on a second
+    stack (same weights, same chunk), then a decode step on the state the chunk left."""
+    import torch
+    s = M.StackShape(n_layers=2, dim=256, n_q_heads=4, n_kv_heads=2, head_dim=64, ffn=704, vocab=512,
+                     capacity_M=128, batch=3)
+    T = 70
+    ref, gpu = stack_pair(M, s, seed=6, max_prefill_T=T)
+    _, gpu2 = stack_pair(M, s, seed=6, max_prefill_T=T)
+    ids = syn.make_token_ids(6, 0, s.batch * T, s.vocab)
+    r_ids, r_lg = ref.forward(ids, T=T)
+    g_ids, g_lg = gpu.forward(torch.from_numpy(ids).cuda(), T=T)
+    check_logits(host(g_lg), r_lg, g_ids.cpu().numpy(), r_ids, 2e-2, "chunk, all rows")
+    l_ids, l_lg = gpu2.forward(torch.from_numpy(ids).cuda(), T=T, head="last")
+    last = np.arange(s.batch) * T + T - 1
+    assert l_lg.shape == (s.batch, s.vocab) and l_ids.shape == (s.batch,)
+    assert np.array_equal(host(l_lg), host(g_lg)[last])          # the same kernels on the same rows
+    assert np.array_equal(l_ids.cpu().numpy(), g_ids.cpu().numpy()[last])
+    ids1 = syn.make_token_ids(6, 1, s.batch, s.vocab)
+    r_ids, r_lg = ref.forward(ids1)
+    for g in (gpu, gpu2):
+        g_ids, g_lg = g.forward(torch.from_numpy(ids1).cuda())
+        check_logits(host(g_lg), r_lg, g_ids.cpu().numpy(), r_ids, 2e-2, "decode after the chunk")
