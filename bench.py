@@ -158,6 +158,7 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (0 = the workload's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefill", action="store_true", help="start decoding from MV_0 = 0, without the prompt")
+    ap.add_argument("--no-copy-ceiling", action="store_true", help="skip timing the plain copy kernel")
     ap.add_argument("--no-full-stack", action="store_true",
                     help="skip the leg that decodes through the whole Llama-shaped model (cfg3 only)")
     args = ap.parse_args()
@@ -274,7 +275,7 @@ def main():
     # The practical ceiling for a 1:1 read/write stream: the library's plain copy kernel, in place,
     # on a buffer of MV's size, timed in this same run.
     copy = None
-    if mv_bytes >= (64 << 20):
+    if mv_bytes >= (64 << 20) and not args.no_copy_ceiling:
         import ctypes
         buf = torch.empty(mv_bytes, dtype=torch.uint8, device=dev)
         bp, sp = ctypes.c_void_p(buf.data_ptr()), ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
