@@ -354,3 +354,24 @@ def test_stack_long_chunk_through_the_many_rows_kernels(M):
     for g in (gpu, gpu2):
         g_ids, g_lg = g.forward(torch.from_numpy(ids1).cuda())
         check_logits(host(g_lg), r_lg, g_ids.cpu().numpy(), r_ids, 2e-2, "decode after the chunk")
+
+
+def test_stack_one_layer_at_the_7b_shape(M):
+    """One layer at the full Llama-7B widths of the third workload (d_model 4096, ffn 11008, vocab 32000,
+    32 heads of 128, M = 4096, batch 32): an 8-token chunk (256 rows: every projection, the 12288-, 11008-
+    and 32000-wide ones included, in the many-rows kernel) and a decode step (the streaming kernels) against
+    the oracle.  The oracle needs about 40 s for this."""
+    import torch
+    s = M.StackShape(n_layers=1, dim=4096, n_q_heads=32, n_kv_heads=32, head_dim=128, ffn=11008, vocab=32000,
+                     capacity_M=4096, batch=32)
+    T = 8
+    ref, gpu = stack_pair(M, s, seed=9, max_prefill_T=T)
+    ids = syn.make_token_ids(9, 1, s.batch * T, s.vocab)
+    r_ids, r_lg = ref.forward(ids, T=T)
+    g_ids, g_lg = gpu.forward(torch.from_numpy(ids).cuda(), T=T)
+    n_clear = check_logits(host(g_lg), r_lg, g_ids.cpu().numpy(), r_ids, 2e-2, "chunk at the 7B shape")
+    ids = syn.make_token_ids(9, 0, s.batch, s.vocab)
+    r_ids, r_lg = ref.forward(ids)
+    g_ids, g_lg = gpu.forward(torch.from_numpy(ids).cuda())
+    n_clear += check_logits(host(g_lg), r_lg, g_ids.cpu().numpy(), r_ids, 2e-2, "decode step at the 7B shape")
+    assert n_clear >= 32
