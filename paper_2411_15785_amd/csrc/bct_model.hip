@@ -182,32 +182,42 @@ __global__ __launch_bounds__(64 * WAVES) void linear_kernel(const uint16_t* __re
 }
 
 // The same projections for MANY token rows (a prefill chunk: batch x T rows), where the product is a
-// dense contraction bound by the matrix cores and no longer by streaming the weights.  A workgroup of four
-// wavefronts owns 128 token rows x 128 output features (SwiGLU: 64 features of both matrices), each
-// wavefront 64 x 64 of it as 4 x 4 accumulators of v_mfma_f32_16x16x32_bf16.  Both operands are already
-// stored in MFMA operand order (packed weights, tiled activations), so a K step of 32 inputs is 16 one-KB
-// tiles that the workgroup copies to LDS unchanged (linear 16-byte accesses on both sides) and every
-// wavefront reads back its four row tiles and four feature tiles; the loads of the next K step are in
-// flight in registers while the current one is multiplied (two LDS stages, one barrier per K step).
-// Workgroups are numbered so that the 64 of them resident on one XCD at a time (every eighth workgroup id)
-// form 8 row tiles x 8 feature tiles: each operand panel is fetched into that XCD's L2 once for eight uses.
-// Output: the accumulators go through LDS (fp32) and leave as 16-byte row-contiguous chunks, with the
-// residual added / the SwiGLU applied in fp32 before the one rounding to bf16.
-template <bool SWIGLU, bool XT>
-__global__ __launch_bounds__(256, 2) void linear_rows_kernel(const uint16_t* __restrict__ x,
-                                                             const u32x4* __restrict__ w,
-                                                             const u32x4* __restrict__ w2, const uint16_t* residual,
-                                                             LinearOut dst, uint32_t rows, uint32_t K, uint32_t NT,
-                                                             uint32_t out_tiled) {
+// dense contraction bound by the matrix cores and no longer by streaming the weights.  A workgroup of
+// 2 x WC wavefronts owns 32 * MI token rows x 64 * WC output features (SwiGLU: 32 * WC features of both
+// matrices), each wavefront 16 * MI x 64 of it as MI x 4 accumulators of v_mfma_f32_16x16x32_bf16; built as
+// 128 x 128 (MI 4, WC 2) and 256 x 256 (MI 8, WC 4).  Both operands are already stored in MFMA operand
+// order (packed weights, tiled activations), so a K step of 32 inputs is a set of one-KB tiles that the
+// workgroup copies to LDS unchanged (linear 16-byte accesses on both sides) and every wavefront reads back
+// its MI row tiles and four feature tiles; the loads of the next K step are in flight in registers while the
+// current one is multiplied (two LDS stages, one barrier per K step).
+// Workgroups are numbered so that those resident on one XCD at a time (every eighth workgroup id) cover
+// 8 row tiles x consecutive feature tiles: each operand panel is fetched into that XCD's L2 once for
+// eight uses.  Output: the accumulators go through LDS (fp32) and leave as 16-byte row-contiguous chunks,
+// with the residual added / the SwiGLU applied in fp32 before the one rounding to bf16.
+template <bool SWIGLU, bool XT, int MI, int WC>
+__global__ __launch_bounds__(128 * WC, 2) void linear_rows_kernel(const uint16_t* __restrict__ x,
+                                                                  const u32x4* __restrict__ w,
+                                                                  const u32x4* __restrict__ w2,
+                                                                  const uint16_t* residual, LinearOut dst,
+                                                                  uint32_t rows, uint32_t K, uint32_t NT,
+                                                                  uint32_t out_tiled) {
+  // 2 x WC wavefronts; a wavefront owns MI row tiles x 4 feature tiles (of 16 each)
+  constexpr int NW = 2 * WC;                       // wavefronts
+  constexpr int TA = 2 * MI, TB = 4 * WC;          // 1 KB tiles of a K step: activations, weights
+  constexpr int NA = TA / NW, NB = TB / NW;        // of them per thread
+  static_assert(TA % NW == 0 && TB % NW == 0, "tiles must divide among the wavefronts");
   constexpr uint32_t HB = 8;                       // row tiles of a band
-  constexpr uint32_t BNF = SWIGLU ? 64 : 128;      // output features of a workgroup
+  constexpr uint32_t BM = 32 * MI;                 // token rows of a workgroup
+  constexpr uint32_t BNF = (SWIGLU ? 32 : 64) * WC;  // output features of a workgroup
   constexpr int ES = 68;                           // floats per row of the output staging (64 + pad)
-  __shared__ __attribute__((aligned(16))) unsigned char smem[4 * 32 * ES * 4 > 32768 ? 4 * 32 * ES * 4 : 32768];
-  u32x4(*sA)[8][64] = (u32x4(*)[8][64])smem;               // [stage][tile][lane]
-  u32x4(*sB)[8][64] = (u32x4(*)[8][64])(smem + 16384);
-  float(*sE)[32][ES] = (float(*)[32][ES])smem;             // [wavefront][row][column], after the K loop
+  constexpr int ER = NW > 4 ? 16 : 32;             // rows of a wavefront staged at a time
+  constexpr int kStage = (TA + TB) * 1024, kOut = NW * ER * ES * 4;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[2 * kStage > kOut ? 2 * kStage : kOut];
+  u32x4(*sA)[TA][64] = (u32x4(*)[TA][64])smem;             // [stage][tile][lane]
+  u32x4(*sB)[TB][64] = (u32x4(*)[TB][64])(smem + 2 * TA * 1024);
+  float(*sE)[ER][ES] = (float(*)[ER][ES])smem;             // [wavefront][row][column], after the K loop
 
-  const uint32_t RT = (rows + 127) / 128, total = RT * NT, per = (total + 7) / 8;
+  const uint32_t RT = (rows + BM - 1) / BM, total = RT * NT, per = (total + 7) / 8;
   const uint32_t vid = (blockIdx.x % 8) * per + blockIdx.x / 8;
   if (vid >= total) return;
   const uint32_t nfull = RT / HB;
@@ -222,15 +232,15 @@ __global__ __launch_bounds__(256, 2) void linear_rows_kernel(const uint16_t* __r
     rt = nfull * HB + rem % cnt;
   }
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64, jl = lane % 16, kg = lane / 16;
-  const int wr = wave / 2, wc = wave % 2;
-  const uint32_t r0 = rt * 128, KT = K / 32;
+  const int wr = wave / WC, wc = wave % WC;
+  const uint32_t r0 = rt * BM, KT = K / 32;
 
-  // this thread's two chunks of the A tiles and of the B tiles of a K step: tiles wave and wave + 4
-  const uint16_t* pa[2];
-  const u32x4* pb[2];
+  // this thread's chunks of a K step: tiles wave, wave + NW, ... of either operand
+  const uint16_t* pa[NA];
+  const u32x4* pb[NB];
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const uint32_t tile = wave + 4 * j;
+  for (int j = 0; j < NA; ++j) {
+    const uint32_t tile = wave + NW * j;
     if (XT) {
       const uint32_t g = min(r0 / 32 + tile / 2, (rows + 31) / 32 - 1);   // row groups past the end: a valid one
       pa[j] = x + (((size_t)g * KT * 2 + tile % 2) * 64 + lane) * 8;
@@ -238,80 +248,80 @@ __global__ __launch_bounds__(256, 2) void linear_rows_kernel(const uint16_t* __r
       const uint32_t r = min(r0 + tile * 16 + jl, rows - 1);
       pa[j] = x + (size_t)r * K + kg * 8;
     }
-    if (SWIGLU) pb[j] = ((tile % 2) ? w2 : w) + (size_t)(nt * 4 + tile / 2) * KT * 64 + lane;
-    else pb[j] = w + (size_t)(nt * 8 + tile) * KT * 64 + lane;
+  }
+#pragma unroll
+  for (int j = 0; j < NB; ++j) {
+    const uint32_t tile = wave + NW * j;
+    if (SWIGLU) pb[j] = ((tile % 2) ? w2 : w) + (size_t)(nt * (TB / 2) + tile / 2) * KT * 64 + lane;
+    else pb[j] = w + (size_t)(nt * TB + tile) * KT * 64 + lane;
   }
   constexpr size_t astep = XT ? 128 * 8 : 32;
 
-  f32x4 acc[4][4];
+  f32x4 acc[MI][4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < MI; ++i)
 #pragma unroll
     for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  u32x4 ga[2], gb[2];
+  u32x4 ga[NA], gb[NB];
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    ga[j] = *(const u32x4*)pa[j];
-    gb[j] = *pb[j];
-  }
+  for (int j = 0; j < NA; ++j) ga[j] = *(const u32x4*)pa[j];
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    sA[0][wave + 4 * j][lane] = ga[j];
-    sB[0][wave + 4 * j][lane] = gb[j];
-  }
+  for (int j = 0; j < NB; ++j) gb[j] = *pb[j];
+#pragma unroll
+  for (int j = 0; j < NA; ++j) sA[0][wave + NW * j][lane] = ga[j];
+#pragma unroll
+  for (int j = 0; j < NB; ++j) sB[0][wave + NW * j][lane] = gb[j];
   __syncthreads();
   for (uint32_t kt = 0; kt < KT; ++kt) {
     const int st = kt & 1;
     const bool more = kt + 1 < KT;
     if (more) {
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        ga[j] = *(const u32x4*)(pa[j] + (size_t)(kt + 1) * astep);
-        gb[j] = pb[j][(size_t)(kt + 1) * 64];
-      }
-    }
-    bf16x8 a[4], b[4];
+      for (int j = 0; j < NA; ++j) ga[j] = *(const u32x4*)(pa[j] + (size_t)(kt + 1) * astep);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      a[i] = __builtin_bit_cast(bf16x8, sA[st][4 * wr + i][lane]);
-      b[i] = __builtin_bit_cast(bf16x8, sB[st][4 * wc + i][lane]);
+      for (int j = 0; j < NB; ++j) gb[j] = pb[j][(size_t)(kt + 1) * 64];
     }
+    bf16x8 a[MI], b[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < MI; ++i) a[i] = __builtin_bit_cast(bf16x8, sA[st][MI * wr + i][lane]);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) b[i] = __builtin_bit_cast(bf16x8, sB[st][4 * wc + i][lane]);
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
       for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
     if (more) {
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        sA[st ^ 1][wave + 4 * j][lane] = ga[j];
-        sB[st ^ 1][wave + 4 * j][lane] = gb[j];
-      }
+      for (int j = 0; j < NA; ++j) sA[st ^ 1][wave + NW * j][lane] = ga[j];
+#pragma unroll
+      for (int j = 0; j < NB; ++j) sB[st ^ 1][wave + NW * j][lane] = gb[j];
     }
     __syncthreads();
   }
 
-  // Output, 32 rows of every wavefront at a time.  Accumulator element v of a lane: token row 4 * kg + v of
+  // Output, ER rows of every wavefront at a time.  Accumulator element v of a lane: token row 4 * kg + v of
   // row tile i, column jl of B tile j.  Staging columns: plain, B tile j at 16 * j; SwiGLU, B tile
   // j = 2 * f + matrix at 32 * matrix + 16 * f (gate columns 0..31, up columns 32..63).
+  constexpr int TPP = ER / 16;                     // row tiles per pass
 #pragma unroll
-  for (int hf = 0; hf < 2; ++hf) {
+  for (int hf = 0; hf < MI / TPP; ++hf) {
     if (hf) __syncthreads();
 #pragma unroll
-    for (int ii = 0; ii < 2; ++ii)
+    for (int ii = 0; ii < TPP; ++ii)
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const int col = SWIGLU ? 32 * (j % 2) + 16 * (j / 2) + jl : 16 * j + jl;
 #pragma unroll
-        for (int v = 0; v < 4; ++v) sE[wave][16 * ii + 4 * kg + v][col] = acc[2 * hf + ii][j][v];
+        for (int v = 0; v < 4; ++v) sE[wave][16 * ii + 4 * kg + v][col] = acc[TPP * hf + ii][j][v];
       }
     __syncthreads();
     const int cc = lane % 8;
     if (!SWIGLU || cc < 4) {
 #pragma unroll
-      for (int ps = 0; ps < 4; ++ps) {
+      for (int ps = 0; ps < ER / 8; ++ps) {
         const int rr = ps * 8 + lane / 8;
-        const uint32_t row = r0 + wr * 64 + hf * 32 + rr;
+        const uint32_t row = r0 + wr * (16 * MI) + hf * ER + rr;
         if (row < rows) {
           float y[8];
           *(f32x4*)&y[0] = *(const f32x4*)&sE[wave][rr][8 * cc];
@@ -470,19 +480,32 @@ static bool rows_kernel_fits(uint32_t rows, uint32_t N, bool swiglu) {
   return rows >= 128 && N % (swiglu ? 64u : 128u) == 0;
 }
 
+template <bool SWIGLU, int MI, int WC>
+static void launch_rows_shape(const void* x, const void* w, const void* w2, const void* residual,
+                              const LinearOut& dst, uint32_t rows, uint32_t K, uint32_t N, uint32_t flags,
+                              void* hip_stream) {
+  const uint32_t NT = N / ((SWIGLU ? 32u : 64u) * WC), RT = (rows + 32 * MI - 1) / (32 * MI);
+  const dim3 grid(8 * ((RT * NT + 7) / 8)), block(128 * WC);
+  const uint32_t ot = flags & BCTM_OUT_TILED ? 1u : 0u;
+  if (flags & BCTM_X_TILED)
+    hipLaunchKernelGGL((linear_rows_kernel<SWIGLU, true, MI, WC>), grid, block, 0, (hipStream_t)hip_stream,
+                       (const uint16_t*)x, (const u32x4*)w, (const u32x4*)w2, (const uint16_t*)residual, dst, rows, K,
+                       NT, ot);
+  else
+    hipLaunchKernelGGL((linear_rows_kernel<SWIGLU, false, MI, WC>), grid, block, 0, (hipStream_t)hip_stream,
+                       (const uint16_t*)x, (const u32x4*)w, (const u32x4*)w2, (const uint16_t*)residual, dst, rows, K,
+                       NT, ot);
+}
+
 template <bool SWIGLU>
 static void launch_rows(const void* x, const void* w, const void* w2, const void* residual, const LinearOut& dst,
                         uint32_t rows, uint32_t K, uint32_t N, uint32_t flags, void* hip_stream) {
-  const uint32_t NT = N / (SWIGLU ? 64u : 128u), RT = (rows + 127) / 128;
-  const dim3 grid(8 * ((RT * NT + 7) / 8)), block(256);
-  const uint32_t ot = flags & BCTM_OUT_TILED ? 1u : 0u;
-  if (flags & BCTM_X_TILED)
-    hipLaunchKernelGGL((linear_rows_kernel<SWIGLU, true>), grid, block, 0, (hipStream_t)hip_stream, (const uint16_t*)x,
-                       (const u32x4*)w, (const u32x4*)w2, (const uint16_t*)residual, dst, rows, K, NT, ot);
+  // 256 x 256 workgroups halve the LDS and L1 traffic per flop (measured +5..10 % at 16384 rows) but pad
+  // the rows to 256 and need a feature count they divide; smaller or odd shapes take 128 x 128
+  if (rows >= 1024 && N % (SWIGLU ? 128u : 256u) == 0)
+    launch_rows_shape<SWIGLU, 8, 4>(x, w, w2, residual, dst, rows, K, N, flags, hip_stream);
   else
-    hipLaunchKernelGGL((linear_rows_kernel<SWIGLU, false>), grid, block, 0, (hipStream_t)hip_stream,
-                       (const uint16_t*)x, (const u32x4*)w, (const u32x4*)w2, (const uint16_t*)residual, dst, rows, K,
-                       NT, ot);
+    launch_rows_shape<SWIGLU, 4, 2>(x, w, w2, residual, dst, rows, K, N, flags, hip_stream);
 }
 
 template <int WV, int UN, int FT>

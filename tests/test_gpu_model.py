@@ -63,7 +63,8 @@ def test_linear(M, rows, K, N, with_res):
 
 # Many rows (a prefill chunk): the 128 x 128 matrix-core kernel.  Ragged row counts, several row bands,
 # one K step and many, feature counts that make the last XCD round partial.
-ROWS_SHAPES = [(128, 32, 128), (130, 320, 256), (257, 4096, 384), (300, 96, 128), (1100, 64, 640), (129, 2336, 1152)]
+ROWS_SHAPES = [(128, 32, 128), (130, 320, 256), (257, 4096, 384), (300, 96, 128), (1100, 64, 640), (129, 2336, 1152),
+               (1100, 64, 768), (1024, 4096, 256), (2050, 96, 512)]   # the last three: 256 x 256 workgroups
 
 
 @pytest.mark.parametrize("rows,K,N", ROWS_SHAPES)
@@ -110,7 +111,7 @@ def test_linear_many_rows_in_place_residual_and_split(M):
         check_close(host(o), R.linear(x, wi, None), 2.0 ** -20 * m, "split, many rows")
 
 
-@pytest.mark.parametrize("rows,K,N", [(128, 64, 64), (200, 544, 192), (260, 4096, 320)])
+@pytest.mark.parametrize("rows,K,N", [(128, 64, 64), (200, 544, 192), (260, 4096, 320), (1030, 96, 384), (1300, 1024, 128)])
 def test_swiglu_many_rows(M, rows, K, N):
     x, wg, wu = draw(5, (rows, K)), draw(6, (N, K), 2.0 * K ** -0.5), draw(7, (N, K), K ** -0.5)
     pg, pu = M.bctm_pack_weight(dev(wg)), M.bctm_pack_weight(dev(wu))
