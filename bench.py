@@ -64,8 +64,9 @@ def cpu_baseline(w, seconds_budget=20.0):
 
 
 def full_stack(w, L, steps, warmup, attention_ms_per_step):
-    """Greedy decoding through the whole Llama-7B-shaped model: embedding, L x (RMSNorm, W_q / W_wq / W_wv,
-    bounded-cache attention, W_o, RMSNorm, SwiGLU MLP), RMSNorm, output head, arg-max, the next ids fed back.
+    """The whole Llama-7B-shaped model: embedding, L x (RMSNorm, W_q / W_wq / W_wv, bounded-cache attention,
+    W_o, RMSNorm, SwiGLU MLP), RMSNorm, output head, arg-max.  First the prompt, chunk by chunk, then greedy
+    decoding with the next ids fed back.
     Weights ~ N(0, 0.02) drawn on the device (their values do not change the cost); token ids start random."""
     import torch
 
