@@ -462,7 +462,7 @@ __global__ __launch_bounds__(512) void prefill_read_kernel(const PrefillParams p
 // ------------------------------------------------------------------ state
 
 // MV tile of 128 slots: acc = MV_start; tokens are walked 64 at a time; at the
-// start of every sub-chunk c >= 1 (if reads follow) round(acc) is left as MV_c;
+// start of every sub-chunk c (if reads follow) round(acc) is left as MV_c;
 // acc += WW^T . WV; finally MV = round(acc).  The write weights are recomputed
 // per token tile and never leave the registers: a wavefront owns 32 slots and
 // all d value columns.  Its score product has rows = tokens, columns = slots, so
@@ -539,8 +539,9 @@ __global__ __launch_bounds__(256, 2) void prefill_state_kernel(const PrefillPara
   fetch_tokens(0);
   for (uint32_t tt = 0; tt < ntile; ++tt) {
     const uint32_t t0 = tt * TT;
-    if (p.has_read && tt > 0 && (t0 % kTC) == 0) {
-      // MV at the start of sub-chunk c, transposed ([column][slot]) for the read kernel.  A lane holds
+    if (p.has_read && (t0 % kTC) == 0) {
+      // MV at the start of sub-chunk c (c = 0: the tile just loaded, which saves a transposing pass over
+      // MV of its own), transposed ([column][slot]) for the read kernel.  A lane holds
       // 4 consecutive slots of one column, and columns are M elements apart in memory, so the tile
       // goes through LDS (in place of the token tiles, which nobody reads any more) and leaves in
       // whole 256-byte rows.
@@ -644,7 +645,8 @@ hipError_t launch_prefill_bf16(const PrefillParams& p0, hipStream_t s) {
     return hipGetLastError();
   };
   if (p.has_write && (e = transpose(0)) != hipSuccess) return e;
-  if (p.has_read && (e = transpose(1)) != hipSuccess) return e;
+  // with a write, the state kernel leaves MV_0 transposed as the first snapshot on its way through
+  if (p.has_read && !p.has_write && (e = transpose(1)) != hipSuccess) return e;
 
   const dim3 gs((rows + kTC - 1) / kTC, units);
   if (d128) hipLaunchKernelGGL(prefill_stats_kernel<128>, gs, dim3(512), 0, s, p);
