@@ -376,3 +376,29 @@ def test_stack_one_layer_at_the_7b_shape(M):
     g_ids, g_lg = gpu.forward(torch.from_numpy(ids).cuda())
     n_clear += check_logits(host(g_lg), r_lg, g_ids.cpu().numpy(), r_ids, 2e-2, "decode step at the 7B shape")
     assert n_clear >= 32
+
+
+@pytest.mark.parametrize("case", range(12))
+def test_projection_shapes_drawn_at_random(M, case):
+    """Seeded sweep over row counts on both sides of the 128- and 1024-row dispatch borders, K of one to 40
+    steps, feature counts that select the streaming kernel, the 128 x 128 or the 256 x 256 workgroups."""
+    rng = np.random.default_rng(1000 + case)
+    rows = [int(rng.integers(1, 128)), int(rng.integers(128, 1024)), int(rng.integers(1024, 1600))][case % 3]
+    K = 32 * int(rng.integers(1, 41))
+    N = [64, 256, 128, 256][case % 4] * int(rng.integers(1, 5)) if case % 5 else 16 * int(rng.integers(1, 20))
+    tiled, with_res = bool(rng.integers(2)), bool(rng.integers(2))
+    x, w = draw(30 + case, (rows, K)), draw(50 + case, (N, K), K ** -0.5)
+    res = draw(70 + case, (rows, N)) if with_res else None
+    xin = M.bctm_pack_rows(dev(x)) if tiled else dev(x)
+    out = M.bctm_linear(xin, M.bctm_pack_weight(dev(w)), dev(res) if with_res else None)
+    mass = np.abs(R.bf16_to_f64(x)) @ np.abs(R.bf16_to_f64(w)).T
+    check_close(host(out), R.linear(x, w, res), 2.0 ** -20 * mass, f"linear {rows}x{K}x{N} tiled={tiled} res={with_res}")
+    if N % 2 == 0 and (N // 2) % 16 == 0:
+        # the same weights as gate | up halves of a SwiGLU
+        wg, wu = w[: N // 2], w[N // 2:]
+        o2 = M.bctm_swiglu(xin, M.bctm_pack_weight(dev(wg)), M.bctm_pack_weight(dev(wu)))
+        xa = np.abs(R.bf16_to_f64(x))
+        g, u = R.linear_f64(x, wg), R.linear_f64(x, wu)
+        mg, mu = xa @ np.abs(R.bf16_to_f64(wg)).T, xa @ np.abs(R.bf16_to_f64(wu)).T
+        slack = 2.0 ** -20 * (1.1 * mg * np.abs(u) + (np.abs(g) + 1.0) * mu + np.abs(g * u))
+        check_close(host(o2), R.swiglu(x, wg, wu), slack, f"swiglu {rows}x{K}x{N // 2}")
