@@ -58,8 +58,10 @@ bct_status bctm_pack_weight(const void* w, void* packed, uint32_t N, uint32_t K,
  * x [rows][K] row-major, or tiled with flags = BCTM_X_TILED; w_packed = bctm_pack_weight of w [N][K];
  * out/residual [rows][N] row-major;
  * K a multiple of 32, N a multiple of 16; fp32 accumulation (MFMA), one rounding to bf16 at the end.
- * out may alias residual; x must not alias out.  Built for few rows (a decode batch): every 32 rows
- * stream the weights once more. */
+ * out may alias residual; x must not alias out.  Two kernels: up to 127 rows (a decode batch) the weights
+ * are streamed once per 32 rows against activations read from cache; from 128 rows on (a prompt chunk), when
+ * N is a multiple of 128 (bctm_swiglu: 64), a tiled matrix-core kernel with 128 x 128 or 256 x 256 workgroups
+ * runs instead - fastest with a tiled x.  Both give the sum in fp32 with their own, fixed, summation order. */
 bct_status bctm_linear(const void* x, const void* w_packed, const void* residual, void* out, uint32_t rows,
                        uint32_t K, uint32_t N, uint32_t flags, void* hip_stream);
 
