@@ -78,6 +78,14 @@ bct_status bctm_linear_split(const void* x, const void* w_packed, void* out0, ui
 bct_status bctm_swiglu(const void* x, const void* w_gate_packed, const void* w_up_packed, void* out, uint32_t rows,
                        uint32_t K, uint32_t N, uint32_t flags, void* hip_stream);
 
+/* Which kernel bctm_linear / bctm_linear_split (swiglu = 0) or bctm_swiglu (swiglu = 1) launches for a
+ * shape: host logic only, no GPU call.  *kernel receives one of the values below. */
+#define BCTM_KERNEL_STREAMING 0u /* weights streamed once per 32 rows (one 16-feature tile per workgroup) */
+#define BCTM_KERNEL_STREAMING_WIDE 1u /* the same with two feature tiles per workgroup (wide output heads) */
+#define BCTM_KERNEL_TILE128 2u   /* matrix-core kernel, 128 rows x 128 features per workgroup */
+#define BCTM_KERNEL_TILE256 3u   /* matrix-core kernel, 256 rows x 256 features per workgroup */
+bct_status bctm_linear_plan(uint32_t rows, uint32_t K, uint32_t N, uint32_t swiglu, uint32_t* kernel);
+
 /* ids[r] = index of the largest logits[r][:] (the lowest index among equal maxima). */
 bct_status bctm_argmax(const void* logits, int32_t* ids, uint32_t rows, uint32_t N, void* hip_stream);
 

@@ -475,9 +475,17 @@ static void launch_linear_w(const void* x, const void* w, const void* residual, 
                        K, 0u);
 }
 
-// Many rows: the matrix-core kernel, for shapes its 128-feature (SwiGLU: 64) workgroup tiles cover exactly.
-static bool rows_kernel_fits(uint32_t rows, uint32_t N, bool swiglu) {
-  return rows >= 128 && N % (swiglu ? 64u : 128u) == 0;
+// The kernel of a projection shape.  Many rows (from 128 on): the matrix-core kernel, for feature counts its
+// 128-feature (SwiGLU: 64) workgroup tiles cover exactly; 256 x 256 workgroups halve the LDS and L1 traffic
+// per flop (measured +5..10 % at 16384 rows) but pad the rows to 256 and need a feature count they divide.
+// Few rows: the streaming kernel; measured at 32 rows (weights in TB/s): K = 4096, N = 4096 / 12288: 16
+// wavefronts, one feature tile 3.6 / 4.0 against 2.8 / 3.8 for two tiles (too few workgroups); N = 32000:
+// two tiles 5.0 against 4.3.
+static uint32_t linear_kernel_of(uint32_t rows, uint32_t N, bool swiglu) {
+  if (rows >= 128 && N % (swiglu ? 64u : 128u) == 0)
+    return (rows >= 1024 && N % (swiglu ? 128u : 256u) == 0) ? BCTM_KERNEL_TILE256 : BCTM_KERNEL_TILE128;
+  if (!swiglu && N >= 16384 && N % 32 == 0) return BCTM_KERNEL_STREAMING_WIDE;
+  return BCTM_KERNEL_STREAMING;
 }
 
 template <bool SWIGLU, int MI, int WC>
@@ -498,11 +506,10 @@ static void launch_rows_shape(const void* x, const void* w, const void* w2, cons
 }
 
 template <bool SWIGLU>
-static void launch_rows(const void* x, const void* w, const void* w2, const void* residual, const LinearOut& dst,
-                        uint32_t rows, uint32_t K, uint32_t N, uint32_t flags, void* hip_stream) {
-  // 256 x 256 workgroups halve the LDS and L1 traffic per flop (measured +5..10 % at 16384 rows) but pad
-  // the rows to 256 and need a feature count they divide; smaller or odd shapes take 128 x 128
-  if (rows >= 1024 && N % (SWIGLU ? 128u : 256u) == 0)
+static void launch_rows(uint32_t kernel, const void* x, const void* w, const void* w2, const void* residual,
+                        const LinearOut& dst, uint32_t rows, uint32_t K, uint32_t N, uint32_t flags,
+                        void* hip_stream) {
+  if (kernel == BCTM_KERNEL_TILE256)
     launch_rows_shape<SWIGLU, 8, 4>(x, w, w2, residual, dst, rows, K, N, flags, hip_stream);
   else
     launch_rows_shape<SWIGLU, 4, 2>(x, w, w2, residual, dst, rows, K, N, flags, hip_stream);
@@ -575,10 +582,9 @@ bct_status bctm_pack_weight(const void* w, void* packed, uint32_t N, uint32_t K,
 
 static bct_status launch_linear(const void* x, const void* w, const void* residual, const LinearOut& dst,
                                 uint32_t rows, uint32_t K, uint32_t N, uint32_t flags, void* hip_stream) {
-  // Measured at 32 rows (weights in TB/s): K = 4096, N = 4096 / 12288: 16 wavefronts, one feature tile
-  // 3.6 / 4.0 against 2.8 / 3.8 for two tiles (too few workgroups); N = 32000: two tiles 5.0 against 4.3.
-  if (rows_kernel_fits(rows, N, false)) launch_rows<false>(x, w, nullptr, residual, dst, rows, K, N, flags, hip_stream);
-  else if (N >= 16384 && N % 32 == 0) launch_linear_w<8, 4, 2>(x, w, residual, dst, rows, K, N, flags, hip_stream);
+  const uint32_t kernel = linear_kernel_of(rows, N, false);
+  if (kernel >= BCTM_KERNEL_TILE128) launch_rows<false>(kernel, x, w, nullptr, residual, dst, rows, K, N, flags, hip_stream);
+  else if (kernel == BCTM_KERNEL_STREAMING_WIDE) launch_linear_w<8, 4, 2>(x, w, residual, dst, rows, K, N, flags, hip_stream);
   else launch_linear_w<16, 8, 1>(x, w, residual, dst, rows, K, N, flags, hip_stream);
   return launched("linear");
 }
@@ -622,9 +628,17 @@ bct_status bctm_swiglu(const void* x, const void* w_gate, const void* w_up, void
     return mfail(BCT_ERR_UNSUPPORTED, "tiled activations need a multiple of 32 columns");
   if (!al16(w_up)) return mfail(BCT_ERR_MISALIGNED, "pointers must be 16-byte aligned");
   const LinearOut dst = {{(uint16_t*)out, nullptr, nullptr}, {0u, N, N, N}};
-  if (rows_kernel_fits(rows, N, true)) launch_rows<true>(x, w_gate, w_up, nullptr, dst, rows, K, N, flags, hip_stream);
+  const uint32_t kernel = linear_kernel_of(rows, N, true);
+  if (kernel >= BCTM_KERNEL_TILE128) launch_rows<true>(kernel, x, w_gate, w_up, nullptr, dst, rows, K, N, flags, hip_stream);
   else launch_swiglu_w<4, 8, 1>(x, w_gate, w_up, dst, rows, K, N, flags, hip_stream);   // 36 us at 4096 -> 11008 (8 wavefronts: 38)
   return launched("swiglu");
+}
+
+bct_status bctm_linear_plan(uint32_t rows, uint32_t K, uint32_t N, uint32_t swiglu, uint32_t* kernel) {
+  if (!kernel || rows == 0 || K == 0 || N == 0) return mfail(BCT_ERR_INVALID_ARG, "NULL pointer or zero size");
+  if (K % 32 != 0 || N % 16 != 0) return mfail(BCT_ERR_UNSUPPORTED, "K must be a multiple of 32 and N of 16");
+  *kernel = linear_kernel_of(rows, N, swiglu != 0);
+  return BCT_OK;
 }
 
 bct_status bctm_argmax(const void* logits, int32_t* ids, uint32_t rows, uint32_t N, void* hip_stream) {

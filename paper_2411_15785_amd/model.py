@@ -15,8 +15,10 @@ from . import binding
 from .binding import BCT_OK, BctCache, BctError, _dptr, _stream_ptr, _torch
 
 MODEL_EXPORTS = ["bctm_embed", "bctm_rmsnorm", "bctm_pack_weight", "bctm_pack_rows", "bctm_linear", "bctm_linear_split",
-                 "bctm_swiglu",
+                 "bctm_swiglu", "bctm_linear_plan",
                  "bctm_argmax", "bctm_last_error"]
+
+BCTM_KERNEL_STREAMING, BCTM_KERNEL_STREAMING_WIDE, BCTM_KERNEL_TILE128, BCTM_KERNEL_TILE256 = 0, 1, 2, 3
 
 BCTM_X_TILED = 1
 BCTM_OUT_TILED = 2
@@ -38,6 +40,7 @@ def mlib() -> ctypes.CDLL:
     L.bctm_linear.argtypes = [vp, vp, vp, vp, u32, u32, u32, u32, vp]
     L.bctm_linear_split.argtypes = [vp, vp, vp, u32, vp, u32, vp, u32, u32, u32, u32, vp]
     L.bctm_swiglu.argtypes = [vp, vp, vp, vp, u32, u32, u32, u32, vp]
+    L.bctm_linear_plan.argtypes = [u32, u32, u32, u32, ctypes.POINTER(u32)]
     L.bctm_argmax.argtypes = [vp, vp, u32, u32, vp]
     for n in MODEL_EXPORTS[:-1]:
         getattr(L, n).restype = ctypes.c_int
@@ -82,6 +85,13 @@ def bctm_embed(ids, table, out=None):
         _ck(mlib().bctm_embed(_dptr(ids), _dptr(table), _dptr(out), ids.numel(), table.shape[0], table.shape[1],
                               _stream_ptr()), "bctm_embed")
     return out
+
+
+def bctm_linear_plan(rows, K, N, swiglu=False):
+    """The kernel a projection of this shape runs in (one of the BCTM_KERNEL_ values); host logic, no GPU."""
+    k = ctypes.c_uint32(0)
+    _ck(mlib().bctm_linear_plan(rows, K, N, 1 if swiglu else 0, ctypes.byref(k)), "bctm_linear_plan")
+    return k.value
 
 
 class TiledRows:

@@ -81,6 +81,33 @@ def test_model_entry_points_check_arguments_before_touching_the_gpu(L):
     assert ML.bctm_last_error().decode() != ""
 
 
+def test_projection_kernel_choice():
+    """bctm_linear_plan: which kernel a projection shape runs in (host logic).  The 7B-shaped stack: a decode
+    batch streams the weights; a prompt chunk takes the matrix-core kernel, 256 x 256 where the shape allows."""
+    from paper_2411_15785_amd import model as Mo
+    S, SW, T128, T256 = (Mo.BCTM_KERNEL_STREAMING, Mo.BCTM_KERNEL_STREAMING_WIDE, Mo.BCTM_KERNEL_TILE128,
+                         Mo.BCTM_KERNEL_TILE256)
+    plan = Mo.bctm_linear_plan
+    # decode batch of 32
+    assert plan(32, 4096, 12288) == S and plan(32, 4096, 4096) == S and plan(32, 11008, 4096) == S
+    assert plan(32, 4096, 32000) == SW and plan(32, 4096, 11008, swiglu=True) == S
+    assert plan(127, 4096, 4096) == S
+    # prompt chunk of 32 x 512 rows
+    for N in (12288, 4096, 32000):
+        assert plan(16384, 4096, N) == T256
+    assert plan(16384, 4096, 11008, swiglu=True) == T256
+    # in between, and feature counts the larger tiles do not divide
+    assert plan(128, 4096, 4096) == T128 and plan(1023, 4096, 4096) == T128 and plan(1024, 4096, 4096) == T256
+    assert plan(4096, 4096, 384) == T128 and plan(4096, 4096, 192, swiglu=True) == T128
+    assert plan(4096, 4096, 48) == S and plan(4096, 4096, 96, swiglu=True) == S
+    assert plan(4096, 4096, 16416) == SW
+    ML = Mo.mlib()
+    k = ctypes.c_uint32(0)
+    assert ML.bctm_linear_plan(4, 72, 32, 0, ctypes.byref(k)) == P.BCT_ERR_UNSUPPORTED
+    assert ML.bctm_linear_plan(4, 64, 32, 0, None) == P.BCT_ERR_INVALID_ARG
+    assert ML.bctm_linear_plan(0, 64, 32, 0, ctypes.byref(k)) == P.BCT_ERR_INVALID_ARG
+
+
 def desc(**kw):
     d = dict(capacity_M=4096, batch=32, n_q_heads=32, n_kv_heads=32, head_dim=128, dtype=P.BCT_BF16,
              read_scale=0.0884, write_scale=0.0884, flags=0)
