@@ -84,6 +84,7 @@ bct_status bctm_swiglu(const void* x, const void* w_gate_packed, const void* w_u
 #define BCTM_KERNEL_STREAMING_WIDE 1u /* the same with two feature tiles per workgroup (wide output heads) */
 #define BCTM_KERNEL_TILE128 2u   /* matrix-core kernel, 128 rows x 128 features per workgroup */
 #define BCTM_KERNEL_TILE256 3u   /* matrix-core kernel, 256 rows x 256 features per workgroup */
+#define BCTM_KERNEL_STREAMING_TRIPLE 4u /* streaming with three feature tiles per workgroup */
 bct_status bctm_linear_plan(uint32_t rows, uint32_t K, uint32_t N, uint32_t swiglu, uint32_t* kernel);
 
 /* ids[r] = index of the largest logits[r][:] (the lowest index among equal maxima). */

@@ -19,6 +19,7 @@ MODEL_EXPORTS = ["bctm_embed", "bctm_rmsnorm", "bctm_pack_weight", "bctm_pack_ro
                  "bctm_argmax", "bctm_last_error"]
 
 BCTM_KERNEL_STREAMING, BCTM_KERNEL_STREAMING_WIDE, BCTM_KERNEL_TILE128, BCTM_KERNEL_TILE256 = 0, 1, 2, 3
+BCTM_KERNEL_STREAMING_TRIPLE = 4
 
 BCTM_X_TILED = 1
 BCTM_OUT_TILED = 2

@@ -89,7 +89,8 @@ def test_projection_kernel_choice():
                          Mo.BCTM_KERNEL_TILE256)
     plan = Mo.bctm_linear_plan
     # decode batch of 32
-    assert plan(32, 4096, 12288) == S and plan(32, 4096, 4096) == S and plan(32, 11008, 4096) == S
+    assert plan(32, 4096, 12288) == Mo.BCTM_KERNEL_STREAMING_TRIPLE and plan(32, 4096, 4096) == S
+    assert plan(32, 11008, 4096) == S and plan(32, 4096, 6144) == S and plan(32, 4096, 12304) == S
     assert plan(32, 4096, 32000) == SW and plan(32, 4096, 11008, swiglu=True) == S
     assert plan(127, 4096, 4096) == S
     # prompt chunk of 32 x 512 rows

@@ -48,6 +48,7 @@ LIN_SHAPES = [  # rows, K, N
     (1, 32, 16), (5, 64, 96), (32, 192, 48), (33, 320, 32), (70, 1024, 160), (32, 4096, 256), (3, 11008, 64),
     (17, 2336, 16),    # 73 K tiles: uneven shares for the wavefronts, whole rounds plus a masked one
     (33, 96, 16416),   # wide output (an output head): two feature tiles per workgroup
+    (33, 96, 12288), (7, 2336, 12336),   # three feature tiles per workgroup (the fused q | wq | wv projection)
 ]
 
 
@@ -171,7 +172,8 @@ def test_rmsnorm_tiled_out(M, rows, dim):
     assert np.array_equal(untile(t, rows, dim), plain)
 
 
-@pytest.mark.parametrize("rows,K,widths", [(32, 4096, (512, 128, 128)), (7, 320, (48, 16, 32)), (33, 64, (16, 64))])
+@pytest.mark.parametrize("rows,K,widths", [(32, 4096, (512, 128, 128)), (7, 320, (48, 16, 32)), (33, 64, (16, 64)),
+                                           (5, 64, (6144, 3072, 3072))])
 def test_linear_split_is_bitwise_the_separate_projections(M, rows, K, widths):
     import torch
     x = dev(draw(1, (rows, K)))
