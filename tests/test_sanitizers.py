@@ -43,8 +43,9 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 def test_library_host_layer_is_clean_under_asan_and_ubsan(tmp_path):
     root = os.path.dirname(HERE)
     flags = ["--offload-arch=gfx950", "-O1", "-g", "-std=c++17", "-fno-gpu-rdc", "-Xclang", "-target-feature", "-Xclang",
-             "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-I", os.path.join(root, "include"),
-             "-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined"]
+             "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-I", os.path.join(root, "include")]
+    # host pass only: every sanitizer option directly after -Xarch_host
+    flags += "-Xarch_host -fsanitize=address -Xarch_host -fsanitize=undefined".split()
     srcs = sorted(glob.glob(os.path.join(root, "paper_2411_15785_amd", "csrc", "*.hip")))
     assert srcs
 
@@ -58,8 +59,9 @@ def test_library_host_layer_is_clean_under_asan_and_ubsan(tmp_path):
     with concurrent.futures.ThreadPoolExecutor(max_workers=8) as ex:
         objs = list(ex.map(compile_one, srcs + [os.path.join(HERE, "host_sanitizer_drive.cpp")]))
     exe = str(tmp_path / "host_drive")
-    r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-fno-gpu-rdc", "-fsanitize=address", "-fsanitize=undefined",
-                        "-fno-gpu-sanitize", *objs, "-o", exe], capture_output=True, text=True)
+    link = "-fsanitize=address -fsanitize=undefined -fno-gpu-sanitize".split()   # host runtimes only
+    r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-fno-gpu-rdc", *link, *objs, "-o", exe],
+                       capture_output=True, text=True)
     if r.returncode != 0 and "asan" in r.stderr and "cannot find" in r.stderr:
         pytest.skip("the sanitizer runtimes are not installed")
     assert r.returncode == 0, r.stderr[-2000:]
