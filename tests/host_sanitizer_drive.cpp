@@ -31,7 +31,8 @@ int main() {
   bad |= strlen(bct_last_error()) == 0;
   uint32_t k = 99;
   bad |= bctm_linear_plan(16384, 4096, 12288, 0, &k) != BCT_OK || k != BCTM_KERNEL_TILE256;
-  bad |= bctm_linear_plan(32, 4096, 12288, 0, &k) != BCT_OK || k != BCTM_KERNEL_STREAMING;
+  bad |= bctm_linear_plan(32, 4096, 12288, 0, &k) != BCT_OK || k != BCTM_KERNEL_STREAMING_TRIPLE;
+  bad |= bctm_linear_plan(32, 4096, 4096, 0, &k) != BCT_OK || k != BCTM_KERNEL_STREAMING;
   bad |= bctm_linear((void*)0x10000, (void*)0x20000, NULL, (void*)0x30000, 4, 72, 32, 0, NULL) != BCT_ERR_UNSUPPORTED;
   bad |= bctm_rmsnorm((void*)0x10000, (void*)0x20000, (void*)0x30000, 4, 12, 1e-5f, 0, NULL) != BCT_ERR_UNSUPPORTED;
   bad |= strlen(bctm_last_error()) == 0;
