@@ -71,6 +71,7 @@ struct PrefillParams {
   uint32_t has_write, has_read, mk_per_seq;
   float rscale_l2e, wscale_l2e;
   uint32_t c_begin;    // first sub-chunk of a read launch
+  uint32_t stats_read; // the statistics kernel also covers the read rows (chunks that only read)
   const float* gate;   // [B][T][Hkv] step sizes (>= 0) or null
 };
 constexpr uint32_t kPrefillSubChunk = 128;

@@ -13,8 +13,9 @@
 //     out_c = RW_c . MV_c + tril(RW_c . WW_c^T) . WV_c,   MV_c = MV at the start of the sub-chunk,
 // where the state kernel, which walks the sub-chunks in order with its MV tile
 // in fp32 registers, leaves MV_c (rounded to bf16, as an MFMA operand has to be)
-// in the workspace.  Launches: transposes -> stats -> state -> read (all
-// sub-chunks; sub-chunk 0 reads the transposed copy of the initial MV).
+// in the workspace.  Launches: transpose (WV) -> stats (write rows) -> state -> read (all
+// sub-chunks, the read rows normalised on the fly); a chunk that only reads: transpose (MV) -> stats
+// (read rows) -> read.
 //
 // All matrix products use v_mfma_f32_32x32x16_bf16 with both operands read from
 // LDS tiles whose rows run along the contraction index (C[i][j] += sum_k
@@ -180,7 +181,7 @@ __global__ __launch_bounds__(512, 4) void prefill_stats_kernel(const PrefillPara
   // launch order: all sequences of one KV head, then the next head, so that the workgroups in flight
   // share one head's keys (1 MB at M = 4096) in each XCD's L2 instead of cycling through all heads
   const uint32_t h = blockIdx.y / p.B, b = blockIdx.y % p.B, unit = b * p.Hkv + h;
-  const uint32_t nw = p.has_write ? p.T : 0u, nr = p.has_read ? p.T * p.G : 0u;
+  const uint32_t nw = p.has_write ? p.T : 0u, nr = (p.has_read && p.stats_read) ? p.T * p.G : 0u;
   const uint32_t row0 = blockIdx.x * kTC;
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64, col = lane % 32, half = lane / 32;
   // wavefront = (32 slots sg of the key tile, 64 rows rh of the row tile)
@@ -278,34 +279,23 @@ __global__ __launch_bounds__(512, 4) void prefill_stats_kernel(const PrefillPara
   }
 }
 
-// ------------------------------------------------------------------ read
+// ------------------------------------------------------------------ read of a chunk that does not write
 
-// Output rows of one tile of 128 read rows of sub-chunk c (row rho of the
-// sub-chunk = token rho / G, query head rho % G):
-//     out = RW . MV_c  +  mask(RW . WW_c^T) . WV_c ,  mask: write token s <= the row's token.
-// The workgroup walks the M slots 64 at a time, recomputing the score tiles.
-// Eight wavefronts: for the scores each takes 32 rows x 32 slots of the tile,
-// for the products 32 output rows x d/2 value columns and 32 write tokens x 64
-// read rows of the within-sub-chunk matrix; that keeps a lane under 256
-// registers, so two wavefronts share a SIMD.
-template <int D, bool INTRA>
-__global__ __launch_bounds__(512) void prefill_read_kernel(const PrefillParams p) {
+// Output rows of one tile of 128 read rows (row rho of the tile = token rho / G, query head rho % G)
+// when MV does not change over the chunk:  out = RW . MV,  with the rows' shifts from the statistics
+// kernel.  The workgroup walks the M slots 64 at a time, recomputing the score tiles.  Eight wavefronts:
+// for the scores each takes 32 rows x 32 slots of the tile, for the product 32 output rows x d/2 value
+// columns.
+template <int D>
+__global__ __launch_bounds__(512) void prefill_read_only_kernel(const PrefillParams p) {
   constexpr int NT = 512;
   constexpr int LD = D + 8, KS = D / 16;
   constexpr int LP = 64 + 8;    // row length of tiles contracted over 64 slots
-  constexpr int LA = kTC + 8;   // row length of tiles contracted over 128 tokens
-  constexpr int kLoop = 64 * LD + D * LP + 2 * kTC * LP;  // sK, sVt, sPr, sPw
-  constexpr int kTail = kTC * LA + D * LA;                // sA, sWVt
-  constexpr int kRegion = kLoop > kTail ? kLoop : kTail;
   __shared__ __attribute__((aligned(16))) uint16_t sXr[kTC * LD];
-  __shared__ __attribute__((aligned(16))) uint16_t sXw[kTC * LD];
-  __shared__ __attribute__((aligned(16))) uint16_t sBuf[kRegion];
+  __shared__ __attribute__((aligned(16))) uint16_t sBuf[64 * LD + D * LP + kTC * LP];
   uint16_t* const sK = sBuf;
   uint16_t* const sVt = sK + 64 * LD;
   uint16_t* const sPr = sVt + D * LP;
-  uint16_t* const sPw = sPr + kTC * LP;
-  uint16_t* const sA = sBuf;
-  uint16_t* const sWVt = sA + kTC * LA;
 
   // launch order: all sequences of one KV head, then the next head, so that the workgroups in flight
   // share one head's keys (1 MB at M = 4096) in each XCD's L2 instead of cycling through all heads
@@ -314,8 +304,6 @@ __global__ __launch_bounds__(512) void prefill_read_kernel(const PrefillParams p
   const uint32_t c = p.c_begin + blockIdx.x / G, gp = blockIdx.x % G;
   const uint32_t t0 = c * kTC, rho0 = gp * kTC;
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64, col = lane % 32, half = lane / 32;
-  constexpr bool intra = INTRA;  // the chunk also writes: add the within-sub-chunk term
-  const size_t units = (size_t)p.B * p.Hkv;
 
   {
     Tile<kTC, D, NT> t;
@@ -325,46 +313,28 @@ __global__ __launch_bounds__(512) void prefill_read_kernel(const PrefillParams p
     });
     t.put(sXr, LD);
   }
-  if (intra) {
-    Tile<kTC, D, NT> t;
-    t.fetch_rows(p.mk, [&](int r) -> const uint16_t* {
-      return t0 + r < T ? p.wq + (((size_t)b * T + t0 + r) * p.Hkv + h) * D : nullptr;
-    });
-    t.put(sXw, LD);
-  }
   const uint16_t* mk = p.mk + (size_t)(p.mk_per_seq ? unit : h) * p.M * D;
-  // MV at the start of the sub-chunk, transposed: [column][slot]
-  const uint16_t* mvt = p.snap + ((size_t)(intra ? c : 0u) * units + unit) * p.M * D;
+  const uint16_t* mvt = p.snap + (size_t)unit * p.M * D;   // MV, transposed: [column][slot]
 
   // score step: wavefront = (slot half si, row group rj of 32); lane column = row
   const int si = wave & 1, rj = wave >> 1;
-  float nrm_r, nrm_w;
+  float nrm_r;
   {
-    const uint32_t r = 32 * rj + col;
-    const uint32_t rho = rho0 + r, t = t0 + rho / G;
+    const uint32_t rho = rho0 + 32 * rj + col, t = t0 + rho / G;
     nrm_r = t < T ? p.norm_r[(size_t)unit * T * G + (size_t)t * G + rho % G].x : kNoRow;
-    nrm_w = (intra && t0 + r < T) ? p.norm_w[(size_t)unit * T + t0 + r].x : kNoRow;
   }
-  // product step: wavefront = (32 output rows, half of the value columns) and, for the
-  // within-sub-chunk matrix, (32 write tokens, 64 read rows)
+  // product step: wavefront = (32 output rows, half of the value columns)
   constexpr int NOC = D / 64;                      // 32-column tiles per wavefront in the output product
   const int orow = 32 * (wave & 3), ocol = 32 * NOC * (wave >> 2);
-  const int as0 = 32 * (wave & 3), ar0 = 64 * (wave >> 2);
-  f32x16 oacc[NOC], aacc[2];
+  f32x16 oacc[NOC];
 #pragma unroll
   for (int jt = 0; jt < NOC; ++jt) oacc[jt] = zero16();
-#pragma unroll
-  for (int jt = 0; jt < 2; ++jt) aacc[jt] = zero16();
 
-  // the query rows (and write-query rows) do not change over the loop: keep
-  // their operand fragments in registers instead of re-reading LDS per tile
+  // the query rows do not change over the loop: keep their operand fragments in registers
   __syncthreads();
-  bf16x8 xr[KS], xw[KS];
+  bf16x8 xr[KS];
 #pragma unroll
-  for (int ks = 0; ks < KS; ++ks) {
-    xr[ks] = frag(sXr, LD, 32 * rj + col, ks * 16 + half * 8);
-    if (intra) xw[ks] = frag(sXw, LD, 32 * rj + col, ks * 16 + half * 8);
-  }
+  for (int ks = 0; ks < KS; ++ks) xr[ks] = frag(sXr, LD, 32 * rj + col, ks * 16 + half * 8);
   Tile<64, D, NT> tk;
   Tile<D, 64, NT> tv;
   tk.fetch_block(mk, D);
@@ -379,13 +349,9 @@ __global__ __launch_bounds__(512) void prefill_read_kernel(const PrefillParams p
     }
     __syncthreads();
     {
-      f32x16 sr = zero16(), sw = zero16();
+      f32x16 sr = zero16();
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        const bf16x8 a = frag(sK, LD, 32 * si + col, ks * 16 + half * 8);
-        sr = mfma_bf16(a, xr[ks], sr);
-        if (intra) sw = mfma_bf16(a, xw[ks], sw);
-      }
+      for (int ks = 0; ks < KS; ++ks) sr = mfma_bf16(frag(sK, LD, 32 * si + col, ks * 16 + half * 8), xr[ks], sr);
       const int r = 32 * rj + col;
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
@@ -393,11 +359,6 @@ __global__ __launch_bounds__(512) void prefill_read_kernel(const PrefillParams p
 #pragma unroll
         for (int i = 0; i < 4; ++i) e[i] = fast_exp2(sr[4 * q4 + i] * p.rscale_l2e - nrm_r);
         store4_bf16(sPr + r * LP + 32 * si + 8 * q4 + 4 * half, e[0], e[1], e[2], e[3]);
-        if (intra) {
-#pragma unroll
-          for (int i = 0; i < 4; ++i) e[i] = fast_exp2(sw[4 * q4 + i] * p.wscale_l2e - nrm_w);
-          store4_bf16(sPw + r * LP + 32 * si + 8 * q4 + 4 * half, e[0], e[1], e[2], e[3]);
-        }
       }
     }
     __syncthreads();
@@ -407,43 +368,6 @@ __global__ __launch_bounds__(512) void prefill_read_kernel(const PrefillParams p
       const bf16x8 a = frag(sPr, LP, orow + col, k);
 #pragma unroll
       for (int jt = 0; jt < NOC; ++jt) oacc[jt] = mfma_bf16(a, frag(sVt, LP, ocol + 32 * jt + col, k), oacc[jt]);
-      if (intra) {
-        // rows of this product = write tokens s, columns = read rows
-        const bf16x8 aw = frag(sPw, LP, as0 + col, k);
-#pragma unroll
-        for (int jt = 0; jt < 2; ++jt) aacc[jt] = mfma_bf16(aw, frag(sPr, LP, ar0 + 32 * jt + col, k), aacc[jt]);
-      }
-    }
-  }
-
-  if (intra) {
-    __syncthreads();
-    // A[row][s] = (s <= token of the row) ? sum_m rw[row][m] ww[s][m] : 0
-#pragma unroll
-    for (int jt = 0; jt < 2; ++jt) {
-      const int r = ar0 + 32 * jt + col;
-      const int tl = (int)((rho0 + r) / G);  // the row's token within the sub-chunk
-#pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        const int s0 = as0 + 8 * q4 + 4 * half;
-        float e[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) e[i] = (s0 + i <= tl) ? aacc[jt][4 * q4 + i] : 0.f;
-        store4_bf16(sA + r * LA + s0, e[0], e[1], e[2], e[3]);
-      }
-    }
-    {
-      Tile<D, kTC, NT> t;
-      t.fetch_block(p.wvt + (size_t)unit * D * p.Tpad + t0, p.Tpad);
-      t.put(sWVt, LA);
-    }
-    __syncthreads();
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      const int k = ks * 16 + half * 8;
-      const bf16x8 a = frag(sA, LA, orow + col, k);
-#pragma unroll
-      for (int jt = 0; jt < NOC; ++jt) oacc[jt] = mfma_bf16(a, frag(sWVt, LA, ocol + 32 * jt + col, k), oacc[jt]);
     }
   }
 
@@ -455,6 +379,242 @@ __global__ __launch_bounds__(512) void prefill_read_kernel(const PrefillParams p
       uint16_t* o = p.out + (((size_t)b * T + t) * p.Hq + h * G + rho % G) * D;
 #pragma unroll
       for (int jt = 0; jt < NOC; ++jt) o[ocol + 32 * jt + col] = bf16_bits(oacc[jt][v]);
+    }
+  }
+}
+
+// ------------------------------------------------------------------ read of a chunk that writes
+
+// The read of a chunk that also writes, without a statistics pass over the read rows: the softmax of a
+// read row is normalised at the end, out = (sum_m e_m MV_c[m] + sum_s A'[s] wv_s) / sum_m e_m with
+// e_m = exp2(score_m - shift), and the shift follows the row's running maximum lazily - it moves only
+// when a tile's maximum exceeds it by more than kTau (the weights then reach at most 2^kTau, far inside
+// bf16 and fp32 range), which after the first tile is rare, so rescaling what has been accumulated is a
+// seldom-taken, workgroup-uniform branch.  The write rows keep their shifts from the statistics kernel
+// (the state kernel needs those before it can add anything to MV).
+// Output rows of one tile of 128 read rows of sub-chunk c:
+//     out = RW . MV_c  +  mask(RW . WW_c^T) . WV_c ,  mask: write token s <= the row's token.
+// The workgroup walks the M slots 64 at a time, recomputing the score tiles.  Eight wavefronts.
+// Score step: wavefront = (role, row group of 32): role 0 scores 32 read rows, role 1 32 write tokens,
+// against all 64 slots of the tile, so a row's tile maximum and its sum are in two lanes.  Product step:
+// 32 output rows x d/2 value columns and 32 write tokens x 64 read rows of the within-sub-chunk
+// matrix; that keeps a lane under 256 registers, so two wavefronts share a SIMD.
+template <int D>
+__global__ __launch_bounds__(512) void prefill_read_online_kernel(const PrefillParams p) {
+  constexpr int NT = 512;
+  constexpr int LD = D + 8, KS = D / 16;
+  constexpr int LP = 64 + 8;    // row length of tiles contracted over 64 slots
+  constexpr int LA = kTC + 8;   // row length of tiles contracted over 128 tokens
+  constexpr float kTau = 8.f;
+  constexpr int kLoop = 64 * LD + D * LP + 2 * kTC * LP;  // sK, sVt, sPr, sPw
+  constexpr int kTail = kTC * LA + D * LA;                // sA, sWVt
+  constexpr int kRegion = kLoop > kTail ? kLoop : kTail;
+  __shared__ __attribute__((aligned(16))) uint16_t sXr[kTC * LD];
+  __shared__ __attribute__((aligned(16))) uint16_t sXw[kTC * LD];
+  __shared__ __attribute__((aligned(16))) uint16_t sBuf[kRegion];
+  __shared__ float sScale[kTC];     // per read row: this tile's rescaling factor; at the end 1 / sum
+  __shared__ uint32_t sFlag[2];     // tile parity -> some row's shift moved in that tile
+  uint16_t* const sK = sBuf;
+  uint16_t* const sVt = sK + 64 * LD;
+  uint16_t* const sPr = sVt + D * LP;
+  uint16_t* const sPw = sPr + kTC * LP;
+  uint16_t* const sA = sBuf;
+  uint16_t* const sWVt = sA + kTC * LA;
+
+  // launch order: all sequences of one KV head, then the next head (shared keys stay in L2)
+  const uint32_t h = blockIdx.y / p.B, b = blockIdx.y % p.B, unit = b * p.Hkv + h;
+  const uint32_t G = p.G, T = p.T;
+  const uint32_t c = p.c_begin + blockIdx.x / G, gp = blockIdx.x % G;
+  const uint32_t t0 = c * kTC, rho0 = gp * kTC;
+  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64, col = lane % 32, half = lane / 32;
+  const size_t units = (size_t)p.B * p.Hkv;
+
+  {
+    Tile<kTC, D, NT> t;
+    t.fetch_rows(p.mk, [&](int r) -> const uint16_t* {
+      const uint32_t rho = rho0 + r, tk = t0 + rho / G;
+      return tk < T ? p.q + (((size_t)b * T + tk) * p.Hq + h * G + rho % G) * D : nullptr;
+    });
+    t.put(sXr, LD);
+  }
+  {
+    Tile<kTC, D, NT> t;
+    t.fetch_rows(p.mk, [&](int r) -> const uint16_t* {
+      return t0 + r < T ? p.wq + (((size_t)b * T + t0 + r) * p.Hkv + h) * D : nullptr;
+    });
+    t.put(sXw, LD);
+  }
+  if (threadIdx.x < 2) sFlag[threadIdx.x] = 0u;
+  const uint16_t* mk = p.mk + (size_t)(p.mk_per_seq ? unit : h) * p.M * D;
+  const uint16_t* mvt = p.snap + ((size_t)c * units + unit) * p.M * D;   // MV_c, transposed: [column][slot]
+
+  // score step: role 0 = read rows, role 1 = write tokens; row (token) 32 * rg + col of the tile
+  const int role = wave >> 2, rg = wave & 3;
+  const int srow = 32 * rg + col;
+  float cs = role == 0 ? p.rscale_l2e : p.wscale_l2e;   // scale of this wavefront's rows (log2 domain)
+  // role 0: the lazily followed running maximum of the row (scaled); role 1: the token's fixed shift
+  float shift = kNegBig, zsum = 0.f;
+  if (role == 1) shift = (t0 + srow < T) ? p.norm_w[(size_t)unit * T + t0 + srow].x : kNoRow;
+  // product step: wavefront = (32 output rows, half of the value columns) and, for the
+  // within-sub-chunk matrix, (32 write tokens, 64 read rows)
+  constexpr int NOC = D / 64;
+  const int orow = 32 * (wave & 3), ocol = 32 * NOC * (wave >> 2);
+  const int as0 = 32 * (wave & 3), ar0 = 64 * (wave >> 2);
+  f32x16 oacc[NOC], aacc[2];
+#pragma unroll
+  for (int jt = 0; jt < NOC; ++jt) oacc[jt] = zero16();
+#pragma unroll
+  for (int jt = 0; jt < 2; ++jt) aacc[jt] = zero16();
+
+  // this wavefront's rows as operand fragments, kept in registers.  A negative read scale moves into the
+  // row (negating bf16 is exact), so that the largest raw score is also the largest scaled one.
+  __syncthreads();
+  bf16x8 x[KS];
+  {
+    const uint32_t flip = (role == 0 && cs < 0.f) ? 0x80008000u : 0u;
+    if (role == 0) cs = fabsf(cs);
+    const uint16_t* sX = role == 0 ? sXr : sXw;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      u32x4 v = __builtin_bit_cast(u32x4, frag(sX, LD, srow, ks * 16 + half * 8));
+      v ^= (u32x4){flip, flip, flip, flip};
+      x[ks] = __builtin_bit_cast(bf16x8, v);
+    }
+  }
+  Tile<64, D, NT> tk;
+  Tile<D, 64, NT> tv;
+  tk.fetch_block(mk, D);
+  tv.fetch_block(mvt, p.M);
+  uint32_t it = 0;
+  for (uint32_t m0 = 0; m0 < p.M; m0 += 64, ++it) {
+    __syncthreads();
+    tk.put(sK, LD);
+    tv.put(sVt, LP);
+    if (m0 + 64 < p.M) {  // next tiles, in flight during this tile's products
+      tk.fetch_block(mk + (size_t)(m0 + 64) * D, D);
+      tv.fetch_block(mvt + m0 + 64, p.M);
+    }
+    if (threadIdx.x == 0) sFlag[(it + 1) & 1] = 0u;   // last read before this tile's first barrier
+    __syncthreads();
+    {
+      f32x16 s0 = zero16(), s1 = zero16();
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        s0 = mfma_bf16(frag(sK, LD, col, ks * 16 + half * 8), x[ks], s0);
+        s1 = mfma_bf16(frag(sK, LD, 32 + col, ks * 16 + half * 8), x[ks], s1);
+      }
+      if (role == 0) {
+        float tm = fmaxf(s0[0], s1[0]);
+#pragma unroll
+        for (int v = 1; v < 16; ++v) tm = fmaxf(tm, fmaxf(s0[v], s1[v]));
+        tm = fmaxf(tm, __shfl_xor(tm, 32, 64)) * cs;
+        float f = 1.f;
+        if (tm > shift + kTau) {        // also the first tile (shift = kNegBig: f = 0, nothing accumulated yet)
+          f = fast_exp2(shift - tm);
+          shift = tm;
+          zsum *= f;
+          sFlag[it & 1] = 1u;
+        }
+        if (half == 0) sScale[srow] = f;
+        float add = 0.f;
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          float e0[4], e1[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            e0[i] = fast_exp2(__builtin_fmaf(s0[4 * q4 + i], cs, -shift));
+            e1[i] = fast_exp2(__builtin_fmaf(s1[4 * q4 + i], cs, -shift));
+            add += e0[i] + e1[i];
+          }
+          store4_bf16(sPr + srow * LP + 8 * q4 + 4 * half, e0[0], e0[1], e0[2], e0[3]);
+          store4_bf16(sPr + srow * LP + 32 + 8 * q4 + 4 * half, e1[0], e1[1], e1[2], e1[3]);
+        }
+        zsum += add;
+      } else {
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          float e0[4], e1[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            e0[i] = fast_exp2(__builtin_fmaf(s0[4 * q4 + i], cs, -shift));
+            e1[i] = fast_exp2(__builtin_fmaf(s1[4 * q4 + i], cs, -shift));
+          }
+          store4_bf16(sPw + srow * LP + 8 * q4 + 4 * half, e0[0], e0[1], e0[2], e0[3]);
+          store4_bf16(sPw + srow * LP + 32 + 8 * q4 + 4 * half, e1[0], e1[1], e1[2], e1[3]);
+        }
+      }
+    }
+    __syncthreads();
+    if (sFlag[it & 1]) {   // uniform over the workgroup: bring what has been accumulated to the new shifts
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const float fr = sScale[orow + 8 * (v / 4) + 4 * half + (v % 4)];
+#pragma unroll
+        for (int jt = 0; jt < NOC; ++jt) oacc[jt][v] *= fr;
+      }
+#pragma unroll
+      for (int jt = 0; jt < 2; ++jt) {
+        const float fc = sScale[ar0 + 32 * jt + col];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) aacc[jt][v] *= fc;
+      }
+    }
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const int k = ks * 16 + half * 8;
+      const bf16x8 a = frag(sPr, LP, orow + col, k);
+#pragma unroll
+      for (int jt = 0; jt < NOC; ++jt) oacc[jt] = mfma_bf16(a, frag(sVt, LP, ocol + 32 * jt + col, k), oacc[jt]);
+      // rows of this product = write tokens s, columns = read rows
+      const bf16x8 aw = frag(sPw, LP, as0 + col, k);
+#pragma unroll
+      for (int jt = 0; jt < 2; ++jt) aacc[jt] = mfma_bf16(aw, frag(sPr, LP, ar0 + 32 * jt + col, k), aacc[jt]);
+    }
+  }
+
+  __syncthreads();
+  // 1 / (sum of the row's weights): the normaliser of everything accumulated for the row
+  if (role == 0) {
+    const float z = zsum + __shfl_xor(zsum, 32, 64);
+    if (half == 0) sScale[srow] = 1.0f / z;
+  }
+  // A[row][s] = (s <= token of the row) ? sum_m e[row][m] ww[s][m] : 0
+#pragma unroll
+  for (int jt = 0; jt < 2; ++jt) {
+    const int r = ar0 + 32 * jt + col;
+    const int tl = (int)((rho0 + r) / G);  // the row's token within the sub-chunk
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+      const int s0 = as0 + 8 * q4 + 4 * half;
+      float e[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) e[i] = (s0 + i <= tl) ? aacc[jt][4 * q4 + i] : 0.f;
+      store4_bf16(sA + r * LA + s0, e[0], e[1], e[2], e[3]);
+    }
+  }
+  {
+    Tile<D, kTC, NT> t;
+    t.fetch_block(p.wvt + (size_t)unit * D * p.Tpad + t0, p.Tpad);
+    t.put(sWVt, LA);
+  }
+  __syncthreads();
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) {
+    const int k = ks * 16 + half * 8;
+    const bf16x8 a = frag(sA, LA, orow + col, k);
+#pragma unroll
+    for (int jt = 0; jt < NOC; ++jt) oacc[jt] = mfma_bf16(a, frag(sWVt, LA, ocol + 32 * jt + col, k), oacc[jt]);
+  }
+
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const uint32_t r = orow + 8 * (v / 4) + 4 * half + (v % 4);
+    const uint32_t rho = rho0 + r, t = t0 + rho / G;
+    if (t < T) {
+      const float inv = sScale[r];
+      uint16_t* o = p.out + (((size_t)b * T + t) * p.Hq + h * G + rho % G) * D;
+#pragma unroll
+      for (int jt = 0; jt < NOC; ++jt) o[ocol + 32 * jt + col] = bf16_bits(oacc[jt][v] * inv);
     }
   }
 }
@@ -631,7 +791,10 @@ __global__ __launch_bounds__(256, 2) void prefill_state_kernel(const PrefillPara
 hipError_t launch_prefill_bf16(const PrefillParams& p0, hipStream_t s) {
   PrefillParams p = p0;
   const uint32_t units = p.B * p.Hkv;
-  const uint32_t rows = (p.has_write ? p.T : 0u) + (p.has_read ? p.T * p.G : 0u);
+  // a chunk that writes normalises its read rows on the fly (prefill_read_online_kernel): statistics of
+  // the write rows only
+  p.stats_read = (p.has_read && !p.has_write) ? 1u : 0u;
+  const uint32_t rows = (p.has_write ? p.T : 0u) + (p.stats_read ? p.T * p.G : 0u);
   const uint32_t nb = (p.T + kTC - 1) / kTC;
   const bool d128 = p.d == 128;
   const dim3 block(256);
@@ -658,11 +821,11 @@ hipError_t launch_prefill_bf16(const PrefillParams& p0, hipStream_t s) {
     const dim3 g(c_count * p.G, units);
     const dim3 rblock(512);
     if (p.has_write) {
-      if (d128) hipLaunchKernelGGL((prefill_read_kernel<128, true>), g, rblock, 0, s, p);
-      else hipLaunchKernelGGL((prefill_read_kernel<64, true>), g, rblock, 0, s, p);
+      if (d128) hipLaunchKernelGGL((prefill_read_online_kernel<128>), g, rblock, 0, s, p);
+      else hipLaunchKernelGGL((prefill_read_online_kernel<64>), g, rblock, 0, s, p);
     } else {
-      if (d128) hipLaunchKernelGGL((prefill_read_kernel<128, false>), g, rblock, 0, s, p);
-      else hipLaunchKernelGGL((prefill_read_kernel<64, false>), g, rblock, 0, s, p);
+      if (d128) hipLaunchKernelGGL((prefill_read_only_kernel<128>), g, rblock, 0, s, p);
+      else hipLaunchKernelGGL((prefill_read_only_kernel<64>), g, rblock, 0, s, p);
     }
     return hipGetLastError();
   };

@@ -189,3 +189,29 @@ def test_prefill_argument_errors(P):
     assert L.bct_prefill(gpu._h, p(q), p(wq), p(wv), 0, p(out), s) == P.BCT_ERR_INVALID_ARG
     assert L.bct_prefill(gpu._h, p(q), p(wq), None, 8, p(out), s) == P.BCT_ERR_INVALID_ARG
     assert gpu.steps == 0
+
+
+@pytest.mark.parametrize("direction", ["rising", "falling"])
+def test_prefill_read_rows_whose_maximum_keeps_moving(P, R, direction):
+    """Read scores that grow (or fall) steadily along the slot axis, about 12 binary orders per 64-slot tile:
+    with "rising" the running maximum of every read row jumps in every tile, so whatever a kernel that
+    normalises on the fly has accumulated is rescaled each time; with "falling" the first tile holds the
+    maximum and all later weights are tiny.  Keys = ramp * u + small noise, queries = 16.6 * u."""
+    w = syn.Workload(f"pf_ramp_{direction}", 1, 2, 2, 2, 64, 512, "bf16", 0)
+    T = 70
+    ref, gpu, _, _, _ = make_pair(w, R.RefCache, P.BctCache, mv0=True, max_prefill_T=T)
+    u = np.ones(w.d) / np.sqrt(w.d)
+    ramp = np.arange(w.M) / w.M
+    if direction == "falling":
+        ramp = ramp[::-1]
+    noise = 0.05 * syn.unpack(syn.make_keys(w, 3), "bf16")
+    mk = syn.pack(16.0 * ramp[None, :, None] * u[None, None, :] + noise, "bf16")
+    ref.set_keys(mk)
+    gpu.set_keys(to_dev(mk, "bf16"))
+    q, wq, wv = syn.make_step(w, 0, T=T)
+    qf = syn.unpack(q, "bf16")
+    q = syn.pack(16.6 * u[None, None, None, :] * (1.0 + 0.01 * np.arange(T))[None, :, None, None] + 0.05 * qf, "bf16")
+    o_ref = ref.prefill(q, wq, wv, T)
+    o_gpu = gpu.prefill(to_dev(q, "bf16"), to_dev(wq, "bf16"), to_dev(wv, "bf16"), T)
+    e = check_prefill_out(to_np(o_gpu, "bf16"), o_ref, "bf16", f"ramp {direction}")
+    print(f"ramp {direction}: out err {e:.3g}")
