@@ -74,3 +74,67 @@ def test_random_case(P, R, i):
         else:
             check_state_one_step(to_np(mv_g, dt), ref.values(), dt, what, before=before)
         assert st == t + 1
+
+
+# ---------------------------------------------------------------- chunks (bf16 MFMA prefill)
+
+def draw_chunk(i):
+    r = syn.integers(20241126, 6, i, (12,), 1 << 30)
+    d = (64, 128)[r[0] % 2]
+    M = 64 * (1 + r[1] % 12)
+    B = 1 + r[2] % 3
+    Hkv = 1 + r[3] % 2
+    G = (1, 1, 2, 3, 4, 8)[r[4] % 6]
+    T = int((1 + r[5] % 300, 128, 129, 256, 127)[r[6] % 5] if r[6] % 3 else 1 + r[5] % 300)
+    flags = (0, 0, 1)[r[7] % 3]
+    mode = ("rw", "rw", "rw", "write_only", "read_only")[r[8] % 5]
+    gated = bool(r[9] % 2) and mode != "read_only"
+    scales = ((None, None), (0.2, 0.05), (-0.07, 0.11), (0.09, -0.1))[r[10] % 4]
+    return dict(d=d, M=int(M), B=int(B), Hkv=int(Hkv), G=G, T=T, flags=flags, mode=mode, gated=gated, scales=scales)
+
+
+CHUNKS = [draw_chunk(i) for i in range(24)]
+
+
+@pytest.mark.parametrize("i", range(len(CHUNKS)))
+def test_random_chunk(P, R, i):
+    """Seeded random sweep of prefill chunks (bf16): ragged lengths around the 128-token sub-chunk, all modes,
+    step sizes, per-sequence keys, scales of either sign; one chunk from a common random state."""
+    import torch
+    from test_gpu_prefill import check_prefill_out, check_prefill_state
+    c = CHUNKS[i]
+    what = f"chunk {i}: {c}"
+    w = syn.Workload(f"randpf{i}", 1, c["B"], c["Hkv"] * c["G"], c["Hkv"], c["d"], c["M"], "bf16", 0)
+    kw = {}
+    if c["scales"][0] is not None:
+        kw = dict(read_scale=c["scales"][0], write_scale=c["scales"][1])
+    T = c["T"]
+    ref, gpu, mk, _, _ = make_pair(w, R.RefCache, P.BctCache, flags=c["flags"], mv0=True, layer=100 + i,
+                                   max_prefill_T=T, **kw)
+    q, wq, wv = syn.make_step(w, 0, layer=100 + i, T=T)
+    if c["mode"] == "write_only":
+        q = None
+    if c["mode"] == "read_only":
+        wq = wv = None
+    gate = None
+    if c["gated"]:
+        gate = np.abs(syn.normal(i, 9, 77, (w.B, T, w.Hkv))).astype(np.float32)
+        gate.reshape(-1)[::5] = 0.0
+    before = ref.values()
+    o_ref = ref.prefill(q, wq, wv, T, gate=gate)
+    o_gpu = gpu.prefill(to_dev(q, "bf16"), to_dev(wq, "bf16"), to_dev(wv, "bf16"), T,
+                        gate=None if gate is None else torch.from_numpy(gate).cuda())
+    if q is not None:
+        check_prefill_out(to_np(o_gpu, "bf16"), o_ref, "bf16", what)
+    mk_g, mv_g, st = gpu.export()
+    assert np.array_equal(to_np(mk_g, "bf16"), mk), what
+    if c["mode"] == "read_only":
+        assert np.array_equal(to_np(mv_g, "bf16"), before), what
+    elif gate is None:
+        check_prefill_state(R, ref, mk, wq, wv, to_np(mv_g, "bf16"), T, what)
+    else:
+        # with step sizes the written mass is eta-weighted: bound it with wv scaled by the largest step size
+        gmax = float(np.max(gate))
+        scaled = syn.pack(syn.unpack(wv, "bf16") * max(gmax, 1.0), "bf16")
+        check_prefill_state(R, ref, mk, wq, scaled, to_np(mv_g, "bf16"), T, what)
+    assert st == T
