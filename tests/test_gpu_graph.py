@@ -101,3 +101,48 @@ def test_captured_stack_step_replays_exactly():
             assert torch.equal(graphed.caches[l].values_view(), eager.caches[l].values_view()), f"replay {t}: state"
         junk = torch.randn(1 << 20, device="cuda:0").sum().item()
         assert np.isfinite(junk)
+
+
+def test_captured_prefill_chunk_replays_exactly():
+    """A prefill chunk (transpose, statistics, state and read kernels; no allocation, no memset) captured as one
+    graph: every replay, with the program's own eager chunk and unrelated work in between, gives the eager
+    outputs and state bit for bit."""
+    import torch
+    import paper_2411_15785_amd as P
+    from oracle import bct_ref as R
+    w = syn.Workload("graph_pf", 1, 2, 4, 2, 128, 256, "bf16", 0)
+    T = 200
+    eager = make_pair(w, R.RefCache, P.BctCache, max_prefill_T=T)[1]
+    graphed = make_pair(w, R.RefCache, P.BctCache, max_prefill_T=T)[1]
+    sq = torch.empty((w.B, T, w.Hq, w.d), dtype=torch.bfloat16, device="cuda:0")
+    swq = torch.empty((w.B, T, w.Hkv, w.d), dtype=torch.bfloat16, device="cuda:0")
+    swv = torch.empty_like(swq)
+    sout, eout = torch.empty_like(sq), torch.empty_like(sq)
+
+    def load_inputs(k):
+        q, wq, wv = (to_dev(a, w.dtype) for a in syn.make_step(w, k * T, 0, T=T))
+        sq.copy_(q), swq.copy_(wq), swv.copy_(wv)
+
+    load_inputs(0)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        graphed.prefill(sq, swq, swv, T, sout)
+    torch.cuda.current_stream().wait_stream(side)
+    eager.prefill(sq, swq, swv, T, eout)
+    torch.cuda.synchronize()
+    assert torch.equal(sout, eout)
+
+    g = torch.cuda.CUDAGraph()
+    load_inputs(1)
+    with torch.cuda.graph(g):
+        graphed.prefill(sq, swq, swv, T, sout)
+    for k in range(1, 5):
+        load_inputs(k)
+        g.replay()
+        eager.prefill(sq, swq, swv, T, eout)
+        torch.cuda.synchronize()
+        assert torch.equal(sout, eout), f"replay of chunk {k}: out differs from eager"
+        assert torch.equal(graphed.values_view(), eager.values_view()), f"chunk {k}: state"
+        junk = torch.randn(1 << 20, device="cuda:0").sum().item()
+        assert np.isfinite(junk)
