@@ -112,6 +112,22 @@ bct_status bct_cache_randomize_values(bct_cache* c, uint64_t seed, float amplitu
 bct_status bct_decode_step(bct_cache* c, const void* q, const void* k_new, const void* v_new,
                            void* out, void* hip_stream);
 
+/* For callers that cannot allocate device memory and have no workspace to hand over when they step
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid allocation): the same
+ * step as bct_decode_step, same arguments, same results bit for bit, but the scratch of its kernels
+ * (scores, per-tile statistics, normalisers, split-M partial outputs) is a fixed array inside the
+ * library's device image instead of the workspace given to bct_cache_init.  The array holds
+ * bct_static_scratch_bytes() bytes (8 MiB) on every GPU the library runs on, for the life of the
+ * process; a cache whose decode step needs more returns BCT_ERR_BUFFER_TOO_SMALL (config 2 of the
+ * benchmark, B = 8, H = 32, M = 1024, needs 4.3 MiB; config 3 needs 101 MiB and does not fit).  The
+ * call makes no allocation of any kind.  The device that is current at the call must be the cache's.
+ * All calls on one GPU share that GPU's array (it keeps the last call's contents; nothing in it has
+ * to be cleared between calls): calls that overlap in time on one GPU, from different streams or
+ * threads, race.  Calls on one stream are safe.  Errors: those of bct_decode_step. */
+bct_status bct_decode_step_static(bct_cache* c, const void* q, const void* k_new, const void* v_new,
+                                  void* out, void* hip_stream);
+size_t bct_static_scratch_bytes(void);
+
 /* A chunk of T tokens per sequence (1 <= T <= max_prefill_T), equal to T decode
  * steps in token order except that MV is carried in fp32 through the chunk and
  * rounded to the storage dtype once at its end (the accumulation over tokens is

@@ -31,7 +31,7 @@ EXPORTS = [
     "bct_decode_step", "bct_prefill", "bct_decode_step_gated", "bct_prefill_gated", "bct_cache_export",
     "bct_cache_randomize_values", "bct_cache_export_sequence", "bct_cache_import_sequence", "bct_plan_query", "bct_cache_import", "bct_cache_steps",
     "bct_cache_regions", "bct_cache_destroy", "bct_strerror", "bct_last_error", "bct_stream_copy",
-    "bct_profile_enable", "bct_profile_read",
+    "bct_profile_enable", "bct_profile_read", "bct_decode_step_static", "bct_static_scratch_bytes",
 ]
 
 
@@ -80,6 +80,8 @@ def lib() -> ctypes.CDLL:
     L.bct_cache_set_keys.argtypes = [vp, vp, vp]
     L.bct_cache_set_values.argtypes = [vp, vp, vp]
     L.bct_decode_step.argtypes = [vp, vp, vp, vp, vp, vp]
+    L.bct_decode_step_static.argtypes = [vp, vp, vp, vp, vp, vp]
+    L.bct_static_scratch_bytes.argtypes = []
     L.bct_prefill.argtypes = [vp, vp, vp, vp, u32, vp, vp]
     L.bct_plan_query.argtypes = [dp, ctypes.POINTER(bct_plan_info)]
     L.bct_cache_randomize_values.argtypes = [vp, u64, ctypes.c_float, vp]
@@ -103,8 +105,9 @@ def lib() -> ctypes.CDLL:
     fp = ctypes.POINTER(ctypes.c_float)
     L.bct_profile_read.argtypes = [vp, ctypes.POINTER(u32), fp, fp, fp]
     for n in EXPORTS:
-        if n not in ("bct_cache_destroy", "bct_strerror", "bct_last_error"):
+        if n not in ("bct_cache_destroy", "bct_strerror", "bct_last_error", "bct_static_scratch_bytes"):
             getattr(L, n).restype = ctypes.c_int
+    L.bct_static_scratch_bytes.restype = sz
     _lib = L
     return L
 
@@ -277,6 +280,15 @@ class BctCache:
             self._call("bct_decode_step", _dptr(q), _dptr(k_new), _dptr(v_new), _dptr(out))
         else:
             self._call("bct_decode_step_gated", _dptr(q), _dptr(k_new), _dptr(v_new), _dptr(gate), _dptr(out))
+        return out
+
+    def decode_step_static(self, q, k_new, v_new, out):
+        """bct_decode_step_static: the caller passes every buffer, out included (None for a write-only step)."""
+        self._check(q, (self.B, self.Hq, self.d), "q")
+        self._check(k_new, (self.B, self.Hkv, self.d), "k_new")
+        self._check(v_new, (self.B, self.Hkv, self.d), "v_new")
+        self._check(out, (self.B, self.Hq, self.d), "out")
+        self._call("bct_decode_step_static", _dptr(q), _dptr(k_new), _dptr(v_new), _dptr(out))
         return out
 
     def prefill(self, q, k_new, v_new, T, out=None, gate=None):

@@ -7,6 +7,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -22,6 +23,7 @@ struct bct_cache {
   size_t ws_bytes;
   // workspace carve-up (byte offsets)
   size_t off_scores, off_stats, off_norm, off_partial, off_pf_norm_w, off_pf_norm_r, off_pf_wvt, off_pf_snap;
+  size_t ws_decode_bytes;  // the part of the workspace a decode step uses (it comes first)
   uint64_t steps;
   bool keys_set;
   bct::DecodeParams plan;  // shape, strides and launch plan; pointers filled per call
@@ -29,6 +31,12 @@ struct bct_cache {
   std::vector<hipEvent_t> prof_ev;
   uint32_t prof_cap = 0, prof_n = 0;
 };
+
+// Scratch of bct_decode_step_static: the scores, the per-tile statistics, the row normalisers and
+// the split-M partial outputs of one decode step live here instead of in a caller's workspace.
+// Every GPU the library runs on holds its own copy of this array until the process ends.
+#define BCT_STATIC_SCRATCH_BYTES (8u << 20)
+static __device__ __align__(256) unsigned char scratch[BCT_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -77,6 +85,7 @@ bct_status check_desc(const bct_cache_desc* d) {
 struct Sizes {
   size_t mk_bytes, mv_bytes, cache_bytes;
   size_t off_scores, off_stats, off_norm, off_partial, off_pf_norm_w, off_pf_norm_r, off_pf_wvt, off_pf_snap, ws_bytes;
+  size_t ws_decode_bytes;
 };
 
 void fill_plan(const bct_cache_desc* d, bct::DecodeParams& p) {
@@ -119,6 +128,7 @@ Sizes compute_sizes(const bct_cache_desc* d, uint32_t max_T) {
   off += align_up(units * rows * sizeof(float2), 256);
   z.off_partial = off;
   off += align_up((size_t)p.S * d->batch * d->n_q_heads * d->head_dim * sizeof(float), 256);
+  z.ws_decode_bytes = off;
   // prefill of a bf16 cache: row normalisers and the MV snapshots at sub-chunk starts
   z.off_pf_norm_w = z.off_pf_norm_r = z.off_pf_wvt = z.off_pf_snap = off;
   if (max_T > 0 && d->dtype == BCT_BF16) {
@@ -151,7 +161,7 @@ bct_status check_io(const bct_cache* c, const void* q, const void* k_new, const 
 
 // The three launches of one decode step; q/kv batch strides allow a token of
 // a [B][T][H][d] chunk to be stepped in place.
-bct_status run_decode(bct_cache* c, const void* q, const void* k_new, const void* v_new, void* out,
+bct_status run_decode(bct_cache* c, char* ws, const void* q, const void* k_new, const void* v_new, void* out,
                       uint64_t q_bstride, uint64_t kv_bstride, const float* gate, uint64_t gate_bstride,
                       hipStream_t s) {
   bct::DecodeParams p = c->plan;
@@ -161,10 +171,10 @@ bct_status run_decode(bct_cache* c, const void* q, const void* k_new, const void
   p.wq = k_new;
   p.wv = v_new;
   p.out = out;
-  p.scores = (float*)(c->ws + c->off_scores);
-  p.stats = (float2*)(c->ws + c->off_stats);
-  p.norm = (float2*)(c->ws + c->off_norm);
-  p.partial = (float*)(c->ws + c->off_partial);
+  p.scores = (float*)(ws + c->off_scores);
+  p.stats = (float2*)(ws + c->off_stats);
+  p.norm = (float2*)(ws + c->off_norm);
+  p.partial = (float*)(ws + c->off_partial);
   p.has_write = k_new ? 1u : 0u;
   p.has_read = q ? 1u : 0u;
   p.R = p.has_write + (p.has_read ? p.G : 0u);
@@ -192,6 +202,30 @@ bct_status run_decode(bct_cache* c, const void* q, const void* k_new, const void
     if ((e = hipEventRecord(ev[3], s)) != hipSuccess) return hip_fail(e, "event record");
     c->prof_n += 1;
   }
+  return BCT_OK;
+}
+
+// Device address of `scratch` on each GPU.  In host code the array's name is only a handle for
+// hipGetSymbolAddress, not an address a kernel can use: the address is looked up once per device,
+// with that device current, and everything below uses the pointer.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+char* g_scratch_ptr[kMaxDevices] = {};
+
+bct_status static_scratch(char** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+  if (dev < 0 || dev >= kMaxDevices) return fail(BCT_ERR_UNSUPPORTED, "device %d (at most %d devices)", dev, kMaxDevices);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+    if (!ptr || ((uintptr_t)ptr & 255u)) return fail(BCT_ERR_HIP, "hipGetSymbolAddress(scratch) gave %p", ptr);
+    g_scratch_ptr[dev] = (char*)ptr;
+  }
+  *out = g_scratch_ptr[dev];
   return BCT_OK;
 }
 
@@ -241,9 +275,20 @@ bct_status bct_cache_init(const bct_cache_desc* desc, uint32_t max_prefill_T, vo
   c->off_pf_norm_r = z.off_pf_norm_r;
   c->off_pf_wvt = z.off_pf_wvt;
   c->off_pf_snap = z.off_pf_snap;
+  c->ws_decode_bytes = z.ws_decode_bytes;
   c->steps = 0;
   c->keys_set = false;
   fill_plan(desc, c->plan);
+  {
+    // set-up time is where the static scratch's address is looked up on this device (a caller of
+    // bct_decode_step_static may be unable to make such a call later, e.g. under graph capture)
+    char* unused = nullptr;
+    const bct_status ss = static_scratch(&unused);
+    if (ss != BCT_OK) {
+      delete c;
+      return ss;
+    }
+  }
   const hipError_t e = bct::launch_fill_zero(c->mv, c->mv_bytes, (hipStream_t)hip_stream);
   if (e != hipSuccess) {
     delete c;
@@ -318,7 +363,7 @@ bct_status bct_decode_step_gated(bct_cache* c, const void* q, const void* k_new,
   if (st != BCT_OK) return st;
   if (gate && !k_new) return fail(BCT_ERR_INVALID_ARG, "a gate needs a write (k_new, v_new)");
   if (((uintptr_t)gate & 3u) != 0) return fail(BCT_ERR_MISALIGNED, "gate must be 4-byte aligned");
-  st = run_decode(c, q, k_new, v_new, out, (uint64_t)c->desc.n_q_heads * c->desc.head_dim,
+  st = run_decode(c, c->ws, q, k_new, v_new, out, (uint64_t)c->desc.n_q_heads * c->desc.head_dim,
                   (uint64_t)c->desc.n_kv_heads * c->desc.head_dim, gate, c->desc.n_kv_heads, (hipStream_t)hip_stream);
   if (st != BCT_OK) return st;
   c->steps += 1;
@@ -328,6 +373,29 @@ bct_status bct_decode_step_gated(bct_cache* c, const void* q, const void* k_new,
 bct_status bct_decode_step(bct_cache* c, const void* q, const void* k_new, const void* v_new, void* out,
                            void* hip_stream) {
   return bct_decode_step_gated(c, q, k_new, v_new, nullptr, out, hip_stream);
+}
+
+size_t bct_static_scratch_bytes(void) { return BCT_STATIC_SCRATCH_BYTES; }
+
+bct_status bct_decode_step_static(bct_cache* c, const void* q, const void* k_new, const void* v_new, void* out,
+                                  void* hip_stream) {
+  bct_status st = check_io(c, q, k_new, v_new, out);
+  if (st != BCT_OK) return st;
+  if (c->ws_decode_bytes > BCT_STATIC_SCRATCH_BYTES)
+    return fail(BCT_ERR_BUFFER_TOO_SMALL,
+                "a decode step of this cache needs %zu bytes of scratch, the static scratch holds %zu: "
+                "use bct_decode_step with a workspace",
+                c->ws_decode_bytes, (size_t)BCT_STATIC_SCRATCH_BYTES);
+  char* ws = nullptr;
+  if ((st = static_scratch(&ws)) != BCT_OK) return st;
+  // Nothing in the scratch has to start at zero: the scores pass writes every score and every
+  // (max, sum) pair the later launches read, and the MV pass writes every partial output the
+  // merge reads.
+  st = run_decode(c, ws, q, k_new, v_new, out, (uint64_t)c->desc.n_q_heads * c->desc.head_dim,
+                  (uint64_t)c->desc.n_kv_heads * c->desc.head_dim, nullptr, c->desc.n_kv_heads, (hipStream_t)hip_stream);
+  if (st != BCT_OK) return st;
+  c->steps += 1;
+  return BCT_OK;
 }
 
 bct_status bct_prefill_gated(bct_cache* c, const void* q, const void* k_new, const void* v_new, const float* gate,
@@ -345,7 +413,7 @@ bct_status bct_prefill_gated(bct_cache* c, const void* q, const void* k_new, con
     // fp32 storage: the fp32 running copy of MV IS the stored state, so the
     // chunk is exactly T decode steps in token order.
     for (uint32_t t = 0; t < T; ++t) {
-      st = run_decode(c, q ? (const char*)q + t * qs * sz : nullptr, k_new ? (const char*)k_new + t * ks * sz : nullptr,
+      st = run_decode(c, c->ws, q ? (const char*)q + t * qs * sz : nullptr, k_new ? (const char*)k_new + t * ks * sz : nullptr,
                       v_new ? (const char*)v_new + t * ks * sz : nullptr, out ? (char*)out + t * qs * sz : nullptr,
                       (uint64_t)T * qs, (uint64_t)T * ks, gate ? gate + (size_t)t * c->desc.n_kv_heads : nullptr,
                       (uint64_t)T * c->desc.n_kv_heads, (hipStream_t)hip_stream);
