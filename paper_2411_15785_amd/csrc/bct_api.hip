@@ -1,6 +1,7 @@
 // C ABI of libbct: argument checks, the per-cache plan and the launch
 // sequence.  Every check runs before the first HIP call of an entry point.
 #include "../../include/bct.h"
+#include "../../include/bct_measure.h"
 
 #include <math.h>
 #include <stdarg.h>
@@ -76,8 +77,8 @@ bct_status check_desc(const bct_cache_desc* d) {
     return fail(BCT_ERR_UNSUPPORTED, "n_q_heads / n_kv_heads = %u (at most %u)", d->n_q_heads / d->n_kv_heads,
                 bct::kMaxG);
   if (d->flags & ~(uint32_t)(BCT_MK_PER_SEQUENCE | BCT_STEP_STREAMING)) return fail(BCT_ERR_UNSUPPORTED, "unknown flags 0x%x", d->flags);
-  if ((uint64_t)d->batch * d->n_kv_heads > 65535u)
-    return fail(BCT_ERR_UNSUPPORTED, "batch * n_kv_heads = %llu (at most 65535)",
+  if ((uint64_t)d->batch * d->n_kv_heads > (1u << 24))
+    return fail(BCT_ERR_UNSUPPORTED, "batch * n_kv_heads = %llu (at most 16777216)",
                 (unsigned long long)d->batch * d->n_kv_heads);
   return BCT_OK;
 }

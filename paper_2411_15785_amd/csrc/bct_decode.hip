@@ -37,7 +37,8 @@ __global__ __launch_bounds__(256) void scores_generic_kernel(const DecodeParams 
 
   __shared__ float s_sc[kMaxRows][TILE];
 
-  const uint32_t tile = blockIdx.x, unit = blockIdx.y;
+  const uint32_t tile = blockIdx.x, unit = block_unit();
+  if (unit >= p.B * p.Hkv) return;
   const uint32_t b = unit / p.Hkv, h = unit % p.Hkv;
   const int tid = threadIdx.x, sub = tid % LPS, sl = tid / LPS;
   const elem* mk = (const elem*)p.mk + (size_t)(p.mk_per_seq ? unit : h) * p.M * D;
@@ -312,7 +313,7 @@ hipError_t launch_scores(const DecodeParams& p, int dtype, hipStream_t s) {
     if (nt == 2) return launch_scores_mfma<64, 2>(p, s);
     return launch_scores_mfma<64, 1>(p, s);
   }
-  const dim3 grid(p.M / 64, p.B * p.Hkv);
+  const dim3 grid = unit_grid(p.M / 64, (uint64_t)p.B * p.Hkv);
   if (dtype == 0) {
     if (p.d == 128) hipLaunchKernelGGL((scores_generic_kernel<F32, 128>), grid, dim3(256), 0, s, p);
     else hipLaunchKernelGGL((scores_generic_kernel<F32, 64>), grid, dim3(256), 0, s, p);

@@ -91,6 +91,9 @@ __device__ __forceinline__ float load_elem(const uint16_t* p, size_t i) {
   return __uint_as_float((uint32_t)p[i] << 16);
 }
 
+// The memory a workgroup of a unit_grid launch works on (see bct_internal.h).
+__device__ __forceinline__ uint32_t block_unit() { return blockIdx.z * 32768u + blockIdx.y; }
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // Butterfly reductions over the lanes whose ids differ in the bits of `mask`

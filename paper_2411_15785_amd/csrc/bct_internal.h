@@ -72,10 +72,11 @@ struct PrefillParams {
   float rscale_l2e, wscale_l2e;
   uint32_t c_begin;    // first sub-chunk of a read launch
   uint32_t stats_read; // the statistics kernel also covers the read rows (chunks that only read)
-  const float* gate;   // [B][T][Hkv] step sizes (>= 0) or null
+  const float* gate;   // [B][T][Hkv] step sizes (any sign) or null
 };
 constexpr uint32_t kPrefillSubChunk = 128;
 hipError_t launch_prefill_bf16(const PrefillParams& p, hipStream_t s);
+
 
 // dtype: 0 = fp32, 1 = bf16 (the ABI's bct_dtype values).
 hipError_t launch_scores(const DecodeParams& p, int dtype, hipStream_t s);
@@ -87,6 +88,14 @@ hipError_t launch_fused(const DecodeParams& p, int dtype, hipStream_t s);
 hipError_t launch_fill_zero(void* dst, size_t n_bytes, hipStream_t s);
 hipError_t launch_copy(void* dst, const void* src, size_t n_bytes, hipStream_t s);
 hipError_t launch_randomize(void* dst, size_t n_bytes, int dtype, uint64_t seed, float amplitude, hipStream_t s);
+
+// Launches indexed by memory (unit = b * Hkv + h) put the unit on grid.y and, beyond the 65535 that a grid
+// dimension other than x holds, on grid.z as well: unit = blockIdx.z * kUnitsPerZ + blockIdx.y.  A workgroup
+// whose unit is past the end returns at once (the test is uniform over the workgroup).
+constexpr uint32_t kUnitsPerZ = 32768;
+inline dim3 unit_grid(uint32_t x, uint64_t units) {
+  return dim3(x, (unsigned)(units < kUnitsPerZ ? units : kUnitsPerZ), (unsigned)((units + kUnitsPerZ - 1) / kUnitsPerZ));
+}
 
 // Chooses stat_tile / n_tiles (scores pass) and the MV pass shape (mv_bs, mv_u, S).
 void plan_decode(DecodeParams& p, int dtype);

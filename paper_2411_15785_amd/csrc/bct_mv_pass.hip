@@ -57,7 +57,8 @@ __global__ __launch_bounds__(BS) void mv_pass_kernel(const DecodeParams p) {
 
   __shared__ float s_red[READ ? NW * GT * D : 1];
 
-  const uint32_t split = blockIdx.x, unit = blockIdx.y;
+  const uint32_t split = blockIdx.x, unit = block_unit();
+  if (unit >= p.B * p.Hkv) return;
   const uint32_t b = unit / p.Hkv, h = unit % p.Hkv;
   const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
   const int sub = lane % LPS, sl = lane / LPS;
@@ -219,7 +220,7 @@ void plan_mv_pass(DecodeParams& p, int dtype) {
 
 template <typename DT, int D, int GT, int BS, int U, bool NORM>
 static void launch_mode_n(const DecodeParams& p, hipStream_t s) {
-  const dim3 grid(p.S, p.B * p.Hkv), block(BS);
+  const dim3 grid = unit_grid(p.S, (uint64_t)p.B * p.Hkv), block(BS);
   if (p.has_write && p.has_read)
     hipLaunchKernelGGL((mv_pass_kernel<DT, D, GT, true, true, BS, U, NORM>), grid, block, 0, s, p);
   else if (p.has_read)

@@ -32,7 +32,8 @@ __global__ __launch_bounds__(BS) void mv_pass_gqa_kernel(const DecodeParams p) {
   constexpr uint32_t W = WRITE ? 1u : 0u;
   __shared__ float s_red[NW * kMaxG * D];
 
-  const uint32_t split = blockIdx.x, unit = blockIdx.y;
+  const uint32_t split = blockIdx.x, unit = block_unit();
+  if (unit >= p.B * p.Hkv) return;
   const uint32_t b = unit / p.Hkv, h = unit % p.Hkv;
   const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
   const int sub = lane % 16, sl = lane / 16;
@@ -163,7 +164,7 @@ __global__ __launch_bounds__(BS) void mv_pass_gqa_kernel(const DecodeParams p) {
 
 template <int BS>
 static void launch_gqa_bs(const DecodeParams& p, hipStream_t s) {
-  const dim3 grid(p.S, p.B * p.Hkv), block(BS);
+  const dim3 grid = unit_grid(p.S, (uint64_t)p.B * p.Hkv), block(BS);
   if (p.has_write) {
     if (p.fuse_norm) hipLaunchKernelGGL((mv_pass_gqa_kernel<true, BS, true>), grid, block, 0, s, p);
     else hipLaunchKernelGGL((mv_pass_gqa_kernel<true, BS, false>), grid, block, 0, s, p);

@@ -139,7 +139,9 @@ template <int D>
 __global__ __launch_bounds__(256) void prefill_transpose_kernel(const PrefillParams p, int which) {
   constexpr int LD = D + 8;
   __shared__ __attribute__((aligned(16))) uint16_t sT[64 * LD];
-  const uint32_t unit = blockIdx.y, b = unit / p.Hkv, h = unit % p.Hkv;
+  const uint32_t unit = block_unit();
+  if (unit >= p.B * p.Hkv) return;
+  const uint32_t b = unit / p.Hkv, h = unit % p.Hkv;
   const uint32_t r0 = blockIdx.x * 64;
   const uint32_t rows = which == 0 ? p.Tpad : p.M;
   rows_to_lds<D, 64>(sT, LD, p.mv, [&](int r) -> const uint16_t* {
@@ -148,6 +150,18 @@ __global__ __launch_bounds__(256) void prefill_transpose_kernel(const PrefillPar
   });
   __syncthreads();
   uint16_t* dst = (which == 0 ? p.wvt : p.snap) + (size_t)unit * D * rows + r0;
+  // A negative step size eta_t (section 3.5 reading: MV += eta_t ww^T wv) flips the sign of token t's row of
+  // WV here, which is exact; the statistics kernel folds |eta_t| into the token's shift.  A thread's 8 rows
+  // are the same in every pass of the loop below (256 is a multiple of 8).
+  u32x4 flip = {0u, 0u, 0u, 0u};
+  if (which == 0 && p.gate) {
+    const uint32_t t8 = r0 + (threadIdx.x % 8) * 8;
+    uint32_t sg[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k)
+      sg[k] = (t8 + k < p.T && p.gate[((size_t)b * p.T + t8 + k) * p.Hkv + h] < 0.f) ? 0x8000u : 0u;
+    flip = (u32x4){sg[0] | (sg[1] << 16), sg[2] | (sg[3] << 16), sg[4] | (sg[5] << 16), sg[6] | (sg[7] << 16)};
+  }
   // thread -> (column j, 8 consecutive rows)
   for (int i = threadIdx.x; i < D * 8; i += 256) {
     const int j = i / 8, rr = (i % 8) * 8;
@@ -156,7 +170,7 @@ __global__ __launch_bounds__(256) void prefill_transpose_kernel(const PrefillPar
     v.y = (uint32_t)sT[(rr + 2) * LD + j] | ((uint32_t)sT[(rr + 3) * LD + j] << 16);
     v.z = (uint32_t)sT[(rr + 4) * LD + j] | ((uint32_t)sT[(rr + 5) * LD + j] << 16);
     v.w = (uint32_t)sT[(rr + 6) * LD + j] | ((uint32_t)sT[(rr + 7) * LD + j] << 16);
-    *(u32x4*)(dst + (size_t)j * rows + rr) = v;
+    *(u32x4*)(dst + (size_t)j * rows + rr) = v ^ flip;
   }
 }
 
@@ -180,7 +194,9 @@ __global__ __launch_bounds__(512, 4) void prefill_stats_kernel(const PrefillPara
 
   // launch order: all sequences of one KV head, then the next head, so that the workgroups in flight
   // share one head's keys (1 MB at M = 4096) in each XCD's L2 instead of cycling through all heads
-  const uint32_t h = blockIdx.y / p.B, b = blockIdx.y % p.B, unit = b * p.Hkv + h;
+  const uint32_t uy = block_unit();
+  if (uy >= p.B * p.Hkv) return;
+  const uint32_t h = uy / p.B, b = uy % p.B, unit = b * p.Hkv + h;
   const uint32_t nw = p.has_write ? p.T : 0u, nr = (p.has_read && p.stats_read) ? p.T * p.G : 0u;
   const uint32_t row0 = blockIdx.x * kTC;
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64, col = lane % 32, half = lane / 32;
@@ -269,9 +285,10 @@ __global__ __launch_bounds__(512, 4) void prefill_stats_kernel(const PrefillPara
     for (int w = 1; w < 4; ++w) merge_stat(mm, ss, sRed[w][threadIdx.x].x, sRed[w][threadIdx.x].y);
     uint32_t row = row0 + threadIdx.x;
     if (row < nw) {
-      // a step size eta >= 0 scales the token's write weights: exp2(score - shift) * eta
-      // = exp2(score - (shift - log2 eta)); eta = 0 gives shift = +inf and weights 0
-      const float le = p.gate ? __log2f(p.gate[((size_t)b * p.T + row) * p.Hkv + h]) : 0.f;
+      // a step size eta scales the token's write weights: exp2(score - shift) * |eta|
+      // = exp2(score - (shift - log2 |eta|)); eta = 0 gives shift = +inf and weights 0
+      // (|eta| here; the sign of eta rides on the token's row of WV^T, see prefill_transpose_kernel)
+      const float le = p.gate ? __log2f(fabsf(p.gate[((size_t)b * p.T + row) * p.Hkv + h])) : 0.f;
       p.norm_w[(size_t)unit * p.T + row] = make_float2(mm + __log2f(ss) - le, 0.f);
     } else if (row - nw < nr) {
       p.norm_r[(size_t)unit * p.T * p.G + (row - nw)] = make_float2(mm + __log2f(ss), 0.f);
@@ -299,7 +316,9 @@ __global__ __launch_bounds__(512) void prefill_read_only_kernel(const PrefillPar
 
   // launch order: all sequences of one KV head, then the next head, so that the workgroups in flight
   // share one head's keys (1 MB at M = 4096) in each XCD's L2 instead of cycling through all heads
-  const uint32_t h = blockIdx.y / p.B, b = blockIdx.y % p.B, unit = b * p.Hkv + h;
+  const uint32_t uy = block_unit();
+  if (uy >= p.B * p.Hkv) return;
+  const uint32_t h = uy / p.B, b = uy % p.B, unit = b * p.Hkv + h;
   const uint32_t G = p.G, T = p.T;
   const uint32_t c = p.c_begin + blockIdx.x / G, gp = blockIdx.x % G;
   const uint32_t t0 = c * kTC, rho0 = gp * kTC;
@@ -422,7 +441,9 @@ __global__ __launch_bounds__(512) void prefill_read_online_kernel(const PrefillP
   uint16_t* const sWVt = sA + kTC * LA;
 
   // launch order: all sequences of one KV head, then the next head (shared keys stay in L2)
-  const uint32_t h = blockIdx.y / p.B, b = blockIdx.y % p.B, unit = b * p.Hkv + h;
+  const uint32_t uy = block_unit();
+  if (uy >= p.B * p.Hkv) return;
+  const uint32_t h = uy / p.B, b = uy % p.B, unit = b * p.Hkv + h;
   const uint32_t G = p.G, T = p.T;
   const uint32_t c = p.c_begin + blockIdx.x / G, gp = blockIdx.x % G;
   const uint32_t t0 = c * kTC, rho0 = gp * kTC;
@@ -651,7 +672,9 @@ __global__ __launch_bounds__(256, 2) void prefill_state_kernel(const PrefillPara
   uint16_t* const sSnap = sTok;    // [column][slot] snapshot on its way out
   uint16_t* const sStage = sTok;   // [slot][column] MV tile on its way in and out
 
-  const uint32_t unit = blockIdx.y, b = unit / p.Hkv, h = unit % p.Hkv;
+  const uint32_t unit = block_unit();
+  if (unit >= p.B * p.Hkv) return;
+  const uint32_t b = unit / p.Hkv, h = unit % p.Hkv;
   const uint32_t m0 = blockIdx.x * 128, T = p.T;
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64, col = lane % 32, half = lane / 32;
   const size_t units = (size_t)p.B * p.Hkv;
@@ -802,7 +825,7 @@ hipError_t launch_prefill_bf16(const PrefillParams& p0, hipStream_t s) {
 
   p.Tpad = nb * kTC;
   auto transpose = [&](int which) -> hipError_t {
-    const dim3 g((which == 0 ? p.Tpad : p.M) / 64, units);
+    const dim3 g = unit_grid((which == 0 ? p.Tpad : p.M) / 64, units);
     if (d128) hipLaunchKernelGGL(prefill_transpose_kernel<128>, g, block, 0, s, p, which);
     else hipLaunchKernelGGL(prefill_transpose_kernel<64>, g, block, 0, s, p, which);
     return hipGetLastError();
@@ -811,14 +834,14 @@ hipError_t launch_prefill_bf16(const PrefillParams& p0, hipStream_t s) {
   // with a write, the state kernel leaves MV_0 transposed as the first snapshot on its way through
   if (p.has_read && !p.has_write && (e = transpose(1)) != hipSuccess) return e;
 
-  const dim3 gs((rows + kTC - 1) / kTC, units);
+  const dim3 gs = unit_grid((rows + kTC - 1) / kTC, units);
   if (d128) hipLaunchKernelGGL(prefill_stats_kernel<128>, gs, dim3(512), 0, s, p);
   else hipLaunchKernelGGL(prefill_stats_kernel<64>, gs, dim3(512), 0, s, p);
   if ((e = hipGetLastError()) != hipSuccess) return e;
 
   auto read = [&](uint32_t c_begin, uint32_t c_count) -> hipError_t {
     p.c_begin = c_begin;
-    const dim3 g(c_count * p.G, units);
+    const dim3 g = unit_grid(c_count * p.G, units);
     const dim3 rblock(512);
     if (p.has_write) {
       if (d128) hipLaunchKernelGGL((prefill_read_online_kernel<128>), g, rblock, 0, s, p);
@@ -830,7 +853,7 @@ hipError_t launch_prefill_bf16(const PrefillParams& p0, hipStream_t s) {
     return hipGetLastError();
   };
   if (p.has_write) {
-    const dim3 g((p.M + 127) / 128, units);
+    const dim3 g = unit_grid((p.M + 127) / 128, units);
     if (d128) hipLaunchKernelGGL(prefill_state_kernel<128>, g, dim3(256), 0, s, p);
     else hipLaunchKernelGGL(prefill_state_kernel<64>, g, dim3(256), 0, s, p);
     if ((e = hipGetLastError()) != hipSuccess) return e;

@@ -109,6 +109,55 @@ def test_gated_prefill_chunk(P, R, name, B, Hq, Hkv, d, M, dtype, T):
     assert not np.array_equal(got, before)
 
 
+@pytest.mark.parametrize("name,B,Hq,Hkv,d,M,dtype,T", [
+    ("f32", 2, 4, 2, 64, 128, "f32", 5), ("bf16_small", 2, 4, 4, 128, 128, "bf16", 40),
+    ("bf16_T200", 2, 4, 2, 128, 256, "bf16", 200), ("bf16_gqa4", 1, 8, 2, 128, 2048, "bf16", 130)])
+def test_negative_step_sizes_on_every_path(P, R, name, B, Hq, Hkv, d, M, dtype, T):
+    """eta of either sign: the decode step (one launch or four, vector or MFMA read) and the chunk (token by
+    token in fp32, the MFMA path in bf16, where |eta| goes into the token's shift and the sign into its row
+    of WV^T) all agree with the oracle's eta * ww, to the tolerances of the plain calls."""
+    w = syn.Workload(name, 1, B, Hq, Hkv, d, M, dtype, 0)
+    ref, gpu, mk, _, _ = make_pair(w, R.RefCache, P.BctCache, mv0=True, max_prefill_T=T)
+
+    def signed(seed, shape):
+        g = gates(seed, shape)
+        flat = g.reshape(-1)
+        flat[1::2] *= -1.0
+        flat[5::13] = -1.0
+        return g
+
+    for t in range(3):
+        q, wq, wv = syn.make_step(w, t)
+        g = signed(t, (B, Hkv))
+        before = ref.values()
+        gpu.set_values(to_dev(before, dtype))
+        o_ref = ref.decode_step(q, wq, wv, gate=g)
+        o_gpu = gpu.decode_step(to_dev(q, dtype), to_dev(wq, dtype), to_dev(wv, dtype), gate=gdev(g))
+        check_out(to_np(o_gpu, dtype), o_ref, dtype, f"{name} step {t}")
+        check_state_one_step(to_np(gpu.export()[1], dtype), ref.values(), dtype, f"{name} step {t}", before=before)
+    q, wq, wv = syn.make_step(w, 3, T=T)
+    g = signed(9, (B, T, Hkv))
+    before = ref.values()
+    gpu.set_values(to_dev(before, dtype))
+    o_ref = ref.prefill(q, wq, wv, T, gate=g)
+    o_gpu = gpu.prefill(to_dev(q, dtype), to_dev(wq, dtype), to_dev(wv, dtype), T, gate=gdev(g))
+    check_prefill_out(to_np(o_gpu, dtype), o_ref, dtype, name)
+    got = to_np(gpu.export()[1], dtype)
+    assert np.all(np.isfinite(f64(got, dtype)))
+    if dtype == "f32":
+        check_state_one_step(got, ref.values(), dtype, name)
+        return
+    aux = R.RefCache(M, B, Hq, Hkv, d, dtype, ref.read_scale, ref.write_scale, 0)
+    aux.set_keys(mk)
+    aux.prefill(None, wq, syn.pack(np.ones(wv.shape), dtype), T, gate=np.abs(g))     # mass of |eta| ww
+    mass = f64(aux.values(), dtype)[..., 0]
+    bound = mass[..., :, None] * np.max(np.abs(f64(wv, dtype)), axis=1)[..., None, :] * 1.01
+    r = f64(ref.values(), dtype)
+    dlt = np.abs(f64(got, dtype) - r)
+    allow = bf16_ulp(r) * 1.0001 + PF_WEIGHT_REL * bound
+    assert np.all(dlt <= allow), f"{name}: state off by {np.max(dlt / allow):.2f} x the allowance"
+
+
 def test_gate_argument_errors(P, R):
     import torch
     w = syn.Workload("err", 1, 2, 2, 2, 128, 64, "bf16", 0)

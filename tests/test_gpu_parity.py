@@ -158,6 +158,32 @@ def test_one_step_from_common_state(P, R, name, B, Hq, Hkv, d, M, dtype, mode, f
         assert st == t + 1
 
 
+@pytest.mark.parametrize("dtype,G", [("bf16", 1), ("f32", 2)])
+def test_more_memories_than_one_grid_dimension_holds(P, R, dtype, G):
+    """66000 memories (batch 1100 x 60 KV heads): launches indexed by memory spill from grid.y into grid.z.
+    Two decode steps from MV_0 = 0 and a chunk of three tokens, every memory compared."""
+    from test_gpu_prefill import check_prefill_out
+    w = syn.Workload("many_units", 1, 1100, 60 * G, 60, 64, 64, dtype, 0)
+    ref, gpu, mk, _, _ = make_pair(w, R.RefCache, P.BctCache, max_prefill_T=3)
+    for t in range(2):
+        q, wq, wv = step_np(w, t)
+        before = ref.values()
+        gpu.set_values(to_dev(before, dtype))
+        o_ref = ref.decode_step(q, wq, wv)
+        o_gpu = gpu.decode_step(to_dev(q, dtype), to_dev(wq, dtype), to_dev(wv, dtype))
+        check_out(to_np(o_gpu, dtype), o_ref, dtype, f"many units step {t}")
+        check_state_one_step(to_np(gpu.export()[1], dtype), ref.values(), dtype, f"many units step {t}", before=before)
+    q, wq, wv = syn.make_step(w, 2, T=3)
+    before = ref.values()
+    gpu.set_values(to_dev(before, dtype))
+    o_ref = ref.prefill(q, wq, wv, 3)
+    o_gpu = gpu.prefill(to_dev(q, dtype), to_dev(wq, dtype), to_dev(wv, dtype), 3)
+    check_prefill_out(to_np(o_gpu, dtype), o_ref, dtype, "many units chunk")
+    g, r = f64(to_np(gpu.export()[1], dtype), dtype), f64(ref.values(), dtype)
+    assert np.max(np.abs(g - r)) <= (1e-5 if dtype == "f32" else 2.0 ** -7) * np.max(np.abs(r))
+    assert gpu.steps == 5 and np.array_equal(to_np(gpu.keys_view(), dtype), mk)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_write_scale_one_is_algorithm_1_as_printed(P, R, dtype):
     w = syn.Workload("ws1", 1, 2, 2, 2, 64, 128, dtype, 4)
@@ -257,62 +283,86 @@ def test_capacity_is_constant_and_errors_are_reported(P, R):
 
 # ------------------------------------------------------------------ extreme inputs
 
+def score_tolerance(q, wq, mk, w, base):
+    """Output tolerance when scores are large.  A scaled score s (natural units) comes from an fp32 sum of
+    d exact products and carries a rounding error of about |s| 2^-24 (one rounding of the result; the
+    errors of the partial sums mostly cancel); the softmax weight exp(s - max) inherits it as a RELATIVE
+    error, numerator and normaliser both, so the output can be off by 2 |s|max 2^-24 relative (measured:
+    0.5 |s|max 2^-24).  For |s|max <= 80 that is inside the 1e-5 of unit-scale inputs (the workloads'
+    scores are N(0,1): |s| < 6); beyond, the bound grows with |s|max.  Returns (tolerance, |s|max)."""
+    k = f64(mk, w.dtype)                                           # [Hkv][M][d]
+    smax = 0.0
+    for x in (q, wq):
+        if x is None:
+            continue
+        xf = f64(x, w.dtype).reshape(-1, w.Hkv, x.shape[-2] // w.Hkv, w.d)      # [..][Hkv][G or 1][d]
+        smax = max(smax, float(np.max(np.abs(np.einsum("nhgd,hmd->nhgm", xf, k)))) * w.scale)
+    return max(base, 2.0 * smax * 2.0 ** -24), smax
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("kind", ["zero_keys", "huge_queries", "tiny_queries", "zero_write_value"])
 def test_extreme_inputs(P, R, dtype, kind):
     """Degenerate softmaxes: all-zero keys (uniform weights), queries scaled until the softmax is one-hot
-    (scores of several thousand), queries scaled towards zero, and a write of zeros (state unchanged)."""
+    (scores of several hundred), queries scaled towards zero, and a write of zeros (state unchanged).
+    Every case is held to the plain tolerances except the fp32 outputs and the state of huge_queries,
+    whose bound follows the score magnitude (score_tolerance)."""
+    from test_gpu_prefill import check_prefill_out
     w = syn.Workload(f"extreme_{kind}", 1, 2, 4, 2, 128, 256, dtype, 0)
     ref, gpu, mk, mv0, _ = make_pair(w, R.RefCache, P.BctCache, mv0=True, max_prefill_T=40)
     if kind == "zero_keys":
         z = np.zeros_like(mk)
         ref.set_keys(z)
         gpu.set_keys(to_dev(z, dtype))
-    for t in range(2):
-        q, wq, wv = step_np(w, t)
+
+    def shape_inputs(q, wq, wv):
         if kind == "huge_queries":
             q, wq = (syn.pack(f64(a, dtype) * 256.0, dtype) for a in (q, wq))
         if kind == "tiny_queries":
             q, wq = (syn.pack(f64(a, dtype) * 2.0 ** -20, dtype) for a in (q, wq))
         if kind == "zero_write_value":
             wv = np.zeros_like(wv)
+        return q, wq, wv
+
+    for t in range(2):
+        q, wq, wv = shape_inputs(*step_np(w, t))
         before = ref.values()
         gpu.set_values(to_dev(before, dtype))
         o_ref = ref.decode_step(q, wq, wv)
         o_gpu = gpu.decode_step(to_dev(q, dtype), to_dev(wq, dtype), to_dev(wv, dtype))
-        if kind == "huge_queries":
-            # A score s carries a rounding error of about |s| * 2^-24 from its fp32 dot product, and the
-            # softmax weight inherits it as a RELATIVE error: at |s| of a few thousand that is 1e-4, not
-            # the 1e-6 of unit-scale scores, so the output bound is widened by that factor here.
+        tol, smax = score_tolerance(q, wq, mk, w, 1e-5)
+        if kind == "huge_queries" and dtype == "f32":
             g, r = f64(to_np(o_gpu, dtype), dtype), f64(o_ref, dtype)
-            assert np.all(np.isfinite(g))
-            assert rel_normwise(g, r) <= (4e-4 if dtype == "f32" else 2.0 ** -7), f"{kind} step {t}"
+            e = rel_normwise(g, r)
+            print(f"huge_queries fp32 step {t}: |s|max {smax:.0f}, out rel err {e:.2e}, bound {tol:.2e}")
+            assert np.all(np.isfinite(g)) and smax > 400 and e <= tol, f"{kind} step {t}: {e:.2e} > {tol:.2e}"
         else:
-            check_out(to_np(o_gpu, dtype), o_ref, dtype, f"{kind} step {t}")
+            check_out(to_np(o_gpu, dtype), o_ref, dtype, f"{kind} step {t}")   # bf16: the bound is rounding, not scores
         got = to_np(gpu.export()[1], dtype)
         if kind == "zero_write_value":
             assert np.array_equal(got, before)
         elif kind == "huge_queries" and dtype == "f32":
             r = ref.values().astype(np.float64)
-            assert np.max(np.abs(got - r)) <= 4e-4 * np.max(np.abs(r)), f"{kind} step {t}"
+            assert np.max(np.abs(got - r)) <= tol * np.max(np.abs(r)), f"{kind} step {t}"
         else:
             check_state_one_step(got, ref.values(), dtype, f"{kind} step {t}", before=before,
-                                 rel=4e-4 if kind == "huge_queries" else 4e-6)
+                                 rel=tol if kind == "huge_queries" else 4e-6)
     # the same through a chunk
     T = 40
-    q, wq, wv = syn.make_step(w, 2, T=T)
-    if kind == "huge_queries":
-        q, wq = (syn.pack(f64(a, dtype) * 256.0, dtype) for a in (q, wq))
-    if kind == "tiny_queries":
-        q, wq = (syn.pack(f64(a, dtype) * 2.0 ** -20, dtype) for a in (q, wq))
-    if kind == "zero_write_value":
-        wv = np.zeros_like(wv)
+    q, wq, wv = shape_inputs(*syn.make_step(w, 2, T=T))
     gpu.set_values(to_dev(ref.values(), dtype))
     o_ref = ref.prefill(q, wq, wv, T)
     o_gpu = gpu.prefill(to_dev(q, dtype), to_dev(wq, dtype), to_dev(wv, dtype), T)
     g, r = f64(to_np(o_gpu, dtype), dtype), f64(o_ref, dtype)
     assert np.all(np.isfinite(g))
-    tol = 1e-5 if dtype == "f32" else 2.0 ** -6
-    if kind == "huge_queries":
-        tol = 4e-4 if dtype == "f32" else 2.0 ** -5
-    assert np.max(np.max(np.abs(g - r), axis=-1) / np.maximum(np.max(np.abs(r), axis=-1), 1e-30)) <= tol, kind
+    if dtype == "f32":
+        tol, smax = score_tolerance(q.reshape(-1, w.Hq, w.d), wq.reshape(-1, w.Hkv, w.d), mk, w, 1e-5)
+        e = rel_normwise(g, r)
+        print(f"{kind} fp32 chunk: |s|max {smax:.0f}, out rel err {e:.2e}, bound {tol:.2e}")
+        assert e <= (tol if kind == "huge_queries" else 1e-5), kind
+    else:
+        # huge_queries: a one-hot read returns a stored value of up to 4 in size, where one bf16 spacing is
+        # 0.031: the bound there is the relative one (spacings of the vector's largest entry)
+        e = check_prefill_out(to_np(o_gpu, dtype), o_ref, dtype, f"{kind} chunk",
+                              abs_bound=None if kind == "huge_queries" else 2e-2)
+        print(f"{kind} bf16 chunk: out within {e:.2f} ulp of the vector max")

@@ -501,6 +501,27 @@ def test_p13b_power_of_two_gate_is_a_scaled_write_value(dtype):
         assert np.array_equal(c1.values(), c2.values())
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_p13d_negative_gate_is_the_write_of_the_negated_value(dtype):
+    """eta = -1 (and -2: a power of two) equals the plain write of -wv (-2 wv) bit for bit: negation and
+    scaling by two are exact, and fma(-w, v, x) = fma(w, -v, x).  A step and a chunk."""
+    M, B, Hq, Hkv, d, T = 16, 2, 4, 2, 8, 6
+    c1, _, _ = make_cache(M, B, Hq, Hkv, d, dtype, mv0=True)
+    c2, _, _ = make_cache(M, B, Hq, Hkv, d, dtype, mv0=True)
+    gate = np.array([[-1.0, 1.0], [-2.0, -1.0]], np.float32)
+    for t in range(4):
+        q, wq, wv = step_inputs(c1, 6, t)
+        o1 = c1.decode_step(q, wq, wv, gate=gate)
+        o2 = c2.decode_step(q, wq, syn.pack(f64(wv, dtype) * gate[:, :, None], dtype))
+        assert np.array_equal(o1, o2) and np.array_equal(c1.values(), c2.values())
+    steps = [step_inputs(c1, 6, 10 + t) for t in range(T)]
+    q, wq, wv = (np.ascontiguousarray(np.stack([s[i] for s in steps], axis=1)) for i in range(3))
+    gT = np.ascontiguousarray(np.broadcast_to(gate[:, None, :], (B, T, Hkv)) * np.where(np.arange(T) % 2, 1.0, -1.0)[None, :, None]).astype(np.float32)
+    o1 = c1.prefill(q, wq, wv, T, gate=gT)
+    o2 = c2.prefill(q, wq, syn.pack(f64(wv, dtype) * gT[..., None], dtype), T)
+    assert np.array_equal(o1, o2) and np.array_equal(c1.values(), c2.values())
+
+
 def test_p13c_gated_prefill_equals_gated_steps_in_fp32():
     M, B, Hq, Hkv, d, T = 16, 2, 4, 2, 8, 5
     c1, _, _ = make_cache(M, B, Hq, Hkv, d, "f32", mv0=True)
