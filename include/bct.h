@@ -94,8 +94,8 @@ bct_status bct_cache_init(const bct_cache_desc* desc, uint32_t max_prefill_T,
  * are static: no other call writes them (Algorithm 1 takes MK as an input). */
 bct_status bct_cache_set_keys(bct_cache* c, const void* mk_dev, void* hip_stream);
 
-/* MV := mv0_dev (device, MV layout), or zero if NULL (section 3.1: "zero or
- * random values").  Does not touch steps. */
+/* MV := mv0_dev (device, MV layout), or zero if NULL (section 3.1 lets the
+ * initial contents be zero or random).  Does not touch steps. */
 bct_status bct_cache_set_values(bct_cache* c, const void* mv0_dev, void* hip_stream);
 
 /* MV := amplitude * u with u uniform on [-1, 1) (section 3.1 allows random initial contents and names
@@ -138,8 +138,9 @@ bct_status bct_prefill(bct_cache* c, const void* q, const void* k_new, const voi
 /* The same two calls with a step size per token (section 3.5 lists a "learning rate adaptation" that
  * sets the step size of each token, without an equation; taken here as one scalar eta_t per memory on
  * the write: MV <- MV + eta_t * ww^T wv).  gate: DEVICE, float32, [B][n_kv_heads] for a decode step,
- * [B][T][n_kv_heads] for a chunk; NULL = 1 everywhere = the plain call.  eta must be >= 0 (0 writes
- * nothing); a negative or NaN eta gives NaN in that memory.  A gate without a write is
+ * [B][T][n_kv_heads] for a chunk; NULL = 1 everywhere = the plain call.  eta may be any finite value
+ * on every path and dtype: 0 writes nothing, a negative eta subtracts (eta = -1 equals the plain write
+ * of -wv, bit for bit); a NaN or infinite eta gives NaN in that memory.  A gate without a write is
  * BCT_ERR_INVALID_ARG.  The read is unchanged. */
 bct_status bct_decode_step_gated(bct_cache* c, const void* q, const void* k_new, const void* v_new,
                                  const float* gate, void* out, void* hip_stream);
@@ -156,17 +157,25 @@ bct_status bct_cache_export_sequence(const bct_cache* c, uint32_t b, void* mk_ds
 bct_status bct_cache_import_sequence(bct_cache* c, uint32_t b, const void* mk_src, const void* mv_src,
                                      void* hip_stream);
 
-/* Checkpoint: copies MK and/or MV out of / into the cache (device pointers,
- * either may be NULL) together with the step counter (host). */
+/* Checkpoint.  The whole recurrent state of a layer is (MK, MV_t): section 3.2 step 3 retrieves the
+ * previous MV from the cache and step 5 stores the updated one back, so continuing a stream elsewhere
+ * or later needs exactly these bytes.  Copies MK and/or MV out of / into the cache (device pointers,
+ * either may be NULL) together with the step counter (host).  bct_cache_import with both pointers
+ * NULL only sets the counter. */
 bct_status bct_cache_export(const bct_cache* c, void* mk_dst, void* mv_dst, uint64_t* steps,
                             void* hip_stream);
 bct_status bct_cache_import(bct_cache* c, const void* mk_src, const void* mv_src, uint64_t steps,
                             void* hip_stream);
 
+/* Tokens written or read through this handle so far.  The counter lives in the host handle and counts
+ * CALLS (a decode step 1, a chunk T): replaying a captured HIP graph steps the cache on the GPU without
+ * a call, so after graph replays the caller adds the replayed steps itself (bct_cache_import(c, NULL,
+ * NULL, steps) sets the counter).  Nothing on the GPU depends on it. */
 bct_status bct_cache_steps(const bct_cache* c, uint64_t* steps);
 
-/* The launch plan the library would use for a decode step of this descriptor (no GPU needed):
- * how many launches, and the shape of the pass over MV.  For inspection and tests. */
+/* The launch plan the library would use for a decode step (section 3.2 steps 2-5 and the read) of this
+ * descriptor: how many launches, and the shape of the pass over MV.  Host logic only (no GPU needed);
+ * for inspection, tests and for naming the kernel a measurement belongs to. */
 typedef struct bct_plan_info {
   uint32_t launches;          /* kernels per decode step with both a write and a read: 1, 3 or 4       */
   uint32_t one_launch;        /* 1: the small-cache single-workgroup step                               */
@@ -179,7 +188,8 @@ typedef struct bct_plan_info {
 } bct_plan_info;
 bct_status bct_plan_query(const bct_cache_desc* desc, bct_plan_info* info);
 
-/* Device addresses of the two regions inside cache_mem (for zero-copy views). */
+/* Device addresses of the two regions inside cache_mem, MK first, then MV (section 3.1's two
+ * sequences), for zero-copy views of the state: the bounded-cache layout in HBM as the caller sees it. */
 bct_status bct_cache_regions(const bct_cache* c, void** mk_dev, size_t* mk_bytes,
                              void** mv_dev, size_t* mv_bytes);
 
@@ -188,23 +198,6 @@ void bct_cache_destroy(bct_cache* c);
 
 const char* bct_strerror(bct_status s);
 const char* bct_last_error(void); /* thread-local detail of the last failure */
-
-/* Measurement aid: per-kernel timing of decode steps with HIP events recorded
- * on the caller's stream around each launch (scores, MV pass, merge).
- * bct_profile_enable(c, n) keeps events for the next n decode steps (n = 0
- * switches it off and releases the events).  bct_profile_read waits for the
- * recorded events, returns how many steps were recorded and the mean
- * duration in milliseconds of each launch (host pointers, any may be NULL),
- * and starts over.  Not for use under graph capture. */
-bct_status bct_profile_enable(bct_cache* c, uint32_t n_steps);
-bct_status bct_profile_read(bct_cache* c, uint32_t* n_recorded, float* ms_scores, float* ms_mv_pass,
-                            float* ms_merge);
-
-/* Measurement aid: a plain device-to-device copy kernel (16-byte vectors),
- * n_bytes a multiple of 16, src/dst 16-byte aligned.  Reads n_bytes and
- * writes n_bytes; used to calibrate HBM counters and as the practical ceiling
- * for a 1:1 read/write stream such as the section 3.4 update. */
-bct_status bct_stream_copy(void* dst, const void* src, size_t n_bytes, void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -1,6 +1,6 @@
 /* libbct -- the Llama-shaped glue around the bounded-cache attention layer.
  *
- * The paper applies its mechanism to "the attention layers" of a decoder-only
+ * The paper applies its mechanism to the attention layers of a decoder-only
  * Transformer and obtains the write query and the write key-value vector from
  * the layer input with two learnable matrices (section 3.2 step 1, Algorithm 1:
  * wq_t = W_wq x_t, wv_t = W_wv x_t).  These entry points are the dense pieces

@@ -14,16 +14,18 @@
 //           MV    = MV' + ww^T . wv             (section 3.2 step 4; 3.4 eq.)
 //           MV stored back for the next step    (section 3.2 step 5)
 //   read    out   = softmax(read_scale * q . MK^T) . MV
-//           The paper places the mechanism "in the attention layers" and
-//           never writes the read out; standard softmax attention of the
+//           The paper applies the mechanism to the attention layers of a
+//           decoder-only Transformer (sections 1 and 3.1) and never writes
+//           the read out; standard softmax attention of the
 //           layer's query over keys MK and values MV is the reading taken.
 //
 // Readings where the paper is silent or at odds with itself:
 //   * Every token writes, the first one included (section 3.2 steps 3-4 and
 //     the section 3.4 equation have no first-token exception; Algorithm 1's
 //     t = 1 branch is reachable by passing no write on that step).
-//   * Token t's read sees its own write (the updated MV is what is "stored
-//     back ... ready to be used"; a causal token attends to itself).
+//   * Token t's read sees its own write (section 3.2 step 5 stores the
+//     updated MV back for the steps that follow; a causal token attends to
+//     itself).
 //   * MK is never modified by any step.
 //   * One independent memory per (batch element, KV head); G = Hq / Hkv
 //     query heads read the memory of KV head hq / G; MK is shared over the
@@ -283,7 +285,7 @@ int bct_ref_cache_set_keys(bct_ref_cache* c, const void* mk) {
   return 0;
 }
 
-// mv0 == NULL -> zero ("initialized to zero or random values", section 3.1).
+// mv0 == NULL -> zero (section 3.1: MV_0 may be zero or random).
 int bct_ref_cache_set_values(bct_ref_cache* c, const void* mv0) {
   if (!c) return 1;
   if (mv0) std::memcpy(c->mv.data(), mv0, c->mv.size());
@@ -291,7 +293,7 @@ int bct_ref_cache_set_values(bct_ref_cache* c, const void* mv0) {
   return 0;
 }
 
-// MV := random values (section 3.1 allows "zero or random" initial contents; the distribution is not
+// MV := random values (section 3.1 allows random initial contents; the distribution is not
 // given).  Element i (flat index of [B][Hkv][M][d]) is amplitude * u_i, u_i uniform on the 2^24-point
 // grid of [-1, 1): u_i = ((z_i >> 40) - 2^23) / 2^23 with z_i the (i + 1)-th output of the splitmix64
 // generator (Steele, Lea, Flood 2014) started at `seed`; the product is one fp32 multiplication,

@@ -1,4 +1,4 @@
-"""GPU parity of the state-management calls: random initial MV (section 3.1: "zero or random"),
+"""GPU parity of the state-management calls: random initial MV (section 3.1 allows zero or random initial contents),
 bit for bit against the oracle's generator, and the per-sequence export / import that swaps a
 session's fixed-size state (section 4.3: memory independent of the sequence length)."""
 import numpy as np
