@@ -26,7 +26,11 @@
 //   * Token t's read sees its own write (section 3.2 step 5 stores the
 //     updated MV back for the steps that follow; a causal token attends to
 //     itself).
-//   * MK is never modified by any step.
+//   * MK is never modified by any step of the paper's method.  The one exception is the keyed step
+//     below (bct_ref_decode_step_keyed), a widening that the paper only gestures at (section 3.5,
+//     the adaptive update rule: no equation): the section 3.4 update applied to the key table too,
+//     MK_t = MK_(t-1) + kappa_t * ww_t^T wk_t, with the token's own addressing weights ww_t, which
+//     like its read weights come from MK_(t-1); the new keys address the NEXT token.
 //   * One independent memory per (batch element, KV head); G = Hq / Hkv
 //     query heads read the memory of KV head hq / G; MK is shared over the
 //     batch unless per-sequence keys are requested.
@@ -174,9 +178,12 @@ inline size_t key_offset(const RefCache& c, uint32_t b, uint32_t h) {
 // One decode step of one (b, h) memory.  Any of the write (wq, wv) and the
 // read (q, out) may be absent.  Vectors are addressed through explicit element
 // offsets so that the same routine serves [B][H][d] and [B][T][H][d] inputs.
+// wk (optional, with wq): the key write vector of the keyed step at element offset wv_off; kappa its step
+// size; wwk: M doubles of scratch for the write weights, which the key update needs after the read.
 void unit_decode_step(RefCache& c, uint32_t b, uint32_t h, const void* q, size_t q_off, size_t q_head_stride,
                       const void* wq, size_t wq_off, const void* wv, size_t wv_off, void* out, size_t out_off,
-                      size_t out_head_stride, double* w, double eta = 1.0) {
+                      size_t out_head_stride, double* w, double eta = 1.0, const void* wk = nullptr,
+                      double kappa = 1.0, double* wwk = nullptr) {
   const uint32_t M = c.ds.M, d = c.ds.d, G = c.ds.Hq / c.ds.Hkv;
   const int dt = c.ds.dtype;
   const size_t koff = key_offset(c, b, h);
@@ -185,6 +192,8 @@ void unit_decode_step(RefCache& c, uint32_t b, uint32_t h, const void* q, size_t
 
   if (wq) {
     softmax_weights(c, wq, wq_off, koff, (double)c.ds.write_scale, w);
+    if (wk)
+      for (uint32_t m = 0; m < M; ++m) wwk[m] = w[m];
     for (uint32_t m = 0; m < M; ++m) {
       const float wwm = (float)(eta * w[m]);   // the token's step size scales its write weights
       for (uint32_t j = 0; j < d; ++j) {
@@ -202,6 +211,18 @@ void unit_decode_step(RefCache& c, uint32_t b, uint32_t h, const void* q, size_t
       for (uint32_t m = 0; m < M; ++m)
         for (uint32_t j = 0; j < d; ++j) acc[j] += w[m] * load_elem(mv, voff + (size_t)m * d + j, dt);
       for (uint32_t j = 0; j < d; ++j) store_from_double(out, out_off + (size_t)g * out_head_stride + j, dt, acc[j]);
+    }
+  }
+  if (wq && wk) {
+    // the keys move last: the token's write and read were addressed through MK_(t-1)
+    void* mk = c.mk.data();
+    for (uint32_t m = 0; m < M; ++m) {
+      const float kwm = (float)(kappa * wwk[m]);
+      for (uint32_t j = 0; j < d; ++j) {
+        const size_t i = koff + (size_t)m * d + j;
+        const float upd = std::fmaf(kwm, load_elem_f(wk, wv_off + j, dt), load_elem_f(mk, i, dt));
+        store_from_float(mk, i, dt, upd);
+      }
     }
   }
 }
@@ -401,6 +422,37 @@ int bct_ref_decode_step_gated(bct_ref_cache* c, const void* q, const void* wq, c
 
 int bct_ref_decode_step(bct_ref_cache* c, const void* q, const void* wq, const void* wv, void* out) {
   return bct_ref_decode_step_gated(c, q, wq, wv, nullptr, out);
+}
+
+// The keyed step: a decode step whose write also moves the keys (per-sequence keys only).
+// wk: [B][Hkv][d], the key write vectors; kgate: NULL (1 everywhere) or float [B][Hkv], their step
+// sizes kappa.  Per memory, in this order: ww = softmax(write_scale * wq . MK^T); MV += eta ww^T wv;
+// out = softmax(read_scale * q . MK^T) . MV; MK += kappa ww^T wk (one float fused multiply-add per
+// element, rounded to the storage dtype, like MV).  The write (wq, wv) must be present; the read is
+// optional.  2 = keys shared by the batch.
+int bct_ref_decode_step_keyed(bct_ref_cache* c, const void* q, const void* wq, const void* wv, const void* wk,
+                              const float* gate, const float* kgate, void* out) {
+  if (!c || !wq || !wv || !wk) return 1;
+  if ((q == nullptr) != (out == nullptr)) return 1;
+  if (!(c->ds.flags & REF_FLAG_MK_PER_SEQUENCE)) return 2;
+  if (!c->keys_set) return 5;
+  const uint32_t B = c->ds.B, Hkv = c->ds.Hkv, Hq = c->ds.Hq, d = c->ds.d, G = Hq / Hkv;
+  const long units = (long)B * Hkv;
+#pragma omp parallel
+  {
+    std::vector<double> w(c->ds.M), wwk(c->ds.M);
+#pragma omp for schedule(static)
+    for (long u = 0; u < units; ++u) {
+      const uint32_t b = (uint32_t)(u / Hkv), h = (uint32_t)(u % Hkv);
+      const size_t kv_off = ((size_t)b * Hkv + h) * d;
+      const size_t q_off = ((size_t)b * Hq + (size_t)h * G) * d;
+      unit_decode_step(*c, b, h, q, q_off, d, wq, kv_off, wv, kv_off, out, q_off, d, w.data(),
+                       gate ? (double)gate[(size_t)b * Hkv + h] : 1.0, wk,
+                       kgate ? (double)kgate[(size_t)b * Hkv + h] : 1.0, wwk.data());
+    }
+  }
+  c->steps += 1;
+  return 0;
 }
 
 // q, out: [B][T][Hq][d]; wq, wv: [B][T][Hkv][d].  Same NULL conventions.

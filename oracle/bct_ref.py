@@ -60,6 +60,7 @@ def lib():
         L.bct_ref_cache_import_sequence.argtypes = [vp, ctypes.c_uint32, vp, vp]
         L.bct_ref_decode_step_gated.argtypes = [vp, vp, vp, vp, vp, vp]
         L.bct_ref_prefill_gated.argtypes = [vp, vp, vp, vp, vp, ctypes.c_uint32, vp]
+        L.bct_ref_decode_step_keyed.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp]
         L.bct_ref_probe_weights.argtypes = [vp, ctypes.c_uint32, ctypes.c_uint32, vp, ctypes.c_double, vp]
         L.bct_ref_round_bf16_from_float.argtypes = [ctypes.c_float]
         L.bct_ref_round_bf16_from_float.restype = ctypes.c_uint16
@@ -184,6 +185,26 @@ class RefCache:
         if rc != 0:
             raise RuntimeError(f"bct_ref_decode_step failed ({rc})")
         return out
+
+    def decode_step_keyed(self, q, wq, wv, wk, gate=None, kgate=None):
+        """The keyed step (per-sequence keys): the write also moves the keys, MK += kappa ww^T wk, after the
+        token's read.  wk: [B][Hkv][d]; gate / kgate: float32 [B][Hkv] step sizes of the value / key write."""
+        out = None
+        if q is not None:
+            q = self._chk(q, (self.B, self.Hq, self.d))
+            out = np.empty_like(q)
+        wq, wv, wk = (self._chk(a, (self.B, self.Hkv, self.d)) for a in (wq, wv, wk))
+        gate, kgate = self._gate(gate, (self.B, self.Hkv)), self._gate(kgate, (self.B, self.Hkv))
+        rc = lib().bct_ref_decode_step_keyed(self._h, _ptr(q), _ptr(wq), _ptr(wv), _ptr(wk), _ptr(gate), _ptr(kgate),
+                                             _ptr(out))
+        if rc != 0:
+            raise RuntimeError(f"bct_ref_decode_step_keyed failed ({rc})")
+        return out
+
+    def keys(self):
+        mk = np.empty(self.keys_shape, dtype=self._np)
+        assert lib().bct_ref_cache_export(self._h, _ptr(mk), None, None) == 0
+        return mk
 
     def decode_step_rc(self, q, wq, wv, out):
         return lib().bct_ref_decode_step(self._h, _ptr(q), _ptr(wq), _ptr(wv), _ptr(out))

@@ -37,6 +37,8 @@ int main() {
       rc |= bct_ref_decode_step(c, q1.data(), nullptr, nullptr, out1.data());
       rc |= bct_ref_decode_step(c, nullptr, wq1.data(), wv1.data(), nullptr);
       rc |= bct_ref_decode_step_gated(c, q1.data(), wq1.data(), wv1.data(), gate1.data(), out1.data());
+      if (flags) rc |= bct_ref_decode_step_keyed(c, q1.data(), wq1.data(), wv1.data(), wv1.data(), gate1.data(), gate1.data(), out1.data());
+      else rc |= bct_ref_decode_step_keyed(c, q1.data(), wq1.data(), wv1.data(), wv1.data(), nullptr, nullptr, out1.data()) != 2;
       rc |= bct_ref_prefill(c, q.data(), wq.data(), wv.data(), T, out.data());
       rc |= bct_ref_prefill_gated(c, q.data(), wq.data(), wv.data(), gate.data(), T, out.data());
       rc |= bct_ref_prefill(c, nullptr, wq.data(), wv.data(), T, nullptr);

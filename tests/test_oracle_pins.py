@@ -586,3 +586,107 @@ def test_p14c_sequence_export_import_moves_exactly_one_sequence():
     q, wq, wv = step_inputs(a, 6, 2)
     assert np.array_equal(a.decode_step(q, wq, wv), b.decode_step(q, wq, wv))
     assert np.array_equal(a.values(), b.values())
+
+
+# ------------------------------------------------------------------ P15 the keyed step (updatable keys)
+# The paper never assigns MK; section 3.5 only names an adaptive update rule.  The widening taken here is the
+# section 3.4 update applied to the key table with the token's own addressing weights:
+# MK_t = MK_(t-1) + kappa_t * ww_t^T wk_t, after the token's write to MV and its read, which both use
+# MK_(t-1).  What fixes it: without a key step (kappa = 0) it is the plain step; the keys' update is the
+# value update of section 3.4 under another name, so the already pinned value write must reproduce it
+# bit for bit; mass is conserved; a one-hot write moves exactly one key row; and the NEXT token is
+# addressed through the moved keys, by the brute-force softmax.
+
+def key_inputs(c, seed, step):
+    return rng_normal(seed, 8, step, (c.B, c.Hkv, c.d), c.dtype)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_p15_zero_key_step_is_the_plain_step_and_keys_stay(dtype):
+    M, B, Hq, Hkv, d = 16, 2, 4, 2, 8
+    a, mk, _ = make_cache(M, B, Hq, Hkv, d, dtype, flags=1, mv0=True)
+    b, _, _ = make_cache(M, B, Hq, Hkv, d, dtype, flags=1, mv0=True)
+    for t in range(3):
+        q, wq, wv = step_inputs(a, 6, t)
+        o1 = a.decode_step(q, wq, wv)
+        o2 = b.decode_step_keyed(q, wq, wv, key_inputs(b, 6, t), kgate=np.zeros((B, Hkv), np.float32))
+        assert np.array_equal(o1, o2) and np.array_equal(a.values(), b.values())
+        assert np.array_equal(b.keys(), mk)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_p15b_key_update_is_the_value_update_under_another_name(dtype):
+    """MK_t of a keyed step = what the (pinned) value write produces in a cache whose VALUES hold MK_(t-1)
+    and that is written with the same wq and with wv := wk, step size kappa.  The read of the keyed step
+    and its MV are those of the plain step: they never see the new keys."""
+    M, B, Hq, Hkv, d = 16, 2, 4, 2, 8
+    a, mk, mv = make_cache(M, B, Hq, Hkv, d, dtype, flags=1, mv0=True)
+    plain, _, _ = make_cache(M, B, Hq, Hkv, d, dtype, flags=1, mv0=True)
+    q, wq, wv = step_inputs(a, 6, 0)
+    wk = key_inputs(a, 6, 0)
+    kappa = np.array([[0.5, 1.0], [2.0, 0.25]], np.float32)
+    eta = np.array([[1.0, 0.5], [1.0, 1.0]], np.float32)
+    out = a.decode_step_keyed(q, wq, wv, wk, gate=eta, kgate=kappa)
+    twin = RefCache(M, B, Hq, Hkv, d, dtype, a.read_scale, a.write_scale, 1)
+    twin.set_keys(mk)
+    twin.set_values(mk)                       # the keys, held as values
+    twin.decode_step(None, wq, wk, gate=kappa)
+    assert np.array_equal(a.keys(), twin.values())
+    assert np.array_equal(out, plain.decode_step(q, wq, wv, gate=eta)) and np.array_equal(a.values(), plain.values())
+    assert not np.array_equal(a.keys(), mk)
+
+
+def test_p15c_key_mass_is_conserved_and_one_hot_writes_move_one_row():
+    M, B, Hq, Hkv, d = 8, 1, 2, 2, 4
+    c, mk, _ = make_cache(M, B, Hq, Hkv, d, "f32", flags=1)
+    k0 = f64(mk, "f32")
+    total = np.zeros((B, Hkv, d))
+    for t in range(5):
+        q, wq, wv = step_inputs(c, 6, t)
+        wk = key_inputs(c, 6, t)
+        kap = np.full((B, Hkv), 0.5 + 0.25 * t, np.float32)
+        c.decode_step_keyed(q, wq, wv, wk, kgate=kap)
+        total += f64(wk, "f32") * kap[..., None]
+    assert np.allclose(f64(c.keys(), "f32").sum(axis=2), k0.sum(axis=2) + total, rtol=0, atol=1e-5)
+    # hard addressing: wq = 40 * MK[m*] makes the fp32 write weights exactly one-hot
+    c, mk, _ = make_cache(M, B, Hq, Hkv, d, "f32", ws=1.0, flags=1)
+    k0 = f64(mk, "f32")
+    target = 3
+    wq = syn.pack(40.0 * k0[:, :, target, :], "f32")
+    wv = key_inputs(c, 7, 1)
+    wk = key_inputs(c, 7, 2)
+    assert all(abs(c.probe_weights(0, h, wq[0, h], 1.0)[target] - 1.0) < 1e-12 for h in range(Hkv))
+    c.decode_step_keyed(None, wq, wv, wk, kgate=np.full((B, Hkv), 2.0, np.float32))
+    k1 = f64(c.keys(), "f32")
+    others = [m for m in range(M) if m != target]
+    assert np.array_equal(k1[:, :, others], k0[:, :, others])
+    assert np.array_equal(k1[:, :, target], (k0[:, :, target].astype(np.float32) + np.float32(2.0) * f64(wk, "f32").astype(np.float32)))
+
+
+def test_p15d_the_next_token_is_addressed_through_the_moved_keys():
+    M, B, Hq, Hkv, d = 6, 1, 2, 1, 3
+    c, mk, _ = make_cache(M, B, Hq, Hkv, d, "f32", rs=0.8, ws=0.6, flags=1)
+    q, wq, wv = step_inputs(c, 6, 0)
+    wk = key_inputs(c, 6, 0)
+    c.decode_step_keyed(q, wq, wv, wk)
+    k0, v0 = f64(mk, "f32")[0, 0], np.zeros((M, d))
+    ww = softmax64(0.6 * k0 @ f64(wq, "f32")[0, 0])
+    k1 = k0 + np.outer(ww, f64(wk, "f32")[0, 0])
+    v1 = v0 + np.outer(ww, f64(wv, "f32")[0, 0])
+    assert np.allclose(f64(c.keys(), "f32")[0, 0], k1, rtol=0, atol=1e-6)
+    q2, wq2, wv2 = step_inputs(c, 6, 1)
+    out2 = c.decode_step(q2, wq2, wv2)                       # a plain step on the moved keys
+    ww2 = softmax64(0.6 * k1 @ f64(wq2, "f32")[0, 0])
+    v2 = v1 + np.outer(ww2, f64(wv2, "f32")[0, 0])
+    for g in range(Hq):
+        want = brute_attention(f64(q2, "f32")[0, g], k1, v2, 0.8)
+        assert np.allclose(f64(out2, "f32")[0, g], want, rtol=0, atol=1e-6)
+
+
+def test_p15e_keyed_step_needs_per_sequence_keys_and_a_write():
+    c, _, _ = make_cache(8, 2, 2, 2, 4, "f32", flags=0)
+    q, wq, wv = step_inputs(c, 6, 0)
+    with pytest.raises(RuntimeError):
+        c.decode_step_keyed(q, wq, wv, key_inputs(c, 6, 0))          # keys shared by the batch
+    c, _, _ = make_cache(8, 2, 2, 2, 4, "f32", flags=1)
+    assert bct_ref.lib().bct_ref_decode_step_keyed(c._h, None, None, None, None, None, None, None) == 1
