@@ -141,7 +141,52 @@ def config_leg(name, pkg, syn, torch, np, reps=5):
                                 "frac_of_mfma_peak": alg / (pms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TF}
     del c, graph
     torch.cuda.empty_cache()
+    if name == "cfg3":
+        leg["per_sequence_keys"] = keyed_leg(w, pkg, torch, np, reps)
     return leg
+
+
+def keyed_leg(w, pkg, torch, np, reps):
+    """The same layer shape with one key table per sequence: the plain step (every sequence's keys are read
+    once: 3 x MV bytes) and the keyed step, whose write also moves the keys (bct_decode_step_keyed: the
+    keys are read and written once more, 5 x MV bytes).  Inputs drawn on the device (the cost does not
+    depend on values; parity is the tests' business)."""
+    dev = "cuda:0"
+    tdt = torch.bfloat16
+    g = torch.Generator(device=dev)
+    g.manual_seed(20241117)
+    c = pkg.BctCache(w.M, w.B, w.Hq, w.Hkv, w.d, tdt, w.scale, w.scale, flags=pkg.BCT_MK_PER_SEQUENCE, device=dev)
+    c.set_keys(torch.randn((w.B, w.Hkv, w.M, w.d), generator=g, device=dev).to(tdt))
+    q = torch.randn((w.B, w.Hq, w.d), generator=g, device=dev).to(tdt)
+    wq, wv, wk = (torch.randn((w.B, w.Hkv, w.d), generator=g, device=dev).to(tdt) for _ in range(3))
+    kap = torch.full((w.B, w.Hkv), 1e-3, device=dev)     # small key steps: the keys stay of unit scale over the run
+    out = torch.empty_like(q)
+    sz = 2
+    mv = w.B * w.Hkv * w.M * w.d * sz
+    io = w.B * (2 * w.Hq + 2 * w.Hkv) * w.d * sz
+    res = {}
+    for kind, fn, nbytes in (("plain_step", lambda: c.decode_step(q, wq, wv, out), 3 * mv + io),
+                             ("keyed_step", lambda: c.decode_step_keyed(q, wq, wv, wk, out, key_gate=kap),
+                              5 * mv + io + w.B * w.Hkv * w.d * sz)):
+        n = 10
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        us = []
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(n):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            us.append(e0.elapsed_time(e1) * 1e3 / n)
+        t_us = float(np.median(us))
+        res[kind] = {"us_per_layer_step": t_us, "algorithmic_bytes": nbytes, "GB/s": nbytes / (t_us * 1e-6) / 1e9,
+                     "frac_of_hbm_peak": nbytes / (t_us * 1e-6) / 1e9 / HBM_PEAK_GBS}
+    del c
+    torch.cuda.empty_cache()
+    return res
 
 
 def full_stack(w, L, steps, warmup, attention_ms_per_step):

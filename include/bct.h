@@ -147,6 +147,24 @@ bct_status bct_decode_step_gated(bct_cache* c, const void* q, const void* k_new,
 bct_status bct_prefill_gated(bct_cache* c, const void* q, const void* k_new, const void* v_new,
                              const float* gate, uint32_t T, void* out, void* hip_stream);
 
+/* The keyed step: a decode step whose write also moves the keys.  The paper never assigns MK (Algorithm 1
+ * takes it as an input) and names an adaptive update rule without an equation (section 3.5); this call is
+ * this library's reading of "keys updated by the same soft write": per memory, after the token's write
+ * to MV and its read, both addressed through the keys as they were,
+ *     MK = MK + kappa * ww^T . key_new      (the section 3.4 update applied to the key table, with the
+ *                                            token's own write weights ww; one fp32 FMA and one rounding
+ *                                            to the storage dtype per element)
+ * so the moved keys address the NEXT token.  key_new: [B][n_kv_heads][head_dim], storage dtype;
+ * key_gate: float32 [B][n_kv_heads] step sizes kappa, NULL = 1; gate as in bct_decode_step_gated.
+ * Needs per-sequence keys (BCT_MK_PER_SEQUENCE, else BCT_ERR_STATE) and a write (k_new, v_new); the
+ * read (q, out) may be absent.  key_gate = 0 is bct_decode_step_gated bit for bit and leaves MK alone.
+ * This is the only call besides bct_cache_set_keys / import that writes MK.  There is no chunk form:
+ * unrolling a chunk (section 3.5) needs keys that do not move.  Moves 2 MK more bytes than the plain
+ * step (the keys of every sequence are read and written once more). */
+bct_status bct_decode_step_keyed(bct_cache* c, const void* q, const void* k_new, const void* v_new,
+                                 const void* key_new, const float* gate, const float* key_gate, void* out,
+                                 void* hip_stream);
+
 /* Session swap: copies sequence b's slice of the state, MV[b] = n_kv_heads * M * head_dim contiguous
  * elements (device pointers), out of / into the cache; the memory of a sequence has a fixed size
  * whatever its length (section 4.3), so parking a session is one constant-size copy.  mk_* must be

@@ -32,6 +32,7 @@ EXPORTS = [
     "bct_cache_randomize_values", "bct_cache_export_sequence", "bct_cache_import_sequence", "bct_plan_query", "bct_cache_import", "bct_cache_steps",
     "bct_cache_regions", "bct_cache_destroy", "bct_strerror", "bct_last_error", "bct_stream_copy",
     "bct_profile_enable", "bct_profile_read", "bct_decode_step_static", "bct_static_scratch_bytes",
+    "bct_decode_step_keyed",
 ]
 
 
@@ -81,6 +82,7 @@ def lib() -> ctypes.CDLL:
     L.bct_cache_set_values.argtypes = [vp, vp, vp]
     L.bct_decode_step.argtypes = [vp, vp, vp, vp, vp, vp]
     L.bct_decode_step_static.argtypes = [vp, vp, vp, vp, vp, vp]
+    L.bct_decode_step_keyed.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp]
     L.bct_static_scratch_bytes.argtypes = []
     L.bct_prefill.argtypes = [vp, vp, vp, vp, u32, vp, vp]
     L.bct_plan_query.argtypes = [dp, ctypes.POINTER(bct_plan_info)]
@@ -280,6 +282,22 @@ class BctCache:
             self._call("bct_decode_step", _dptr(q), _dptr(k_new), _dptr(v_new), _dptr(out))
         else:
             self._call("bct_decode_step_gated", _dptr(q), _dptr(k_new), _dptr(v_new), _dptr(gate), _dptr(out))
+        return out
+
+    def decode_step_keyed(self, q, k_new, v_new, key_new, out=None, gate=None, key_gate=None):
+        """bct_decode_step_keyed: the write also moves the (per-sequence) keys after the token's read.
+        key_new: [B][Hkv][d]; gate / key_gate: float32 [B][Hkv] or None."""
+        torch = _torch()
+        self._check_gate(gate, (self.B, self.Hkv))
+        self._check_gate(key_gate, (self.B, self.Hkv))
+        self._check(q, (self.B, self.Hq, self.d), "q")
+        for t, n in ((k_new, "k_new"), (v_new, "v_new"), (key_new, "key_new")):
+            self._check(t, (self.B, self.Hkv, self.d), n)
+        if q is not None and out is None:
+            out = torch.empty_like(q)
+        self._check(out, (self.B, self.Hq, self.d), "out")
+        self._call("bct_decode_step_keyed", _dptr(q), _dptr(k_new), _dptr(v_new), _dptr(key_new), _dptr(gate),
+                   _dptr(key_gate), _dptr(out))
         return out
 
     def decode_step_static(self, q, k_new, v_new, out):

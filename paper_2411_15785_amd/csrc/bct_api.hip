@@ -162,9 +162,10 @@ bct_status check_io(const bct_cache* c, const void* q, const void* k_new, const 
 
 // The three launches of one decode step; q/kv batch strides allow a token of
 // a [B][T][H][d] chunk to be stepped in place.
+// key_new (optional): the keyed step, whose write also moves the per-sequence keys; key_gate its step sizes.
 bct_status run_decode(bct_cache* c, char* ws, const void* q, const void* k_new, const void* v_new, void* out,
                       uint64_t q_bstride, uint64_t kv_bstride, const float* gate, uint64_t gate_bstride,
-                      hipStream_t s) {
+                      hipStream_t s, const void* key_new = nullptr, const float* key_gate = nullptr) {
   bct::DecodeParams p = c->plan;
   p.mk = c->mk;
   p.mv = c->mv;
@@ -186,6 +187,7 @@ bct_status run_decode(bct_cache* c, char* ws, const void* q, const void* k_new, 
   hipError_t e;
   hipEvent_t* ev = (c->prof_n < c->prof_cap) ? &c->prof_ev[(size_t)c->prof_n * 4] : nullptr;
   if (ev && (e = hipEventRecord(ev[0], s)) != hipSuccess) return hip_fail(e, "event record");
+  if (key_new) p.fused = 0u;   // the one-launch step has no key update: take the streaming launches
   if (p.fused) {
     // a small cache: the whole step in one launch (timed as the MV pass)
     if (ev && (e = hipEventRecord(ev[1], s)) != hipSuccess) return hip_fail(e, "event record");
@@ -198,6 +200,18 @@ bct_status run_decode(bct_cache* c, char* ws, const void* q, const void* k_new, 
     if ((e = bct::launch_stream(p, c->desc.dtype, s)) != hipSuccess) return hip_fail(e, "MV pass launch");
     if (ev && (e = hipEventRecord(ev[2], s)) != hipSuccess) return hip_fail(e, "event record");
     if ((e = bct::launch_merge(p, c->desc.dtype, s)) != hipSuccess) return hip_fail(e, "merge launch");
+    if (key_new) {
+      // MK += kappa * ww^T wk: the same pass over a memory of M rows, now the keys of each sequence, with
+      // the write row's scores and statistics still in the scratch (computed from the keys as they
+      // were); no read.  Row 0 of every memory stays the write row: R keeps its value.
+      bct::DecodeParams pk = p;
+      pk.mv = c->mk;
+      pk.wv = key_new;
+      pk.gate = key_gate;
+      pk.has_read = 0u;
+      if ((e = bct::launch_normalise(pk, s)) != hipSuccess) return hip_fail(e, "normaliser launch (keys)");
+      if ((e = bct::launch_stream(pk, c->desc.dtype, s)) != hipSuccess) return hip_fail(e, "key pass launch");
+    }
   }
   if (ev) {
     if ((e = hipEventRecord(ev[3], s)) != hipSuccess) return hip_fail(e, "event record");
@@ -374,6 +388,24 @@ bct_status bct_decode_step_gated(bct_cache* c, const void* q, const void* k_new,
 bct_status bct_decode_step(bct_cache* c, const void* q, const void* k_new, const void* v_new, void* out,
                            void* hip_stream) {
   return bct_decode_step_gated(c, q, k_new, v_new, nullptr, out, hip_stream);
+}
+
+bct_status bct_decode_step_keyed(bct_cache* c, const void* q, const void* k_new, const void* v_new,
+                                 const void* key_new, const float* gate, const float* key_gate, void* out,
+                                 void* hip_stream) {
+  bct_status st = check_io(c, q, k_new, v_new, out);
+  if (st != BCT_OK) return st;
+  if (!k_new || !key_new) return fail(BCT_ERR_INVALID_ARG, "the keyed step needs a write (k_new, v_new) and key_new");
+  if (!aligned16(key_new)) return fail(BCT_ERR_MISALIGNED, "key_new must be 16-byte aligned");
+  if ((((uintptr_t)gate) | ((uintptr_t)key_gate)) & 3u) return fail(BCT_ERR_MISALIGNED, "gates must be 4-byte aligned");
+  if (!(c->desc.flags & BCT_MK_PER_SEQUENCE))
+    return fail(BCT_ERR_STATE, "the keys are shared by the batch: only per-sequence keys (BCT_MK_PER_SEQUENCE) can be written");
+  st = run_decode(c, c->ws, q, k_new, v_new, out, (uint64_t)c->desc.n_q_heads * c->desc.head_dim,
+                  (uint64_t)c->desc.n_kv_heads * c->desc.head_dim, gate, c->desc.n_kv_heads, (hipStream_t)hip_stream,
+                  key_new, key_gate);
+  if (st != BCT_OK) return st;
+  c->steps += 1;
+  return BCT_OK;
 }
 
 size_t bct_static_scratch_bytes(void) { return BCT_STATIC_SCRATCH_BYTES; }
