@@ -7,8 +7,9 @@
 //               slot tile.  (section 3.2 step 2 / Algorithm 1 "score"; the same
 //               pass serves the read.)
 //   2. normalise : merges the (max, sum) pairs into each row's softmax
-//               normaliser.  Only for memories with more than 64 slot tiles:
-//               up to 64 pairs are one per lane, and every workgroup of the MV
+//               normaliser.  Only for memories with more than 128 slot tiles
+//               (and for large grids of the several-query-heads MV pass):
+//               up to 128 pairs are two per lane, and every workgroup of the MV
 //               pass merges them itself while its loads are in flight.
 //   3. MV pass : ONE pass over MV: load, ww[m] * wv + MV (one fp32 FMA),
 //               round to storage, store, and accumulate the read output from
@@ -107,14 +108,12 @@ __global__ __launch_bounds__(64) void scores_mfma_bf16_kernel(const DecodeParams
       kf[t][ks] = *(const u32x4*)(mk + (size_t)(slot0 + t * 32 + col) * D + ks * 16 + half * 8);
 
   const uint32_t rtot = p.B * p.R;
-  for (uint32_t rb = blockIdx.z; rb * 32 < rtot; rb += gridDim.z) {
-    const uint32_t rho = rb * 32 + col;   // this lane's query row
-    const bool valid = rho < rtot;
-    uint32_t b = 0, r = 0;
-    u32x4 xf[KS];
-    if (valid) {
-      b = rho / p.R;
-      r = rho % p.R;
+  // The operand rows of the next block of 32 are requested before the products of the current one:
+  // a wavefront has its SIMD to itself, so nothing else would cover that latency.
+  auto load_rows = [&](uint32_t rb, u32x4 (&xf)[KS]) {
+    const uint32_t rho = rb * 32 + col;
+    if (rho < rtot) {
+      const uint32_t b = rho / p.R, r = rho % p.R;
       const uint16_t* x = (p.has_write && r == 0)
                               ? (const uint16_t*)p.wq + (size_t)b * p.kv_bstride + (size_t)h * D
                               : (const uint16_t*)p.q + (size_t)b * p.q_bstride +
@@ -125,6 +124,17 @@ __global__ __launch_bounds__(64) void scores_mfma_bf16_kernel(const DecodeParams
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) xf[ks] = (u32x4){0u, 0u, 0u, 0u};
     }
+  };
+  u32x4 xn[KS];
+  if (blockIdx.z * 32 < rtot) load_rows(blockIdx.z, xn);
+  for (uint32_t rb = blockIdx.z; rb * 32 < rtot; rb += gridDim.z) {
+    const uint32_t rho = rb * 32 + col;   // this lane's query row
+    const bool valid = rho < rtot;
+    const uint32_t b = valid ? rho / p.R : 0u, r = valid ? rho % p.R : 0u;
+    u32x4 xf[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) xf[ks] = xn[ks];
+    if ((rb + gridDim.z) * 32 < rtot) load_rows(rb + gridDim.z, xn);
     f32x16 c[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t)

@@ -112,6 +112,29 @@ __device__ __forceinline__ float xor_max(float v) {
   return v;
 }
 
+// One wavefront merges the per-tile (max, sum of exp2(score - max)) pairs of a row, up to 128 of them (lane l
+// takes tiles l and l + 64), into the row's (max, sum).  The operations and their order are those of
+// normalise_kernel, so both give the same bits.
+struct TileStats {
+  float2 a, c;
+};
+__device__ __forceinline__ TileStats load_tile_stats(const float2* st, uint32_t n_tiles, uint32_t lane) {
+  TileStats t = {make_float2(-INFINITY, 0.f), make_float2(-INFINITY, 0.f)};
+  if (lane < n_tiles) t.a = st[lane];
+  if (lane + 64 < n_tiles) t.c = st[lane + 64];
+  return t;
+}
+__device__ __forceinline__ float2 merge_tile_stats(const TileStats& t) {
+  const float mx = xor_max<1, 32>(fmaxf(t.a.x, t.c.x));
+  float sm = t.a.y * fast_exp2(t.a.x - mx);
+  sm += t.c.y * fast_exp2(t.c.x - mx);
+  return make_float2(mx, xor_sum<1, 32>(sm));
+}
+__device__ __forceinline__ float2 merge_tile_stats(const float2* st, uint32_t n_tiles, uint32_t lane) {
+  return merge_tile_stats(load_tile_stats(st, n_tiles, lane));
+}
+constexpr uint32_t kMaxMergedTiles = 128;
+
 }  // namespace bct
 
 #endif

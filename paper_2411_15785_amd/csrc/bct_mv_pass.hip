@@ -43,8 +43,8 @@ __device__ __forceinline__ void load_run(const float* p, float* w) {
   }
 }
 
-// NORM: the workgroup merges the per-tile (max, sum) pairs of its memory's rows itself (at most 64
-// tiles: one per lane, the same arithmetic as the normaliser kernel, so the same bits) while its MV
+// NORM: the workgroup merges the per-tile (max, sum) pairs of its memory's rows itself (at most 128
+// tiles: two per lane, the same arithmetic as the normaliser kernel, so the same bits) while its MV
 // loads are in flight, and the normaliser launch is dropped.
 template <typename DT, int D, int GT, bool WRITE, bool READ, int BS, int U, bool NORM>
 __global__ __launch_bounds__(BS) void mv_pass_kernel(const DecodeParams p) {
@@ -89,11 +89,9 @@ __global__ __launch_bounds__(BS) void mv_pass_kernel(const DecodeParams p) {
 #pragma unroll
     for (int r = 0; r < NR; ++r) {
       if ((uint32_t)r < R) {
-        float2 st = make_float2(-INFINITY, 0.f);
-        if ((uint32_t)lane < p.n_tiles) st = p.stats[((size_t)unit * R + r) * p.n_tiles + lane];
-        const float mx = xor_max<1, 32>(st.x);
-        const float sm = xor_sum<1, 32>(st.y * fast_exp2(st.x - mx));
-        float inv = 1.0f / sm;
+        const float2 ms = merge_tile_stats(p.stats + ((size_t)unit * R + r) * p.n_tiles, p.n_tiles, lane);
+        const float mx = ms.x;
+        float inv = 1.0f / ms.y;
         if (WRITE && r == 0 && p.gate) inv *= p.gate[(size_t)b * p.gate_bstride + h];
         nrm[r] = make_float2(mx, inv);
       }
@@ -208,14 +206,19 @@ static constexpr MvShape kWide = {512, 8};   // 64 KB per workgroup
 static constexpr MvShape kGqa = {128, 8};
 
 void plan_mv_pass(DecodeParams& p, int dtype) {
-  const MvShape s = (p.G <= 2) ? kSmall : (dtype == 1 && p.d == 128) ? kGqa : kWide;
+  const bool gqa = p.G > 2 && dtype == 1 && p.d == 128;
+  const MvShape s = (p.G <= 2) ? kSmall : gqa ? kGqa : kWide;
   p.mv_bs = s.bs;
   p.mv_u = s.u;
   const uint32_t row_bytes = p.d * (dtype == 0 ? 4u : 2u);
   const uint32_t spb = s.bs * s.u * 16u / row_bytes;  // slots per workgroup
   p.S = (p.M + spb - 1) / spb;
-  // with at most one (max, sum) pair per lane the MV pass merges them itself
-  p.fuse_norm = p.n_tiles <= 64 ? 1u : 0u;
+  // With at most two (max, sum) pairs per lane the workgroups of the MV pass merge them themselves.  In the
+  // pass for several query heads that costs every workgroup a little (1 + G rows; 13 us over the 65536
+  // workgroups of B = 64, Hkv = 8, M = 8192, where the normaliser launch takes 5), so a large grid leaves it
+  // to the launch.
+  const uint64_t wgs = (uint64_t)p.B * p.Hkv * p.S;
+  p.fuse_norm = (p.n_tiles <= kMaxMergedTiles && (!gqa || wgs <= 16384)) ? 1u : 0u;
 }
 
 template <typename DT, int D, int GT, int BS, int U, bool NORM>

@@ -26,9 +26,9 @@ namespace {
 
 typedef float f32x4v __attribute__((ext_vector_type(4)));
 
-template <bool WRITE, int BS, bool NORM>
+template <bool WRITE, int BS, bool NORM, int U>
 __global__ __launch_bounds__(BS) void mv_pass_gqa_kernel(const DecodeParams p) {
-  constexpr int D = 128, U = 8, NW = BS / 64, SPB = NW * 32;   // a wavefront covers 32 slots
+  constexpr int D = 128, NB = U / 8, NW = BS / 64, SPB = NW * 4 * U;   // a wavefront covers 4 U slots
   constexpr uint32_t W = WRITE ? 1u : 0u;
   __shared__ float s_red[NW * kMaxG * D];
 
@@ -40,7 +40,7 @@ __global__ __launch_bounds__(BS) void mv_pass_gqa_kernel(const DecodeParams p) {
   const uint32_t R = p.R, G = p.G, M = p.M;
 
   // M is a multiple of 64: the 32 slots of a wavefront are all inside the memory or all outside
-  const uint32_t slot0 = split * SPB + wave * 32 + sl * U;
+  const uint32_t slot0 = split * SPB + wave * (4 * U) + sl * U;
   const bool active = slot0 < M;
   uint16_t* mv = (uint16_t*)p.mv + ((size_t)unit * M + slot0) * D + sub * 8;
 
@@ -55,14 +55,17 @@ __global__ __launch_bounds__(BS) void mv_pass_gqa_kernel(const DecodeParams p) {
   // (max, 1/sum) of the write row and of this lane's read row (query head g = sub)
   float2 nw = make_float2(0.f, 0.f), nr = make_float2(0.f, 0.f);
   if (NORM) {
+    // all rows' pairs are requested before the first is reduced (rows past R repeat row 0 and are dropped)
+    TileStats ts[kMaxRows];
+#pragma unroll
+    for (uint32_t r = 0; r < kMaxRows; ++r)
+      ts[r] = load_tile_stats(p.stats + ((size_t)unit * R + (r < R ? r : 0u)) * p.n_tiles, p.n_tiles, lane);
 #pragma unroll
     for (uint32_t r = 0; r < kMaxRows; ++r) {
       if (r < R) {
-        float2 st = make_float2(-INFINITY, 0.f);
-        if ((uint32_t)lane < p.n_tiles) st = p.stats[((size_t)unit * R + r) * p.n_tiles + lane];
-        const float mx = xor_max<1, 32>(st.x);
-        const float sm = xor_sum<1, 32>(st.y * fast_exp2(st.x - mx));
-        float inv = 1.0f / sm;
+        const float2 ms = merge_tile_stats(ts[r]);
+        const float mx = ms.x;
+        float inv = 1.0f / ms.y;
         if (WRITE && r == 0) {
           if (p.gate) inv *= p.gate[(size_t)b * p.gate_bstride + h];
           nw = make_float2(mx, inv);
@@ -80,31 +83,32 @@ __global__ __launch_bounds__(BS) void mv_pass_gqa_kernel(const DecodeParams p) {
 #pragma unroll
   for (int u = 0; u < U; ++u) rw[u] = 0.f;
   if (active && (uint32_t)sub < G) {
-    const f32x4v a = *(const f32x4v*)(sc + (size_t)(W + sub) * M), c = *(const f32x4v*)(sc + (size_t)(W + sub) * M + 4);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      rw[i] = fast_exp2(a[i] - nr.x) * nr.y;
-      rw[4 + i] = fast_exp2(c[i] - nr.x) * nr.y;
+    for (int k = 0; k < U / 4; ++k) {
+      const f32x4v a = *(const f32x4v*)(sc + (size_t)(W + sub) * M + 4 * k);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) rw[4 * k + i] = fast_exp2(a[i] - nr.x) * nr.y;
     }
   }
-  // hi + lo bf16 parts of the lane's 8 weights: the A operands
-  u32x4 ahi, alo;
+  // hi + lo bf16 parts of the lane's weights, 8 slots per block: the A operands
+  u32x4 ahi[NB], alo[NB];
 #pragma unroll
-  for (int w2 = 0; w2 < 4; ++w2) {
-    const uint32_t hw = pack_bf16x2(rw[2 * w2], rw[2 * w2 + 1]);
-    ahi[w2] = hw;
-    alo[w2] = pack_bf16x2(rw[2 * w2] - __uint_as_float(hw << 16), rw[2 * w2 + 1] - __uint_as_float(hw & 0xFFFF0000u));
-  }
+  for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+    for (int w2 = 0; w2 < 4; ++w2) {
+      const float r0 = rw[8 * nb + 2 * w2], r1 = rw[8 * nb + 2 * w2 + 1];
+      const uint32_t hw = pack_bf16x2(r0, r1);
+      ahi[nb][w2] = hw;
+      alo[nb][w2] = pack_bf16x2(r0 - __uint_as_float(hw << 16), r1 - __uint_as_float(hw & 0xFFFF0000u));
+    }
 
   if (WRITE && active) {
     float ww[U];
-    {
-      const f32x4v a = *(const f32x4v*)sc, c = *(const f32x4v*)(sc + 4);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        ww[i] = fast_exp2(a[i] - nw.x) * nw.y;
-        ww[4 + i] = fast_exp2(c[i] - nw.x) * nw.y;
-      }
+    for (int k = 0; k < U / 4; ++k) {
+      const f32x4v a = *(const f32x4v*)(sc + 4 * k);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) ww[4 * k + i] = fast_exp2(a[i] - nw.x) * nw.y;
     }
     float wvf[8];
     const uint16_t* wv = (const uint16_t*)p.wv + (size_t)b * p.kv_bstride + (size_t)h * D;
@@ -124,16 +128,20 @@ __global__ __launch_bounds__(BS) void mv_pass_gqa_kernel(const DecodeParams p) {
   f32x4v acc[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
-    u32x4 t;
-#pragma unroll
-    for (int w2 = 0; w2 < 4; ++w2) {
-      const uint32_t lo = raw[2 * w2][e / 2], hi = raw[2 * w2 + 1][e / 2];
-      t[w2] = (e % 2 == 0) ? ((lo & 0xFFFFu) | (hi << 16)) : ((lo >> 16) | (hi & 0xFFFF0000u));
-    }
-    const bf16x8 bv = __builtin_bit_cast(bf16x8, t);
     f32x4v z = {0.f, 0.f, 0.f, 0.f};
-    z = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ahi), bv, z, 0, 0, 0);
-    acc[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, alo), bv, z, 0, 0, 0);
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      u32x4 t;
+#pragma unroll
+      for (int w2 = 0; w2 < 4; ++w2) {
+        const uint32_t lo = raw[8 * nb + 2 * w2][e / 2], hi = raw[8 * nb + 2 * w2 + 1][e / 2];
+        t[w2] = (e % 2 == 0) ? ((lo & 0xFFFFu) | (hi << 16)) : ((lo >> 16) | (hi & 0xFFFF0000u));
+      }
+      const bf16x8 bv = __builtin_bit_cast(bf16x8, t);
+      z = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ahi[nb]), bv, z, 0, 0, 0);
+      z = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, alo[nb]), bv, z, 0, 0, 0);
+    }
+    acc[e] = z;
   }
 
   // accumulator e, element v of lane (sub, sl): query head 4 sl + v, column 8 sub + e
@@ -162,24 +170,25 @@ __global__ __launch_bounds__(BS) void mv_pass_gqa_kernel(const DecodeParams p) {
 
 }  // namespace
 
-template <int BS>
+template <int BS, int U>
 static void launch_gqa_bs(const DecodeParams& p, hipStream_t s) {
   const dim3 grid = unit_grid(p.S, (uint64_t)p.B * p.Hkv), block(BS);
   if (p.has_write) {
-    if (p.fuse_norm) hipLaunchKernelGGL((mv_pass_gqa_kernel<true, BS, true>), grid, block, 0, s, p);
-    else hipLaunchKernelGGL((mv_pass_gqa_kernel<true, BS, false>), grid, block, 0, s, p);
+    if (p.fuse_norm) hipLaunchKernelGGL((mv_pass_gqa_kernel<true, BS, true, U>), grid, block, 0, s, p);
+    else hipLaunchKernelGGL((mv_pass_gqa_kernel<true, BS, false, U>), grid, block, 0, s, p);
   } else {
-    if (p.fuse_norm) hipLaunchKernelGGL((mv_pass_gqa_kernel<false, BS, true>), grid, block, 0, s, p);
-    else hipLaunchKernelGGL((mv_pass_gqa_kernel<false, BS, false>), grid, block, 0, s, p);
+    if (p.fuse_norm) hipLaunchKernelGGL((mv_pass_gqa_kernel<false, BS, true, U>), grid, block, 0, s, p);
+    else hipLaunchKernelGGL((mv_pass_gqa_kernel<false, BS, false, U>), grid, block, 0, s, p);
   }
 }
 
-// bf16, d = 128, G > 2, a step with a read.  The launch shape is the plan's (threads, 8 loads per lane).
+// bf16, d = 128, G > 2, a step with a read.  The launch shape is the plan's (threads, 8 or 16 loads per lane).
 hipError_t launch_stream_gqa(const DecodeParams& p, hipStream_t s) {
-  if (p.d != 128 || p.G <= 2 || p.G > kMaxG || !p.has_read || p.mv_u != 8) return hipErrorInvalidConfiguration;
-  if (p.mv_bs == 128) launch_gqa_bs<128>(p, s);
-  else if (p.mv_bs == 256) launch_gqa_bs<256>(p, s);
-  else if (p.mv_bs == 512) launch_gqa_bs<512>(p, s);
+  if (p.d != 128 || p.G <= 2 || p.G > kMaxG || !p.has_read) return hipErrorInvalidConfiguration;
+  if (p.mv_bs == 128 && p.mv_u == 8) launch_gqa_bs<128, 8>(p, s);
+  else if (p.mv_bs == 128 && p.mv_u == 16) launch_gqa_bs<128, 16>(p, s);
+  else if (p.mv_bs == 64 && p.mv_u == 16) launch_gqa_bs<64, 16>(p, s);
+  else if (p.mv_bs == 256 && p.mv_u == 8) launch_gqa_bs<256, 8>(p, s);
   else return hipErrorInvalidConfiguration;
   return hipGetLastError();
 }

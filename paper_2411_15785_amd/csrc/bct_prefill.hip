@@ -858,9 +858,9 @@ hipError_t launch_prefill_bf16(const PrefillParams& p0, hipStream_t s) {
     else hipLaunchKernelGGL(prefill_state_kernel<64>, g, dim3(256), 0, s, p);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
-  // every sub-chunk reads its starting state from the transposed copies in the workspace (sub-chunk 0:
-  // the copy made before the state kernel ran; without a write: all of them that copy), so one launch
-  // serves all sub-chunks
+  // every sub-chunk reads its starting state from the transposed copies in the workspace (with a write:
+  // copy c is what the state kernel left when it reached sub-chunk c, MV_0 for c = 0; without a write:
+  // the one copy of MV made above serves all of them), so one launch serves all sub-chunks
   if (p.has_read && (e = read(0, nb)) != hipSuccess) return e;
   return hipSuccess;
 }

@@ -214,6 +214,8 @@ def test_launch_plans_of_the_five_workloads(L):
     st, f4 = P.bct_plan_query(P.make_desc(w4.M, w4.B, w4.Hq, w4.Hkv, w4.d, P.BCT_F32, w4.scale, w4.scale))
     assert st == P.BCT_OK and f4["mv_workgroup"] == 512          # fp32 storage keeps the vector-ALU read
     assert c4["launches"] == 4
+    c5 = plan("cfg5")            # 128 partials per row, two per lane of the MV pass: no normaliser launch
+    assert c5["slots_per_stat"] == 128 and c5["normaliser_launch"] == 0 and c5["launches"] == 3
     c5 = plan("cfg5")
     assert c5["mv_splits"] * c5["mv_workgroup"] * c5["mv_loads_per_lane"] * 16 == 16384 * 128 * 2
     assert plan("cfg3", P.BCT_MK_PER_SEQUENCE)["scores_mfma"] == 0      # per-sequence keys: no shared contraction

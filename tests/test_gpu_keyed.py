@@ -52,7 +52,8 @@ CASES = [
     ("bf16_m512", 3, 4, 4, 128, 512, "bf16"),
     ("bf16_gqa4", 2, 8, 2, 128, 2112, "bf16"),         # MFMA read for the values, vector write-only pass for the keys
     ("bf16_d64_gqa8", 1, 8, 1, 64, 192, "bf16"),
-    ("bf16_m8192", 1, 2, 2, 128, 8192, "bf16"),        # more than 64 statistics tiles per row: the normaliser launch runs twice
+    ("bf16_m8192", 1, 2, 2, 128, 8192, "bf16"),        # 128 statistics tiles per row: two per lane of the value and key passes
+    ("bf16_m16384", 1, 2, 1, 128, 16384, "bf16"),      # more than that: the normaliser launch runs twice
 ]
 
 

@@ -110,6 +110,7 @@ SMALL = [
     ("bf16_m65536", 1, 1, 1, 128, 65536, "bf16"),       # the largest capacity the library accepts
     ("f32_d128_m65536", 1, 1, 1, 128, 65536, "f32"),
     ("bf16_gqa8_m4160", 1, 8, 1, 128, 4160, "bf16"),    # 8 query heads per KV head, 65 chunks of 64
+    ("bf16_gqa2_m8128", 1, 4, 2, 128, 8128, "bf16"),    # 127 chunks of 64: the MV pass merges two (max, sum) pairs per lane
     # Caches of at most 128 slots and 512 memories take the one-launch step, all others the four-launch
     # step (flags = 2 forces the latter): these are cases on both sides of the two limits
     ("f32_d64_units640", 40, 16, 16, 64, 128, "f32"),
