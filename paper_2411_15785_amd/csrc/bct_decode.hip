@@ -99,17 +99,14 @@ __global__ __launch_bounds__(64) void scores_mfma_bf16_kernel(const DecodeParams
   const int lane = threadIdx.x, col = lane % 32, half = lane / 32;
   const uint16_t* mk = (const uint16_t*)p.mk + (size_t)h * p.M * D;
   const uint32_t slot0 = tile * (32 * NT);
-
-  u32x4 kf[NT][KS];
-#pragma unroll
-  for (int t = 0; t < NT; ++t)
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks)
-      kf[t][ks] = *(const u32x4*)(mk + (size_t)(slot0 + t * 32 + col) * D + ks * 16 + half * 8);
-
   const uint32_t rtot = p.B * p.R;
-  // The operand rows of the next block of 32 are requested before the products of the current one:
-  // a wavefront has its SIMD to itself, so nothing else would cover that latency.
+
+  // Order of the requests: the first block of operand rows, then the keys 32 slots at a time.  Loads
+  // return in the order issued and the products below go through the keys in the same order, so the
+  // scores of the first 32 slots are computed and on their way to memory while the other keys are
+  // still arriving: the kernel's reads and its writes overlap, although every wavefront has its SIMD
+  // to itself.  The operand rows of the next block of 32 are requested before the products of the
+  // current one.
   auto load_rows = [&](uint32_t rb, u32x4 (&xf)[KS]) {
     const uint32_t rho = rb * 32 + col;
     if (rho < rtot) {
@@ -127,6 +124,14 @@ __global__ __launch_bounds__(64) void scores_mfma_bf16_kernel(const DecodeParams
   };
   u32x4 xn[KS];
   if (blockIdx.z * 32 < rtot) load_rows(blockIdx.z, xn);
+
+  u32x4 kf[NT][KS];
+#pragma unroll
+  for (int t = 0; t < NT; ++t)
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+      kf[t][ks] = *(const u32x4*)(mk + (size_t)(slot0 + t * 32 + col) * D + ks * 16 + half * 8);
+
   for (uint32_t rb = blockIdx.z; rb * 32 < rtot; rb += gridDim.z) {
     const uint32_t rho = rb * 32 + col;   // this lane's query row
     const bool valid = rho < rtot;
@@ -135,45 +140,43 @@ __global__ __launch_bounds__(64) void scores_mfma_bf16_kernel(const DecodeParams
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) xf[ks] = xn[ks];
     if ((rb + gridDim.z) * 32 < rtot) load_rows(rb + gridDim.z, xn);
-    f32x16 c[NT];
-#pragma unroll
-    for (int t = 0; t < NT; ++t)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) c[t][v] = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-      for (int t = 0; t < NT; ++t)
-        c[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[t][ks]),
-                                                       __builtin_bit_cast(bf16x8, xf[ks]), c[t], 0, 0, 0);
     const float scale = (p.has_write && r == 0) ? p.wscale_l2e : p.rscale_l2e;
     const size_t urow = (size_t)(b * p.Hkv + h) * p.R + r;
     float* dst = p.scores + urow * p.M + slot0 + half * 4;
-    float mx = -INFINITY;
+    // (max, sum of exp2(score - max)) of the row over the tile, 32 slots at a time
+    float mx = -INFINITY, sm = 0.f;
 #pragma unroll
-    for (int t = 0; t < NT; ++t)
+    for (int t = 0; t < NT; ++t) {
+      f32x16 c;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) c[v] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[t][ks]),
+                                                    __builtin_bit_cast(bf16x8, xf[ks]), c, 0, 0, 0);
+      float mt = -INFINITY;
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        c[t][v] *= scale;
-        mx = fmaxf(mx, c[t][v]);
+        c[v] *= scale;
+        mt = fmaxf(mt, c[v]);
       }
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    float sm = 0.f;
-#pragma unroll
-    for (int t = 0; t < NT; ++t)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) sm += fast_exp2(c[t][v] - mx);
-    sm += __shfl_xor(sm, 32, 64);
-    if (valid) {
-#pragma unroll
-      for (int t = 0; t < NT; ++t)
+      if (valid) {
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
-          const f32x4 o = {c[t][q4 * 4 + 0], c[t][q4 * 4 + 1], c[t][q4 * 4 + 2], c[t][q4 * 4 + 3]};
+          const f32x4 o = {c[q4 * 4 + 0], c[q4 * 4 + 1], c[q4 * 4 + 2], c[q4 * 4 + 3]};
           *(f32x4*)(dst + t * 32 + q4 * 8) = o;
         }
-      if (half == 0) p.stats[urow * p.n_tiles + tile] = make_float2(mx, sm);
+      }
+      mt = fmaxf(mt, __shfl_xor(mt, 32, 64));
+      float st = 0.f;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) st += fast_exp2(c[v] - mt);
+      st += __shfl_xor(st, 32, 64);
+      const float mn = fmaxf(mx, mt);
+      sm = sm * fast_exp2(mx - mn) + st * fast_exp2(mt - mn);
+      mx = mn;
     }
+    if (valid && half == 0) p.stats[urow * p.n_tiles + tile] = make_float2(mx, sm);
   }
 }
 

@@ -202,7 +202,7 @@ static constexpr MvShape kWide = {512, 8};   // 64 KB per workgroup
 // bf16, d = 128, G > 2: the MFMA read (bct_mv_pass_gqa.hip), again 16 KB one-shot workgroups.  Measured at
 // B = 64, Hkv = 8, G = 4, M = 8192 (MV pass alone): 128 threads 351 us, 256 threads 386 us, 512 threads 415 us,
 // against 429 us for the vector-ALU read in its best shape (512 x 8); the smaller workgroups leave more
-// partial outputs to sum (merge 21 us against 7 us).
+// partial outputs to sum (merge 21 us against 7 us).  16 loads per lane: 128 threads 397 us, 64 threads 357 us.
 static constexpr MvShape kGqa = {128, 8};
 
 void plan_mv_pass(DecodeParams& p, int dtype) {

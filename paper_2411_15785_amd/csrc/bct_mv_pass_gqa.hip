@@ -182,14 +182,12 @@ static void launch_gqa_bs(const DecodeParams& p, hipStream_t s) {
   }
 }
 
-// bf16, d = 128, G > 2, a step with a read.  The launch shape is the plan's (threads, 8 or 16 loads per lane).
+// bf16, d = 128, G > 2, a step with a read.  The launch shape is the plan's: 128 threads, 8 loads per lane
+// (the kernel is written for any multiple of 8 loads; 16 measured slower, see plan_mv_pass).
 hipError_t launch_stream_gqa(const DecodeParams& p, hipStream_t s) {
   if (p.d != 128 || p.G <= 2 || p.G > kMaxG || !p.has_read) return hipErrorInvalidConfiguration;
-  if (p.mv_bs == 128 && p.mv_u == 8) launch_gqa_bs<128, 8>(p, s);
-  else if (p.mv_bs == 128 && p.mv_u == 16) launch_gqa_bs<128, 16>(p, s);
-  else if (p.mv_bs == 64 && p.mv_u == 16) launch_gqa_bs<64, 16>(p, s);
-  else if (p.mv_bs == 256 && p.mv_u == 8) launch_gqa_bs<256, 8>(p, s);
-  else return hipErrorInvalidConfiguration;
+  if (p.mv_bs != 128 || p.mv_u != 8) return hipErrorInvalidConfiguration;
+  launch_gqa_bs<128, 8>(p, s);
   return hipGetLastError();
 }
 

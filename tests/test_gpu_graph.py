@@ -146,3 +146,60 @@ def test_captured_prefill_chunk_replays_exactly():
         assert torch.equal(graphed.values_view(), eager.values_view()), f"chunk {k}: state"
         junk = torch.randn(1 << 20, device="cuda:0").sum().item()
         assert np.isfinite(junk)
+
+
+def test_captured_static_and_keyed_steps_replay_exactly():
+    """The step that takes its scratch from the library's own device array (made for callers under graph
+    capture) and the step that also moves per-sequence keys, captured together as one graph: each replay gives
+    what the eager workspace step / eager keyed step give, bit for bit, state and keys included."""
+    import torch
+    import paper_2411_15785_amd as P
+    from oracle import bct_ref as R
+    w = syn.Workload("graph_sk", 1, 2, 4, 2, 128, 320, "bf16", 6)
+    e_plain = make_pair(w, R.RefCache, P.BctCache, mv0=True)[1]
+    g_static = make_pair(w, R.RefCache, P.BctCache, mv0=True)[1]
+    e_keyed = make_pair(w, R.RefCache, P.BctCache, flags=1, mv0=True)[1]
+    g_keyed = make_pair(w, R.RefCache, P.BctCache, flags=1, mv0=True)[1]
+    bf = dict(dtype=torch.bfloat16, device="cuda:0")
+    sq, swq = torch.empty((w.B, w.Hq, w.d), **bf), torch.empty((w.B, w.Hkv, w.d), **bf)
+    swv, swk = torch.empty_like(swq), torch.empty_like(swq)
+    kappa = torch.full((w.B, w.Hkv), 0.5, device="cuda:0")
+    o_static, o_keyed, o_plain, o_ekeyed = (torch.empty_like(sq) for _ in range(4))
+
+    def load_inputs(t):
+        q, wq, wv = (to_dev(a, w.dtype) for a in syn.make_step(w, t))
+        wk = to_dev(syn.pack(syn.normal(syn.layer_seed(0), 8, t, (w.B, w.Hkv, w.d)), w.dtype), w.dtype)
+        sq.copy_(q), swq.copy_(wq), swv.copy_(wv), swk.copy_(wk)
+
+    def graphed_steps():
+        g_static.decode_step_static(sq, swq, swv, o_static)
+        g_keyed.decode_step_keyed(sq, swq, swv, swk, out=o_keyed, key_gate=kappa)
+
+    def eager_steps():
+        e_plain.decode_step(sq, swq, swv, o_plain)
+        e_keyed.decode_step_keyed(sq, swq, swv, swk, out=o_ekeyed, key_gate=kappa)
+
+    load_inputs(0)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        graphed_steps()
+    torch.cuda.current_stream().wait_stream(side)
+    eager_steps()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    load_inputs(1)
+    with torch.cuda.graph(g):
+        graphed_steps()
+    for t in range(1, 6):
+        load_inputs(t)
+        g.replay()
+        eager_steps()
+        torch.cuda.synchronize()
+        assert torch.equal(o_static, o_plain), f"replay of step {t}: static-scratch step differs from eager"
+        assert torch.equal(g_static.values_view(), e_plain.values_view()), f"step {t}: state of the static-scratch step"
+        assert torch.equal(o_keyed, o_ekeyed), f"replay of step {t}: keyed step differs from eager"
+        assert torch.equal(g_keyed.values_view(), e_keyed.values_view()), f"step {t}: state of the keyed step"
+        assert torch.equal(g_keyed.keys_view(), e_keyed.keys_view()), f"step {t}: keys of the keyed step"
+        junk = torch.randn(1 << 20, device="cuda:0").sum().item()
+        assert np.isfinite(junk)

@@ -58,9 +58,9 @@ def R():
 
 def _progress(line):
     print(line, flush=True)
-    d = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
-    if os.path.isdir(d):
-        with open(os.path.join(d, "long_runs_progress.log"), "a") as f:
+    path = os.environ.get("BCT_TEST_PROGRESS_LOG")     # a file to append to, for runs whose stdout is captured
+    if path:
+        with open(path, "a") as f:
             f.write(line + "\n")
 
 
