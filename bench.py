@@ -72,7 +72,7 @@ def dominant_kernel(plan, w):
     if plan["one_launch"]:
         return f"decode_fused_kernel<{dt},{w.d},{gt}>"
     if w.dtype == "bf16" and w.d == 128 and w.G > 2:
-        return f"mv_pass_gqa_kernel<true,{plan['mv_workgroup']},{norm}>"
+        return f"mv_pass_gqa_kernel<true,{plan['mv_workgroup']},{norm},{plan['mv_loads_per_lane']}>"
     return f"mv_pass_kernel<{dt},{w.d},{gt},true,true,{plan['mv_workgroup']},{plan['mv_loads_per_lane']},{norm}>"
 
 
