@@ -25,6 +25,9 @@ int main() {
   bad |= bct_cache_init(&d, 0, NULL, 0, NULL, 0, NULL, &c) == BCT_OK;
   bad |= bct_decode_step(NULL, NULL, NULL, NULL, NULL, NULL) == BCT_OK;
   bad |= bct_prefill(NULL, NULL, NULL, NULL, 4, NULL, NULL) == BCT_OK;
+  bad |= bct_decode_step_static(NULL, NULL, NULL, NULL, NULL, NULL) != BCT_ERR_INVALID_ARG;
+  bad |= bct_decode_step_keyed(NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL) != BCT_ERR_INVALID_ARG;
+  bad |= bct_static_scratch_bytes() != ((size_t)8 << 20);
   bad |= bct_cache_steps(NULL, NULL) == BCT_OK;
   bct_cache_destroy(NULL);
   bad |= strlen(bct_strerror(BCT_ERR_MISALIGNED)) == 0;
