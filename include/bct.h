@@ -119,7 +119,7 @@ bct_status bct_decode_step(bct_cache* c, const void* q, const void* k_new, const
  * library's device image instead of the workspace given to bct_cache_init.  The array holds
  * bct_static_scratch_bytes() bytes (8 MiB) on every GPU the library runs on, for the life of the
  * process; a cache whose decode step needs more returns BCT_ERR_BUFFER_TOO_SMALL (config 2 of the
- * benchmark, B = 8, H = 32, M = 1024, needs 4.3 MiB; config 3 needs 101 MiB and does not fit).  The
+ * benchmark, B = 8, H = 32, M = 1024, needs 2.3 MiB; config 3 needs 101 MiB and does not fit).  The
  * call makes no allocation of any kind.  The device that is current at the call must be the cache's.
  * All calls on one GPU share that GPU's array (it keeps the last call's contents; nothing in it has
  * to be cleared between calls): calls that overlap in time on one GPU, from different streams or

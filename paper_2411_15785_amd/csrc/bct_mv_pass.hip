@@ -199,6 +199,20 @@ struct MvShape {
 static constexpr MvShape kSmall = {256, 4};  // 16 KB per workgroup
 static constexpr MvShape kWide = {512, 8};   // 64 KB per workgroup
 
+// Mid-size caches, one query head per KV head: one workgroup per memory, 16 loads per lane (256, 512 or 1024
+// threads for memories up to 64, 128, 256 KB).  No split of M, so no partial outputs and no merge launch;
+// worth it while one or two rounds of such workgroups cover the chip and the launches saved still count.
+// Measured inside a HIP graph, whole step, against the 16 KB shape (us):
+//   bf16 d = 128, M = 1024: 192 memories 27.2 -> 23.1, 256: 32.8 -> 28.5 (config 2 of the benchmark), 384: 44.7 -> 46.1,
+//                           512: 55.9 -> 54.1, 1024: 102 -> 109;  M = 512: 256: 17.5 -> 16.5, 512: 31.8 -> 26.5,
+//                           1024: 55.8 -> 55.4, 2048: 102 -> 109;  M = 256: 512: 17.2 -> 15.8, 1024: 31.9 -> 26.6
+//   fp32 d = 64,  M = 1024: 192: 30.9 -> 29.4, 256: 37.7 -> 36.1, 384: 53.8 -> 59.2;  M = 512: 512: 37.1 -> 33.6
+//   fp32 d = 128, M = 512: 256: 39.9 -> 36.3, 384: 56.2 -> 59.2;  bf16 d = 64, M = 2048: 256: 34.2 -> 28.3
+//   fewer than 192 memories lose (128 x M = 1024: 18.3 -> 19.6; 8: 10.2 -> 13.5): too few workgroups.
+// Hence: at least 192 memories and at most 64 MB of MV in all.
+static constexpr uint64_t kWholeMinBytes = 32u << 10, kWholeMaxBytes = 256u << 10;
+static constexpr uint64_t kWholeMinUnits = 192, kWholeMaxTotal = 64ull << 20;
+
 // bf16, d = 128, G > 2: the MFMA read (bct_mv_pass_gqa.hip), again 16 KB one-shot workgroups.  Measured at
 // B = 64, Hkv = 8, G = 4, M = 8192 (MV pass alone): 128 threads 351 us, 256 threads 386 us, 512 threads 415 us,
 // against 429 us for the vector-ALU read in its best shape (512 x 8); the smaller workgroups leave more
@@ -207,7 +221,10 @@ static constexpr MvShape kGqa = {128, 8};
 
 void plan_mv_pass(DecodeParams& p, int dtype) {
   const bool gqa = p.G > 2 && dtype == 1 && p.d == 128;
-  const MvShape s = (p.G <= 2) ? kSmall : gqa ? kGqa : kWide;
+  MvShape s = (p.G <= 2) ? kSmall : gqa ? kGqa : kWide;
+  const uint64_t mem = (uint64_t)p.M * p.d * (dtype == 0 ? 4u : 2u), units = (uint64_t)p.B * p.Hkv;
+  if (p.G <= 1 && mem > kWholeMinBytes && mem <= kWholeMaxBytes && units >= kWholeMinUnits && units * mem <= kWholeMaxTotal)
+    s = MvShape{mem <= (64u << 10) ? 256u : mem <= (128u << 10) ? 512u : 1024u, 16u};
   p.mv_bs = s.bs;
   p.mv_u = s.u;
   const uint32_t row_bytes = p.d * (dtype == 0 ? 4u : 2u);
@@ -241,6 +258,13 @@ static void launch_mode(const DecodeParams& p, hipStream_t s) {
 template <typename DT, int D>
 static bool launch_shape(const DecodeParams& p, hipStream_t s) {
   const uint32_t G = p.G;
+  if (p.mv_u == 16 && G <= 1 && p.fuse_norm) {   // one workgroup per memory (at most 2048 slots: the statistics always fit)
+    if (p.mv_bs == 1024) launch_mode_n<DT, D, 1, 1024, 16, true>(p, s);
+    else if (p.mv_bs == 512) launch_mode_n<DT, D, 1, 512, 16, true>(p, s);
+    else if (p.mv_bs == 256) launch_mode_n<DT, D, 1, 256, 16, true>(p, s);
+    else return false;
+    return true;
+  }
   if (p.mv_bs == kSmall.bs && p.mv_u == kSmall.u && G <= 2) {
     if (G <= 1) launch_mode<DT, D, 1, 256, 4>(p, s);
     else launch_mode<DT, D, 2, 256, 4>(p, s);

@@ -202,8 +202,13 @@ def test_launch_plans_of_the_five_workloads(L):
     assert c1["one_launch"] == 1 and c1["launches"] == 1
     c1s = plan("cfg1", P.BCT_STEP_STREAMING)
     assert c1s["one_launch"] == 0 and c1s["scores_mfma"] == 0 and c1s["launches"] == 2     # one split: no merge
-    c2 = plan("cfg2")            # M = 1024: too large for the one-launch step
+    c2 = plan("cfg2")            # M = 1024: too large for the one-launch step; 256 memories of 256 KB: one MV-pass workgroup each
     assert c2["one_launch"] == 0 and c2["scores_mfma"] == 1
+    assert c2["mv_workgroup"] == 1024 and c2["mv_loads_per_lane"] == 16 and c2["mv_splits"] == 1 and c2["launches"] == 2
+    w2 = syn.WORKLOADS["cfg2"]
+    for batch, splits in ((4, 16), (5, 16), (6, 1), (8, 1), (9, 16)):     # 128, 160: too few memories; 288 x 256 KB: too much in all
+        st, pl = P.bct_plan_query(P.make_desc(w2.M, batch, w2.Hq, w2.Hkv, w2.d, P.BCT_BF16, w2.scale, w2.scale))
+        assert st == P.BCT_OK and pl["mv_splits"] == splits, (batch, pl)
     c3 = plan("cfg3")            # the headline shape: scores, MV pass (merging the 32 partials per row itself), merge
     assert c3 == dict(launches=3, one_launch=0, scores_mfma=1, slots_per_stat=128, normaliser_launch=0,
                       mv_workgroup=256, mv_loads_per_lane=4, mv_splits=64)

@@ -111,6 +111,12 @@ SMALL = [
     ("f32_d128_m65536", 1, 1, 1, 128, 65536, "f32"),
     ("bf16_gqa8_m4160", 1, 8, 1, 128, 4160, "bf16"),    # 8 query heads per KV head, 65 chunks of 64
     ("bf16_gqa2_m8128", 1, 4, 2, 128, 8128, "bf16"),    # 127 chunks of 64: the MV pass merges two (max, sum) pairs per lane
+    # 192 memories or more of 32 KB to 256 KB, one query head per KV head: one workgroup of the MV pass per memory
+    ("bf16_whole_m512", 8, 32, 32, 128, 512, "bf16"),         # 128 KB per memory: 512 threads
+    ("f32_d64_whole_m320", 6, 32, 32, 64, 320, "f32"),        # 80 KB: 512 threads, 192 of their 512 slots idle
+    ("bf16_d64_whole_m2048", 8, 32, 32, 64, 2048, "bf16"),    # 256 KB: 1024 threads, the largest
+    ("f32_d128_whole_m128", 7, 28, 28, 128, 128, "f32"),      # 64 KB: 256 threads; 196 memories
+    ("bf16_m1024_units128", 4, 32, 32, 128, 1024, "bf16"),    # too few memories: 16 KB workgroups, 16 partials
     # Caches of at most 128 slots and 512 memories take the one-launch step, all others the four-launch
     # step (flags = 2 forces the latter): these are cases on both sides of the two limits
     ("f32_d64_units640", 40, 16, 16, 64, 128, "f32"),

@@ -71,12 +71,16 @@ def _run_and_compare(P, w, steps):
 def test_static_scratch_step_equals_workspace_step_twice_in_a_row(P):
     import torch
     assert P.lib().bct_static_scratch_bytes() == 8 << 20
-    # first call: config 2's shape (4.3 MiB of scratch: split-M partials, 16 tiles per row); second, right
-    # after it on the same GPU array, a smaller fp32 cache with several query heads per KV head
-    big = syn.WORKLOADS["cfg2"]
+    # first call: half of config 2's batch (2.1 MiB of scratch: scores, 32 statistics tiles per row, 16 split-M
+    # partial outputs per memory); second, right after it on the same GPU array, a smaller fp32 cache with
+    # several query heads per KV head; third, config 2 itself (one workgroup per memory, no partials)
+    big = syn.Workload("static_big", 1, 4, 32, 32, 128, 1024, "bf16", 5)
     small = syn.Workload("static_small", 1, 3, 8, 4, 64, 320, "f32", 6)
+    st, plan = P.bct_plan_query(P.make_desc(big.M, big.B, big.Hq, big.Hkv, big.d, P.BCT_BF16, big.scale, big.scale))
+    assert st == P.BCT_OK and plan["mv_splits"] == 16
     _run_and_compare(P, big, 5)
     _run_and_compare(P, small, 6)
+    _run_and_compare(P, syn.WORKLOADS["cfg2"], 3)
     torch.cuda.synchronize()
 
 
