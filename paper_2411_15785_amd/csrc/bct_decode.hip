@@ -25,8 +25,10 @@ namespace bct {
 
 // ------------------------------------------------------------------ scores (generic)
 
-// One workgroup = one (slot tile of 64, memory).  LPS lanes share a slot: each
-// holds 16 bytes of the key row and of the query row.
+// One workgroup = one (slot tile of 64, memory): 16 KB of keys.  LPS lanes share a slot: each
+// holds 16 bytes of the key row and of every query row.  All key loads of a lane are requested
+// before the first product (one memory latency per workgroup, as in the MV pass); keys that belong to
+// one sequence are read once per step and bypass the caches, shared keys stay cacheable.
 template <typename DT, int D>
 __global__ __launch_bounds__(256) void scores_generic_kernel(const DecodeParams p) {
   typedef typename DT::elem elem;
@@ -34,6 +36,7 @@ __global__ __launch_bounds__(256) void scores_generic_kernel(const DecodeParams 
   constexpr int LPS = D / E;       // lanes per slot
   constexpr int SPP = 256 / LPS;   // slots per pass of the workgroup
   constexpr int TILE = 64;
+  constexpr int NP = TILE / SPP;   // passes: key rows per lane
   static_assert(TILE % SPP == 0, "tile must be a whole number of passes");
 
   __shared__ float s_sc[kMaxRows][TILE];
@@ -42,42 +45,53 @@ __global__ __launch_bounds__(256) void scores_generic_kernel(const DecodeParams 
   if (unit >= p.B * p.Hkv) return;
   const uint32_t b = unit / p.Hkv, h = unit % p.Hkv;
   const int tid = threadIdx.x, sub = tid % LPS, sl = tid / LPS;
-  const elem* mk = (const elem*)p.mk + (size_t)(p.mk_per_seq ? unit : h) * p.M * D;
+  const uint32_t R = p.R;
+  const elem* mk = (const elem*)p.mk + ((size_t)(p.mk_per_seq ? unit : h) * p.M + tile * TILE + sl) * D + sub * E;
 
-  for (int pass = 0; pass < TILE / SPP; ++pass) {
-    const uint32_t slot = tile * TILE + pass * SPP + sl;
-    float kf[E];
-    unpack16<DT>(*(const u32x4*)(mk + (size_t)slot * D + sub * E), kf);
-    for (uint32_t r = 0; r < p.R; ++r) {
-      const elem* x;
-      float scale;
-      if (p.has_write && r == 0) {
-        x = (const elem*)p.wq + (size_t)b * p.kv_bstride + (size_t)h * D;
-        scale = p.wscale_l2e;
-      } else {
-        x = (const elem*)p.q + (size_t)b * p.q_bstride + (size_t)(h * p.G + (r - p.has_write)) * D;
-        scale = p.rscale_l2e;
-      }
-      float xf[E];
-      unpack16<DT>(*(const u32x4*)(x + sub * E), xf);
-      float dot = 0.f;
+  u32x4 kraw[NP];
+  if (p.mk_per_seq) {
 #pragma unroll
-      for (int e = 0; e < E; ++e) dot = __builtin_fmaf(kf[e], xf[e], dot);
-      dot = xor_sum<1, LPS / 2>(dot);
-      if (sub == 0) {
-        const float s = dot * scale;
-        s_sc[r][pass * SPP + sl] = s;
-        p.scores[((size_t)unit * p.R + r) * p.M + slot] = s;
+    for (int i = 0; i < NP; ++i) kraw[i] = __builtin_nontemporal_load((const u32x4*)(mk + (size_t)i * SPP * D));
+  } else {
+#pragma unroll
+    for (int i = 0; i < NP; ++i) kraw[i] = *(const u32x4*)(mk + (size_t)i * SPP * D);
+  }
+  float xf[kMaxRows][E], scale[kMaxRows];
+#pragma unroll
+  for (uint32_t r = 0; r < kMaxRows; ++r) {
+    if (r < R) {
+      const elem* x = (p.has_write && r == 0)
+                          ? (const elem*)p.wq + (size_t)b * p.kv_bstride + (size_t)h * D
+                          : (const elem*)p.q + (size_t)b * p.q_bstride + (size_t)(h * p.G + (r - p.has_write)) * D;
+      unpack16<DT>(*(const u32x4*)(x + sub * E), xf[r]);
+      scale[r] = (p.has_write && r == 0) ? p.wscale_l2e : p.rscale_l2e;
+    }
+  }
+  float* sc = p.scores + (size_t)unit * R * p.M + tile * TILE;
+#pragma unroll
+  for (int i = 0; i < NP; ++i) {
+    float kf[E];
+    unpack16<DT>(kraw[i], kf);
+#pragma unroll
+    for (uint32_t r = 0; r < kMaxRows; ++r) {
+      if (r < R) {
+        float dot = 0.f;
+#pragma unroll
+        for (int e = 0; e < E; ++e) dot = __builtin_fmaf(kf[e], xf[r][e], dot);
+        dot = xor_sum<1, LPS / 2>(dot);
+        if (sub == 0) s_sc[r][i * SPP + sl] = dot * scale[r];
       }
     }
   }
   __syncthreads();
+  // a wavefront per row: the tile's 64 scores leave as one 256-byte store, then the row's (max, sum)
   const int wave = tid / 64, lane = tid % 64;
-  for (uint32_t r = wave; r < p.R; r += 4) {
+  for (uint32_t r = wave; r < R; r += 4) {
     const float v = s_sc[r][lane];
+    sc[(size_t)r * p.M + lane] = v;
     const float mx = xor_max<1, 32>(v);
     const float sm = xor_sum<1, 32>(fast_exp2(v - mx));
-    if (lane == 0) p.stats[((size_t)unit * p.R + r) * p.n_tiles + tile] = make_float2(mx, sm);
+    if (lane == 0) p.stats[((size_t)unit * R + r) * p.n_tiles + tile] = make_float2(mx, sm);
   }
 }
 

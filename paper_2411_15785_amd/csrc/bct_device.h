@@ -99,16 +99,43 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 // Butterfly reductions over the lanes whose ids differ in the bits of `mask`
 // (a contiguous range of bits given as lowest and highest xor distance).
 // The butterfly visits partners in a fixed order, so results are reproducible.
+//
+// A butterfly that starts at distance 1 takes its partners at distances 1, 2, 4 and 8 through the
+// data-parallel-primitive path of the vector ALU (no trip through the LDS crossbar that a general
+// lane exchange makes): distances 1 and 2 are quad permutations; at distance 4 every quad already
+// holds one value, so the lane 7 - i of the half row (row_half_mirror) holds what lane i ^ 4 holds,
+// and at distance 8 the lane 15 - i of the row (row_mirror) holds what lane i ^ 8 holds.  Same
+// operands in the same order as the plain butterfly, so the same bits.
+template <int CTRL>
+__device__ __forceinline__ float dpp_partner(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+template <int LO, int O>
+__device__ __forceinline__ float xor_partner(float v) {
+  if constexpr (LO == 1 && O == 1) return dpp_partner<0xB1>(v);        // quad_perm [1, 0, 3, 2]
+  else if constexpr (LO == 1 && O == 2) return dpp_partner<0x4E>(v);   // quad_perm [2, 3, 0, 1]
+  else if constexpr (LO == 1 && O == 4) return dpp_partner<0x141>(v);  // row_half_mirror
+  else if constexpr (LO == 1 && O == 8) return dpp_partner<0x140>(v);  // row_mirror
+  else return __shfl_xor(v, O, 64);
+}
 template <int LO, int HI>
 __device__ __forceinline__ float xor_sum(float v) {
-#pragma unroll
-  for (int o = LO; o <= HI; o <<= 1) v += __shfl_xor(v, o, 64);
+  v += xor_partner<LO, LO>(v);
+  if constexpr (2 * LO <= HI) v += xor_partner<LO, 2 * LO>(v);
+  if constexpr (4 * LO <= HI) v += xor_partner<LO, 4 * LO>(v);
+  if constexpr (8 * LO <= HI) v += xor_partner<LO, 8 * LO>(v);
+  if constexpr (16 * LO <= HI) v += xor_partner<LO, 16 * LO>(v);
+  if constexpr (32 * LO <= HI) v += xor_partner<LO, 32 * LO>(v);
   return v;
 }
 template <int LO, int HI>
 __device__ __forceinline__ float xor_max(float v) {
-#pragma unroll
-  for (int o = LO; o <= HI; o <<= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  v = fmaxf(v, xor_partner<LO, LO>(v));
+  if constexpr (2 * LO <= HI) v = fmaxf(v, xor_partner<LO, 2 * LO>(v));
+  if constexpr (4 * LO <= HI) v = fmaxf(v, xor_partner<LO, 4 * LO>(v));
+  if constexpr (8 * LO <= HI) v = fmaxf(v, xor_partner<LO, 8 * LO>(v));
+  if constexpr (16 * LO <= HI) v = fmaxf(v, xor_partner<LO, 16 * LO>(v));
+  if constexpr (32 * LO <= HI) v = fmaxf(v, xor_partner<LO, 32 * LO>(v));
   return v;
 }
 
