@@ -29,7 +29,7 @@ namespace bct {
 // holds 16 bytes of the key row and of every query row.  All key loads of a lane are requested
 // before the first product (one memory latency per workgroup, as in the MV pass); keys that belong to
 // one sequence are read once per step and bypass the caches, shared keys stay cacheable.
-template <typename DT, int D>
+template <typename DT, int D, int RT>
 __global__ __launch_bounds__(256) void scores_generic_kernel(const DecodeParams p) {
   typedef typename DT::elem elem;
   constexpr int E = DT::kElemsPerVec;
@@ -39,7 +39,7 @@ __global__ __launch_bounds__(256) void scores_generic_kernel(const DecodeParams 
   constexpr int NP = TILE / SPP;   // passes: key rows per lane
   static_assert(TILE % SPP == 0, "tile must be a whole number of passes");
 
-  __shared__ float s_sc[kMaxRows][TILE];
+  __shared__ float s_sc[RT][TILE];
 
   const uint32_t tile = blockIdx.x, unit = block_unit();
   if (unit >= p.B * p.Hkv) return;
@@ -56,9 +56,9 @@ __global__ __launch_bounds__(256) void scores_generic_kernel(const DecodeParams 
 #pragma unroll
     for (int i = 0; i < NP; ++i) kraw[i] = *(const u32x4*)(mk + (size_t)i * SPP * D);
   }
-  float xf[kMaxRows][E], scale[kMaxRows];
+  float xf[RT][E], scale[RT];
 #pragma unroll
-  for (uint32_t r = 0; r < kMaxRows; ++r) {
+  for (uint32_t r = 0; r < RT; ++r) {
     if (r < R) {
       const elem* x = (p.has_write && r == 0)
                           ? (const elem*)p.wq + (size_t)b * p.kv_bstride + (size_t)h * D
@@ -73,7 +73,7 @@ __global__ __launch_bounds__(256) void scores_generic_kernel(const DecodeParams 
     float kf[E];
     unpack16<DT>(kraw[i], kf);
 #pragma unroll
-    for (uint32_t r = 0; r < kMaxRows; ++r) {
+    for (uint32_t r = 0; r < RT; ++r) {
       if (r < R) {
         float dot = 0.f;
 #pragma unroll
@@ -328,6 +328,15 @@ static hipError_t launch_scores_mfma(const DecodeParams& p, hipStream_t s) {
   return hipGetLastError();
 }
 
+// RT: the score rows of a memory the instantiation has registers for (write + read queries)
+template <typename DT, int D>
+static void launch_scores_generic(const DecodeParams& p, dim3 grid, hipStream_t s) {
+  if (p.R <= 2) hipLaunchKernelGGL((scores_generic_kernel<DT, D, 2>), grid, dim3(256), 0, s, p);
+  else if (p.R <= 3) hipLaunchKernelGGL((scores_generic_kernel<DT, D, 3>), grid, dim3(256), 0, s, p);
+  else if (p.R <= 5) hipLaunchKernelGGL((scores_generic_kernel<DT, D, 5>), grid, dim3(256), 0, s, p);
+  else hipLaunchKernelGGL((scores_generic_kernel<DT, D, (int)kMaxRows>), grid, dim3(256), 0, s, p);
+}
+
 hipError_t launch_scores(const DecodeParams& p, int dtype, hipStream_t s) {
   if (use_mfma_scores(p, dtype)) {
     const uint32_t nt = p.stat_tile / 32;
@@ -342,11 +351,11 @@ hipError_t launch_scores(const DecodeParams& p, int dtype, hipStream_t s) {
   }
   const dim3 grid = unit_grid(p.M / 64, (uint64_t)p.B * p.Hkv);
   if (dtype == 0) {
-    if (p.d == 128) hipLaunchKernelGGL((scores_generic_kernel<F32, 128>), grid, dim3(256), 0, s, p);
-    else hipLaunchKernelGGL((scores_generic_kernel<F32, 64>), grid, dim3(256), 0, s, p);
+    if (p.d == 128) launch_scores_generic<F32, 128>(p, grid, s);
+    else launch_scores_generic<F32, 64>(p, grid, s);
   } else {
-    if (p.d == 128) hipLaunchKernelGGL((scores_generic_kernel<BF16, 128>), grid, dim3(256), 0, s, p);
-    else hipLaunchKernelGGL((scores_generic_kernel<BF16, 64>), grid, dim3(256), 0, s, p);
+    if (p.d == 128) launch_scores_generic<BF16, 128>(p, grid, s);
+    else launch_scores_generic<BF16, 64>(p, grid, s);
   }
   return hipGetLastError();
 }
