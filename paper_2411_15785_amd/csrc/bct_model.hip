@@ -410,13 +410,32 @@ __global__ __launch_bounds__(256) void argmax_kernel(const uint16_t* logits, int
   const uint16_t* row = logits + (size_t)blockIdx.x * N;
   float best = -INFINITY;
   uint32_t bi = 0xFFFFFFFFu;
-  for (uint32_t j = threadIdx.x; j < N; j += 256) {
-    const float v = bf16f(row[j]);
+  auto take = [&](float v, uint32_t j) {
     if (v > best || bi == 0xFFFFFFFFu) {  // ascending j: a later equal value never replaces an earlier one
       best = v;
       bi = j;
     }
+  };
+  // 16-byte vectors (8 logits), four in flight per thread; rows start 16-byte aligned when N is a multiple of 8
+  const uint32_t nvec = (N % 8 == 0) ? N / 8 : 0u;
+  for (uint32_t v0 = threadIdx.x; v0 < nvec; v0 += 4 * 256) {
+    u32x4 raw[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (v0 + u * 256 < nvec) raw[u] = *(const u32x4*)(row + (size_t)(v0 + u * 256) * 8);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (v0 + u * 256 < nvec) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const uint32_t j = (v0 + u * 256) * 8 + 2 * e;
+          take(__uint_as_float(raw[u][e] << 16), j);
+          take(__uint_as_float(raw[u][e] & 0xFFFF0000u), j + 1);
+        }
+      }
+    }
   }
+  for (uint32_t j = nvec * 8 + threadIdx.x; j < N; j += 256) take(bf16f(row[j]), j);
   sv[threadIdx.x] = best;
   si[threadIdx.x] = bi;
   __syncthreads();
