@@ -86,6 +86,14 @@ struct Tile {
       missing |= ok ? 0u : (1u << i);
     }
   }
+  // the same for data read once (past the caches, so that it does not push out what is reused)
+  __device__ __forceinline__ void fetch_block_once(const uint16_t* src, size_t src_ld) {
+    const int ch = threadIdx.x % CPR, r0 = threadIdx.x / CPR;
+#pragma unroll
+    for (int i = 0; i < N; ++i)
+      v[i] = __builtin_nontemporal_load((const u32x4*)(src + (size_t)(r0 + i * RPP) * src_ld + ch * 8));
+    missing = 0;
+  }
   // rows at src + r * src_ld, all present
   __device__ __forceinline__ void fetch_block(const uint16_t* src, size_t src_ld) {
     const int ch = threadIdx.x % CPR, r0 = threadIdx.x / CPR;
@@ -357,14 +365,14 @@ __global__ __launch_bounds__(512) void prefill_read_only_kernel(const PrefillPar
   Tile<64, D, NT> tk;
   Tile<D, 64, NT> tv;
   tk.fetch_block(mk, D);
-  tv.fetch_block(mvt, p.M);
+  tv.fetch_block_once(mvt, p.M);
   for (uint32_t m0 = 0; m0 < p.M; m0 += 64) {
     __syncthreads();
     tk.put(sK, LD);
     tv.put(sVt, LP);
     if (m0 + 64 < p.M) {  // next tiles, in flight during this tile's products
       tk.fetch_block(mk + (size_t)(m0 + 64) * D, D);
-      tv.fetch_block(mvt + m0 + 64, p.M);
+      tv.fetch_block_once(mvt + m0 + 64, p.M);
     }
     __syncthreads();
     {
@@ -505,7 +513,7 @@ __global__ __launch_bounds__(512) void prefill_read_online_kernel(const PrefillP
   Tile<64, D, NT> tk;
   Tile<D, 64, NT> tv;
   tk.fetch_block(mk, D);
-  tv.fetch_block(mvt, p.M);
+  tv.fetch_block_once(mvt, p.M);
   uint32_t it = 0;
   for (uint32_t m0 = 0; m0 < p.M; m0 += 64, ++it) {
     __syncthreads();
@@ -513,7 +521,7 @@ __global__ __launch_bounds__(512) void prefill_read_online_kernel(const PrefillP
     tv.put(sVt, LP);
     if (m0 + 64 < p.M) {  // next tiles, in flight during this tile's products
       tk.fetch_block(mk + (size_t)(m0 + 64) * D, D);
-      tv.fetch_block(mvt + m0 + 64, p.M);
+      tv.fetch_block_once(mvt + m0 + 64, p.M);
     }
     if (threadIdx.x == 0) sFlag[(it + 1) & 1] = 0u;   // last read before this tile's first barrier
     __syncthreads();
@@ -743,7 +751,7 @@ __global__ __launch_bounds__(256, 2) void prefill_state_kernel(const PrefillPara
       if (m0 + 8 * ch < p.M) {
 #pragma unroll
         for (int r = threadIdx.x / 16; r < D; r += NT / 16)
-          *(u32x4*)(sn + (size_t)r * p.M + 8 * ch) = *(const u32x4*)(sSnap + r * LS + 8 * ch);
+          __builtin_nontemporal_store(*(const u32x4*)(sSnap + r * LS + 8 * ch), (u32x4*)(sn + (size_t)r * p.M + 8 * ch));
       }
     }
     __syncthreads();
@@ -805,7 +813,7 @@ __global__ __launch_bounds__(256, 2) void prefill_state_kernel(const PrefillPara
     const int ch = threadIdx.x % CPR;
 #pragma unroll
     for (int r = threadIdx.x / CPR; r < 128; r += NT / CPR)
-      if (m0 + r < p.M) *(u32x4*)(mv + (size_t)r * D + 8 * ch) = *(const u32x4*)(sStage + r * LD + 8 * ch);
+      if (m0 + r < p.M) __builtin_nontemporal_store(*(const u32x4*)(sStage + r * LD + 8 * ch), (u32x4*)(mv + (size_t)r * D + 8 * ch));
   }
 }
 
