@@ -365,14 +365,14 @@ __global__ __launch_bounds__(512) void prefill_read_only_kernel(const PrefillPar
   Tile<64, D, NT> tk;
   Tile<D, 64, NT> tv;
   tk.fetch_block(mk, D);
-  tv.fetch_block_once(mvt, p.M);
+  tv.fetch_block(mvt, p.M);
   for (uint32_t m0 = 0; m0 < p.M; m0 += 64) {
     __syncthreads();
     tk.put(sK, LD);
     tv.put(sVt, LP);
     if (m0 + 64 < p.M) {  // next tiles, in flight during this tile's products
       tk.fetch_block(mk + (size_t)(m0 + 64) * D, D);
-      tv.fetch_block_once(mvt + m0 + 64, p.M);
+      tv.fetch_block(mvt + m0 + 64, p.M);
     }
     __syncthreads();
     {
@@ -513,7 +513,8 @@ __global__ __launch_bounds__(512) void prefill_read_online_kernel(const PrefillP
   Tile<64, D, NT> tk;
   Tile<D, 64, NT> tv;
   tk.fetch_block(mk, D);
-  tv.fetch_block_once(mvt, p.M);
+  if (G == 1) tv.fetch_block_once(mvt, p.M);   // nobody else reads this copy of MV
+  else tv.fetch_block(mvt, p.M);
   uint32_t it = 0;
   for (uint32_t m0 = 0; m0 < p.M; m0 += 64, ++it) {
     __syncthreads();
@@ -521,7 +522,8 @@ __global__ __launch_bounds__(512) void prefill_read_online_kernel(const PrefillP
     tv.put(sVt, LP);
     if (m0 + 64 < p.M) {  // next tiles, in flight during this tile's products
       tk.fetch_block(mk + (size_t)(m0 + 64) * D, D);
-      tv.fetch_block_once(mvt + m0 + 64, p.M);
+      if (G == 1) tv.fetch_block_once(mvt + m0 + 64, p.M);
+      else tv.fetch_block(mvt + m0 + 64, p.M);
     }
     if (threadIdx.x == 0) sFlag[(it + 1) & 1] = 0u;   // last read before this tile's first barrier
     __syncthreads();
