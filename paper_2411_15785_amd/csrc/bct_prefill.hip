@@ -435,17 +435,17 @@ __global__ __launch_bounds__(512) void prefill_read_online_kernel(const PrefillP
   constexpr float kTau = 8.f;
   constexpr int kLoop = 64 * LD + D * LP + 2 * kTC * LP;  // sK, sVt, sPr, sPw
   constexpr int kTail = kTC * LA + D * LA;                // sA, sWVt
-  constexpr int kRegion = kLoop > kTail ? kLoop : kTail;
-  __shared__ __attribute__((aligned(16))) uint16_t sXr[kTC * LD];
-  __shared__ __attribute__((aligned(16))) uint16_t sXw[kTC * LD];
-  __shared__ __attribute__((aligned(16))) uint16_t sBuf[kRegion];
-  __shared__ float sScale[kTC];     // per read row: this tile's rescaling factor; at the end 1 / sum
-  __shared__ uint32_t sFlag[2];     // tile parity -> some row's shift moved in that tile
-  uint16_t* const sK = sBuf;
-  uint16_t* const sVt = sK + 64 * LD;
-  uint16_t* const sPr = sVt + D * LP;
-  uint16_t* const sPw = sPr + kTC * LP;
-  uint16_t* const sA = sBuf;
+  constexpr int kRows = 2 * kTC * LD;                     // sXr, sXw
+  constexpr int kSet = kLoop > kTail ? (kLoop > kRows ? kLoop : kRows) : (kTail > kRows ? kTail : kRows);
+  // Two sets of the loop's tiles, used in turn, so that a wavefront can be a step ahead of the others
+  // (one barrier per slot tile, see the loop).  The row tiles are only read into registers before the
+  // loop and share the second set's memory; the tiles of the tail share the first set's.
+  __shared__ __attribute__((aligned(16))) uint16_t sBuf[2][kSet];
+  __shared__ float sScale[2][kTC];  // per read row: this tile's rescaling factor; at the end ([0]) 1 / sum
+  __shared__ uint32_t sFlag[3];     // slot tile number % 3 -> some row's shift moved in that tile
+  uint16_t* const sXr = sBuf[1];
+  uint16_t* const sXw = sBuf[1] + kTC * LD;
+  uint16_t* const sA = sBuf[0];
   uint16_t* const sWVt = sA + kTC * LA;
 
   // launch order: all sequences of one KV head, then the next head (shared keys stay in L2)
@@ -473,7 +473,7 @@ __global__ __launch_bounds__(512) void prefill_read_online_kernel(const PrefillP
     });
     t.put(sXw, LD);
   }
-  if (threadIdx.x < 2) sFlag[threadIdx.x] = 0u;
+  if (threadIdx.x < 3) sFlag[threadIdx.x] = 0u;
   const uint16_t* mk = p.mk + (size_t)(p.mk_per_seq ? unit : h) * p.M * D;
   const uint16_t* mvt = p.snap + ((size_t)c * units + unit) * p.M * D;   // MV_c, transposed: [column][slot]
 
@@ -510,23 +510,43 @@ __global__ __launch_bounds__(512) void prefill_read_online_kernel(const PrefillP
       x[ks] = __builtin_bit_cast(bf16x8, v);
     }
   }
+  // One barrier per slot tile.  Tile i uses set i % 2 of the buffers:
+  //   before the barrier: the keys of tile i + 1 go to the other set (its keys were last read in the
+  //     score step of tile i - 1, which every wavefront finished before the previous barrier); scores of
+  //     tile i from this set's keys -> this set's weights (last read in the product step of tile i - 2);
+  //   after the barrier: the values of tile i + 1 go to the other set (last read in the product step
+  //     of tile i - 1, which every wavefront left before it arrived at this barrier); products of tile i.
+  // So the wavefronts drift up to a step apart, and one's exponentials overlap another's products.
   Tile<64, D, NT> tk;
   Tile<D, 64, NT> tv;
+  auto next_values = [&](uint32_t m) {
+    if (G == 1) tv.fetch_block_once(mvt + m, p.M);   // nobody else reads this copy of MV
+    else tv.fetch_block(mvt + m, p.M);
+  };
   tk.fetch_block(mk, D);
-  if (G == 1) tv.fetch_block_once(mvt, p.M);   // nobody else reads this copy of MV
-  else tv.fetch_block(mvt, p.M);
+  next_values(0);
+  __syncthreads();             // the row fragments are in registers: the second set is free
+  tk.put(sBuf[0], LD);
+  tv.put(sBuf[0] + 64 * LD, LP);
+  if (64 < p.M) {
+    tk.fetch_block(mk + (size_t)64 * D, D);
+    next_values(64);
+  }
   uint32_t it = 0;
   for (uint32_t m0 = 0; m0 < p.M; m0 += 64, ++it) {
-    __syncthreads();
-    tk.put(sK, LD);
-    tv.put(sVt, LP);
-    if (m0 + 64 < p.M) {  // next tiles, in flight during this tile's products
-      tk.fetch_block(mk + (size_t)(m0 + 64) * D, D);
-      if (G == 1) tv.fetch_block_once(mvt + m0 + 64, p.M);
-      else tv.fetch_block(mvt + m0 + 64, p.M);
+    uint16_t* const sK = sBuf[it & 1];
+    uint16_t* const sVt = sK + 64 * LD;
+    uint16_t* const sPr = sVt + D * LP;
+    uint16_t* const sPw = sPr + kTC * LP;
+    uint16_t* const sKn = sBuf[(it + 1) & 1];
+    float* const sSc = sScale[it & 1];
+    const uint32_t fl = it % 3;
+    if (m0 + 64 < p.M) {
+      tk.put(sKn, LD);
+      if (m0 + 128 < p.M) tk.fetch_block(mk + (size_t)(m0 + 128) * D, D);
     }
-    if (threadIdx.x == 0) sFlag[(it + 1) & 1] = 0u;   // last read before this tile's first barrier
-    __syncthreads();
+    if (threadIdx.x == 0) sFlag[(it + 1) % 3] = 0u;   // last read in the product step of tile i - 2
+    if (it == 0) __syncthreads();                     // the first tile's keys were staged just above
     {
       f32x16 s0 = zero16(), s1 = zero16();
 #pragma unroll
@@ -544,9 +564,9 @@ __global__ __launch_bounds__(512) void prefill_read_online_kernel(const PrefillP
           f = fast_exp2(shift - tm);
           shift = tm;
           zsum *= f;
-          sFlag[it & 1] = 1u;
+          sFlag[fl] = 1u;
         }
-        if (half == 0) sScale[srow] = f;
+        if (half == 0) sSc[srow] = f;
         float add = 0.f;
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
@@ -576,16 +596,20 @@ __global__ __launch_bounds__(512) void prefill_read_online_kernel(const PrefillP
       }
     }
     __syncthreads();
-    if (sFlag[it & 1]) {   // uniform over the workgroup: bring what has been accumulated to the new shifts
+    if (m0 + 64 < p.M) {
+      tv.put(sKn + 64 * LD, LP);
+      if (m0 + 128 < p.M) next_values(m0 + 128);
+    }
+    if (sFlag[fl]) {   // uniform over the workgroup: bring what has been accumulated to the new shifts
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const float fr = sScale[orow + 8 * (v / 4) + 4 * half + (v % 4)];
+        const float fr = sSc[orow + 8 * (v / 4) + 4 * half + (v % 4)];
 #pragma unroll
         for (int jt = 0; jt < NOC; ++jt) oacc[jt][v] *= fr;
       }
 #pragma unroll
       for (int jt = 0; jt < 2; ++jt) {
-        const float fc = sScale[ar0 + 32 * jt + col];
+        const float fc = sSc[ar0 + 32 * jt + col];
 #pragma unroll
         for (int v = 0; v < 16; ++v) aacc[jt][v] *= fc;
       }
@@ -607,7 +631,7 @@ __global__ __launch_bounds__(512) void prefill_read_online_kernel(const PrefillP
   // 1 / (sum of the row's weights): the normaliser of everything accumulated for the row
   if (role == 0) {
     const float z = zsum + __shfl_xor(zsum, 32, 64);
-    if (half == 0) sScale[srow] = 1.0f / z;
+    if (half == 0) sScale[0][srow] = 1.0f / z;
   }
   // A[row][s] = (s <= token of the row) ? sum_m e[row][m] ww[s][m] : 0
 #pragma unroll
@@ -642,7 +666,7 @@ __global__ __launch_bounds__(512) void prefill_read_online_kernel(const PrefillP
     const uint32_t r = orow + 8 * (v / 4) + 4 * half + (v % 4);
     const uint32_t rho = rho0 + r, t = t0 + rho / G;
     if (t < T) {
-      const float inv = sScale[r];
+      const float inv = sScale[0][r];
       uint16_t* o = p.out + (((size_t)b * T + t) * p.Hq + h * G + rho % G) * D;
 #pragma unroll
       for (int jt = 0; jt < NOC; ++jt) o[ocol + 32 * jt + col] = bf16_bits(oacc[jt][v] * inv);
