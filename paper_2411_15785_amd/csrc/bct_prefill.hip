@@ -698,12 +698,14 @@ __global__ __launch_bounds__(256, 2) void prefill_state_kernel(const PrefillPara
   constexpr int LP = TT + 8;    // row length of the WV^T tile
   constexpr int NJ = D / 32;    // 32-column tiles of the state product
   constexpr int LS = 128 + 8;   // row length of the snapshot staging tile [column][slot]
-  static_assert(TT * LD + D * LP >= D * LS && TT * LD + D * LP >= 128 * LD, "the staging tiles reuse the token tiles");
+  static_assert(TT * LD + D * LP >= 128 * LD, "the MV staging tile reuses the token tiles");
   __shared__ __attribute__((aligned(16))) uint16_t sTok[TT * LD + D * LP];
+  // the snapshot has LDS of its own: it leaves after the token tile of the step has been staged (see the loop)
+  __shared__ __attribute__((aligned(16))) uint16_t sSnapBuf[D * LS];
   __shared__ __attribute__((aligned(16))) float sNorm[TT];
   uint16_t* const sXw = sTok;
   uint16_t* const sWVt = sTok + TT * LD;
-  uint16_t* const sSnap = sTok;    // [column][slot] snapshot on its way out
+  uint16_t* const sSnap = sSnapBuf;   // [column][slot] snapshot on its way out
   uint16_t* const sStage = sTok;   // [slot][column] MV tile on its way in and out
 
   const uint32_t unit = block_unit();
@@ -756,13 +758,21 @@ __global__ __launch_bounds__(256, 2) void prefill_state_kernel(const PrefillPara
   fetch_tokens(0);
   for (uint32_t tt = 0; tt < ntile; ++tt) {
     const uint32_t t0 = tt * TT;
+    // The token tile is staged first and the next one requested, and only then does a snapshot leave:
+    // loads and stores share one counter, so a wait for loads that follows stores waits for the
+    // stores as well - this way the snapshot's stores have the whole step to complete before the next
+    // wait (for the next token tile) comes.
+    __syncthreads();
+    tx.put(sXw, LD);
+    tw.put(sWVt, LP);
+    if (threadIdx.x < TT) sNorm[threadIdx.x] = (t0 + threadIdx.x < T) ? tn : kNoRow;
+    if (tt + 1 < ntile) fetch_tokens(t0 + TT);  // next tile, in flight during this one's products
     if (p.has_read && (t0 % kTC) == 0) {
       // MV at the start of sub-chunk c (c = 0: the tile just loaded, which saves a transposing pass over
       // MV of its own), transposed ([column][slot]) for the read kernel.  A lane holds
       // 4 consecutive slots of one column, and columns are M elements apart in memory, so the tile
-      // goes through LDS (in place of the token tiles, which nobody reads any more) and leaves in
-      // whole 256-byte rows.
-      __syncthreads();
+      // goes through LDS and leaves in whole 256-byte rows.  (The previous snapshot left this buffer
+      // two steps and several barriers ago.)
       if (live) {
 #pragma unroll
         for (int jt = 0; jt < NJ; ++jt)
@@ -780,11 +790,6 @@ __global__ __launch_bounds__(256, 2) void prefill_state_kernel(const PrefillPara
           __builtin_nontemporal_store(*(const u32x4*)(sSnap + r * LS + 8 * ch), (u32x4*)(sn + (size_t)r * p.M + 8 * ch));
       }
     }
-    __syncthreads();
-    tx.put(sXw, LD);
-    tw.put(sWVt, LP);
-    if (threadIdx.x < TT) sNorm[threadIdx.x] = (t0 + threadIdx.x < T) ? tn : kNoRow;
-    if (tt + 1 < ntile) fetch_tokens(t0 + TT);  // next tile, in flight during this one's products
     __syncthreads();
 #pragma unroll
     for (int st = 0; st < TT / 32; ++st) {
